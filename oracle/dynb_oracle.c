@@ -1,0 +1,397 @@
+/*
+ * CPU oracle for dynamic batching of per-example dynamic architectures.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, one-thing-at-a-time C that states what the
+ * batched GPU path must compute.  It shares no code, headers, tables or helpers with the
+ * HIP library and is only ever called from tests, the smoke check and the benchmark's
+ * CPU-baseline leg.
+ *
+ * Paper: "Effective Approaches to Batch Parallelization for Dynamic Neural Network
+ * Architectures" (Suarez & Zhu).
+ *   - Background / Visual Reasoning Programs: a program is a sequence of function ids whose
+ *     fixed arities give a unique tree, assembled depth first; a SCENE token outputs the
+ *     example's image features; every other function is a neural network.
+ *   - Methods / Improved topological sort: label every node by its distance from the root,
+ *     pool nodes with the same label, run each pool with at most p network calls.
+ *   - Methods / Standard topological sort: flatten each program into a dependency-respecting
+ *     queue, view the batch as a b x s grid and run it column by column, at most p calls each.
+ *   - Results / IEP: the unbatched original loops over examples and runs one module at a
+ *     time; the batched version builds the same network, so outputs must agree.
+ *   - Results / Sparsely Gated Mixture of Experts: n experts, k active per example; the
+ *     naive version runs the k*b expert uses one by one.
+ * The module (residual conv block), the noisy top-k gate and all sizes are fixed by the
+ * benchmark configurations, not by the paper.
+ *
+ * All floating point here is fp64 (inputs arrive as fp32 arrays and are widened).
+ * Float parity of every function below is pinned by tests against library routines,
+ * closed forms and brute force; none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_E_MALFORMED (-2)
+#define ORC_E_INVAL (-1)
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Plan oracle (integers).
+ * ---------------------------------------------------------------------------------------- */
+
+typedef struct {
+    const int32_t* prog;    /* this example's tokens */
+    int32_t len;
+    int32_t base;           /* node id of token 0 = prog_off[example] */
+    const uint8_t* arity;
+    int32_t n_types;
+    int32_t* level;         /* indexed by global node id */
+    int32_t* child0;
+    int32_t* child1;
+    int32_t* post;          /* post[j] = global node id of the j-th node in the post-order queue */
+    int32_t n_post;
+    int bad;
+} tree_ctx;
+
+/* Depth-first assembly (Background / Visual Reasoning Programs): the children of the token at
+ * `pos` are the sub-programs that follow it, one per argument.  Root distance is recorded on
+ * the way down (Methods / Improved topological sort), the dependency-respecting queue on the
+ * way up (Methods / Standard topological sort: a node enters the queue after its arguments). */
+static int32_t build(tree_ctx* c, int32_t pos, int32_t lvl)
+{
+    if (pos >= c->len) { c->bad = 1; return pos; }
+    int32_t t = c->prog[pos];
+    if (t < 0 || t >= c->n_types || c->arity[t] > 2) { c->bad = 1; return c->len + 1; }
+    int32_t id = c->base + pos;
+    c->level[id] = lvl;
+    c->child0[id] = -1;
+    c->child1[id] = -1;
+    int32_t next = pos + 1;
+    for (int a = 0; a < c->arity[t]; ++a) {
+        if (next >= c->len) { c->bad = 1; return next; }
+        if (a == 0) c->child0[id] = c->base + next; else c->child1[id] = c->base + next;
+        next = build(c, next, lvl + 1);
+        if (c->bad) return next;
+    }
+    c->post[c->n_post++] = id;
+    return next;
+}
+
+/* mode 0: label = distance from the root, pools run deepest label first (improved sort).
+ * mode 1: label = position in the example's post-order queue, pools (grid columns) run in
+ *         ascending order (standard sort).
+ * Within a label, one pool per function id, ascending; members ascending by node id.
+ * Returns ORC_OK, or ORC_E_MALFORMED with *bad_example set.
+ * Caller provides: level/type/child0/child1/members/in0/in1/out [N], root [B],
+ * bucket_* [N] (worst case one bucket per node).                                            */
+int oracle_plan(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
+                int32_t n_types, int32_t mode,
+                int32_t* level, int32_t* type, int32_t* child0, int32_t* child1, int32_t* root,
+                int32_t* n_levels, int32_t* n_buckets, int32_t* bucket_level, int32_t* bucket_type,
+                int32_t* bucket_start, int32_t* bucket_count, int32_t* members, int32_t* in0,
+                int32_t* in1, int32_t* out, int32_t* bad_example)
+{
+    if (!prog || !prog_off || B <= 0 || !arity || n_types <= 0) return ORC_E_INVAL;
+    int32_t N = prog_off[B];
+    int32_t* rootdist = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    int32_t* post = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    int32_t D = 0;
+    for (int32_t i = 0; i < B; ++i) {
+        tree_ctx c;
+        c.prog = prog + prog_off[i];
+        c.len = prog_off[i + 1] - prog_off[i];
+        c.base = prog_off[i];
+        c.arity = arity;
+        c.n_types = n_types;
+        c.level = rootdist;
+        c.child0 = child0;
+        c.child1 = child1;
+        c.post = post + prog_off[i];
+        c.n_post = 0;
+        c.bad = 0;
+        int32_t end = (c.len > 0) ? build(&c, 0, 0) : -1;
+        if (c.bad || end != c.len) {          /* ends early, or tokens left over */
+            if (bad_example) *bad_example = i;
+            free(rootdist); free(post);
+            return ORC_E_MALFORMED;
+        }
+        root[i] = c.base;
+        for (int32_t j = 0; j < c.len; ++j) {
+            int32_t id = c.base + j;
+            type[id] = c.prog[j];
+            if (mode == 0) level[id] = rootdist[id];
+        }
+        if (mode == 1)
+            for (int32_t j = 0; j < c.n_post; ++j) level[post[prog_off[i] + j]] = j;
+        for (int32_t j = 0; j < c.len; ++j)
+            if (level[c.base + j] + 1 > D) D = level[c.base + j] + 1;   /* max over the minibatch */
+    }
+    *n_levels = D;
+
+    int32_t nb = 0, filled = 0;
+    for (int32_t step = 0; step < D; ++step) {
+        int32_t lvl = (mode == 0) ? D - 1 - step : step;
+        for (int32_t t = 0; t < n_types; ++t) {
+            int32_t start = filled;
+            for (int32_t id = 0; id < N; ++id)
+                if (level[id] == lvl && type[id] == t) {
+                    members[filled] = id;
+                    in0[filled] = child0[id];
+                    in1[filled] = child1[id];
+                    out[filled] = id;
+                    ++filled;
+                }
+            if (filled > start) {
+                bucket_level[nb] = lvl;
+                bucket_type[nb] = t;
+                bucket_start[nb] = start;
+                bucket_count[nb] = filled - start;
+                ++nb;
+            }
+        }
+    }
+    *n_buckets = nb;
+    free(rootdist); free(post);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * IEP float oracle: one example at a time, one module at a time, by tree recursion.
+ * Feature maps are [H][W][C] (channels innermost); conv weights [Cout][kh][kw][Cin].
+ * ---------------------------------------------------------------------------------------- */
+
+typedef struct {
+    int C, H, W;
+    int n_types;
+    const uint8_t* arity;
+    const float *w1, *b1, *w3a, *b3a, *w3b, *b3b;   /* [n_types, ...], biases may be NULL */
+} modules;
+
+/* cross-correlation, zero padding 1, stride 1 */
+static void conv3x3(const double* in, const float* w, const float* b, double* out, int C, int H, int W)
+{
+    for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x)
+            for (int co = 0; co < C; ++co) {
+                double acc = b ? (double)b[co] : 0.0;
+                for (int kh = 0; kh < 3; ++kh) {
+                    int iy = y + kh - 1;
+                    if (iy < 0 || iy >= H) continue;
+                    for (int kw = 0; kw < 3; ++kw) {
+                        int ix = x + kw - 1;
+                        if (ix < 0 || ix >= W) continue;
+                        const double* px = in + ((size_t)iy * W + ix) * C;
+                        const float* wk = w + (((size_t)co * 3 + kh) * 3 + kw) * C;
+                        for (int ci = 0; ci < C; ++ci) acc += px[ci] * (double)wk[ci];
+                    }
+                }
+                out[((size_t)y * W + x) * C + co] = acc;
+            }
+}
+
+static void relu_inplace(double* a, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) if (!(a[i] > 0.0)) a[i] = 0.0;
+}
+
+/* Res_t(u) = ReLU(u + conv3x3_b(ReLU(conv3x3_a(u) + b_a)) + b_b) */
+static void residual_block(const modules* m, int t, const double* u, double* y)
+{
+    size_t n = (size_t)m->H * m->W * m->C;
+    size_t w3 = (size_t)m->C * 9 * m->C;
+    double* mid = (double*)malloc(n * sizeof(double));
+    conv3x3(u, m->w3a + t * w3, m->b3a ? m->b3a + (size_t)t * m->C : NULL, mid, m->C, m->H, m->W);
+    relu_inplace(mid, n);
+    conv3x3(mid, m->w3b + t * w3, m->b3b ? m->b3b + (size_t)t * m->C : NULL, y, m->C, m->H, m->W);
+    for (size_t i = 0; i < n; ++i) y[i] += u[i];
+    relu_inplace(y, n);
+    free(mid);
+}
+
+/* u = ReLU(conv1x1_{2C->C}(concat_C(a, b)) + b1): first argument feeds input channels [0,C) */
+static void join1x1(const modules* m, int t, const double* a, const double* b, double* u)
+{
+    int C = m->C;
+    const float* w = m->w1 + (size_t)t * C * 2 * C;
+    for (size_t p = 0; p < (size_t)m->H * m->W; ++p)
+        for (int co = 0; co < C; ++co) {
+            double acc = m->b1 ? (double)m->b1[(size_t)t * C + co] : 0.0;
+            for (int ci = 0; ci < C; ++ci) acc += a[p * C + ci] * (double)w[(size_t)co * 2 * C + ci];
+            for (int ci = 0; ci < C; ++ci) acc += b[p * C + ci] * (double)w[(size_t)co * 2 * C + C + ci];
+            u[p * C + co] = acc > 0.0 ? acc : 0.0;
+        }
+}
+
+/* Evaluates the sub-program starting at *pos and advances *pos past it. Returns a malloc'd map. */
+static double* eval_node(const modules* m, const int32_t* prog, int32_t* pos, const float* feat)
+{
+    size_t n = (size_t)m->H * m->W * m->C;
+    int t = prog[(*pos)++];
+    double* y = (double*)malloc(n * sizeof(double));
+    if (m->arity[t] == 0) {                     /* SCENE: the example's image features */
+        for (size_t i = 0; i < n; ++i) y[i] = (double)feat[i];
+    } else if (m->arity[t] == 1) {
+        double* u = eval_node(m, prog, pos, feat);
+        residual_block(m, t, u, y);
+        free(u);
+    } else {
+        double* a = eval_node(m, prog, pos, feat);
+        double* b = eval_node(m, prog, pos, feat);
+        double* u = (double*)malloc(n * sizeof(double));
+        join1x1(m, t, a, b, u);
+        residual_block(m, t, u, y);
+        free(a); free(b); free(u);
+    }
+    return y;
+}
+
+/* Programs must be well formed (check with oracle_plan first). out: double [B,H,W,C]. */
+int oracle_iep_forward(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
+                       int32_t n_types, int32_t C, int32_t H, int32_t W, const float* feats,
+                       const float* w1, const float* b1, const float* w3a, const float* b3a,
+                       const float* w3b, const float* b3b, double* out)
+{
+    if (!prog || !prog_off || B <= 0 || !feats || !out || !w3a || !w3b) return ORC_E_INVAL;
+    modules m = { C, H, W, n_types, arity, w1, b1, w3a, b3a, w3b, b3b };
+    size_t n = (size_t)H * W * C;
+    /* examples are independent: the only parallelism is across them */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < B; ++i) {
+        int32_t pos = 0;
+        double* y = eval_node(&m, prog + prog_off[i], &pos, feats + (size_t)i * n);
+        memcpy(out + (size_t)i * n, y, n * sizeof(double));
+        free(y);
+    }
+    return ORC_OK;
+}
+
+/* single convolution entry points, exported so tests can pin them against library routines */
+void oracle_conv3x3(const float* in, const float* w, const float* b, double* out, int C, int H, int W)
+{
+    size_t n = (size_t)H * W * C;
+    double* d = (double*)malloc(n * sizeof(double));
+    for (size_t i = 0; i < n; ++i) d[i] = (double)in[i];
+    conv3x3(d, w, b, out, C, H, W);
+    free(d);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Mixture-of-experts oracle: token by token.
+ * ---------------------------------------------------------------------------------------- */
+
+static double softplus(double z) { return (z > 0.0 ? z : 0.0) + log1p(exp(-fabs(z))); }
+
+/* logit[t,e] = x_t . Wg[:,e] + noise[t,e] * softplus(x_t . Wn[:,e]);  Wg, Wn are [d,E]. */
+void oracle_moe_logits(const float* x, const float* Wg, const float* Wn, const float* noise,
+                       int32_t T, int32_t d, int32_t E, double* logits)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t e = 0; e < E; ++e) {
+            double g = 0.0, s = 0.0;
+            for (int32_t c = 0; c < d; ++c) {
+                g += (double)x[(size_t)t * d + c] * (double)Wg[(size_t)c * E + e];
+                if (noise) s += (double)x[(size_t)t * d + c] * (double)Wn[(size_t)c * E + e];
+            }
+            logits[(size_t)t * E + e] = noise ? g + (double)noise[(size_t)t * E + e] * softplus(s) : g;
+        }
+}
+
+/* Routing from fp32 logits (decisions are taken on the fp32 values, so they are exact):
+ * k largest per token, equal logits -> lower expert id first; softmax over the k kept logits;
+ * then the grouping of the k*T known expert uses by expert, stable in the flat use id a = t*k+j:
+ * counts[E], offsets[E+1], perm[A] (sorted position -> use id), inv[A] (use id -> position).     */
+int oracle_moe_route(const float* logits, int32_t T, int32_t E, int32_t k, int32_t* topk_idx,
+                     double* topk_w, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv)
+{
+    if (k <= 0 || k > E) return ORC_E_INVAL;
+    for (int32_t t = 0; t < T; ++t) {
+        const float* row = logits + (size_t)t * E;
+        for (int32_t j = 0; j < k; ++j) {
+            int32_t best = -1;
+            for (int32_t e = 0; e < E; ++e) {
+                int taken = 0;
+                for (int32_t q = 0; q < j; ++q) if (topk_idx[(size_t)t * k + q] == e) taken = 1;
+                if (taken) continue;
+                if (best < 0 || row[e] > row[best]) best = e;     /* strict >: lower id wins ties */
+            }
+            topk_idx[(size_t)t * k + j] = best;
+        }
+        double mx = (double)row[topk_idx[(size_t)t * k]];
+        double den = 0.0;
+        for (int32_t j = 0; j < k; ++j) den += exp((double)row[topk_idx[(size_t)t * k + j]] - mx);
+        for (int32_t j = 0; j < k; ++j)
+            topk_w[(size_t)t * k + j] = exp((double)row[topk_idx[(size_t)t * k + j]] - mx) / den;
+    }
+    int32_t A = T * k, pos = 0;
+    for (int32_t e = 0; e < E; ++e) {
+        offsets[e] = pos;
+        for (int32_t a = 0; a < A; ++a)
+            if (topk_idx[a] == e) { perm[pos] = a; inv[a] = pos; ++pos; }
+        counts[e] = pos - offsets[e];
+    }
+    offsets[E] = pos;
+    return ORC_OK;
+}
+
+/* One token through its k experts: out = sum_j w[j] * W2_j . ReLU(W1_j . x)  (no biases: the
+ * paper counts 2*h*n*d parameters).  W1_j is [h,d], W2_j is [d,h] (one output unit per row). */
+void oracle_moe_token(const float* x, int32_t d, int32_t h, int32_t k, const double* w,
+                      const float* const* W1, const float* const* W2, double* out)
+{
+    double* hid = (double*)malloc(sizeof(double) * (size_t)h);
+    for (int32_t c = 0; c < d; ++c) out[c] = 0.0;
+    for (int32_t j = 0; j < k; ++j) {
+        for (int32_t u = 0; u < h; ++u) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < d; ++c) acc += (double)W1[j][(size_t)u * d + c] * (double)x[c];
+            hid[u] = acc > 0.0 ? acc : 0.0;
+        }
+        for (int32_t c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int32_t u = 0; u < h; ++u) acc += (double)W2[j][(size_t)c * h + u] * hid[u];
+            out[c] += w[j] * acc;
+        }
+    }
+    free(hid);
+}
+
+/* All tokens, experts stored contiguously: W1 [E,h,d], W2 [E,d,h]. out: double [T,d]. */
+void oracle_moe_experts(const float* x, const int32_t* topk_idx, const double* topk_w,
+                        const float* W1, const float* W2, int32_t T, int32_t d, int32_t h,
+                        int32_t k, double* out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int32_t t = 0; t < T; ++t) {
+        const float* p1[64];
+        const float* p2[64];
+        for (int32_t j = 0; j < k && j < 64; ++j) {
+            int32_t e = topk_idx[(size_t)t * k + j];
+            p1[j] = W1 + (size_t)e * h * d;
+            p2[j] = W2 + (size_t)e * d * h;
+        }
+        oracle_moe_token(x + (size_t)t * d, d, h, k, topk_w + (size_t)t * k, p1, p2, out + (size_t)t * d);
+    }
+}
