@@ -1,0 +1,219 @@
+/*
+ * dynbatch — dynamic batching of per-example dynamic architectures on one AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Two paths, both from "Effective Approaches to Batch Parallelization for
+ * Dynamic Neural Network Architectures" (Suarez & Zhu):
+ *
+ *   1. Program-tree execution engine (Background / Visual Reasoning Programs; Methods):
+ *      dynbatch_plan()    host  — prefix programs + arities -> trees -> labels -> pools with
+ *                                 gather/scatter index lists
+ *      dynbatch_execute() GPU   — runs the pools: gather the arguments, one batched residual
+ *                                 conv module per pool, scatter the results; root maps come back
+ *   2. Sparsely gated mixture of experts (Results / Sparsely Gated Mixture of Experts):
+ *      moe_forward()      GPU   — noisy top-k gate, grouping of the k*b known expert uses by
+ *                                 expert, one grouped FFN per expert, weighted combine
+ *
+ * Conventions
+ *   - Every function returns DYNB_OK (0) or a negative DYNB_E_* code; dynb_last_error() gives a
+ *     thread-local, library-owned message for the last failure on the calling thread.
+ *   - "host" / "device" in a parameter comment says where the memory must live.  All pointers are
+ *     borrowed: the library never frees or keeps caller memory beyond what is stated, and never
+ *     allocates device memory — the caller brings workspaces.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU entry points
+ *     only enqueue work on it; they do not synchronise.
+ *   - Feature maps are [H][W][C] (channels innermost).  Conv weights are [Cout][kh][kw][Cin].
+ *   - DYNB_BF16 tensors hold bfloat16 bit patterns (uint16_t); accumulation is always fp32.
+ */
+#ifndef DYNBATCH_H
+#define DYNBATCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    DYNB_OK = 0,
+    DYNB_E_INVAL = -1,        /* NULL pointer, non-positive size, k > E, ...                    */
+    DYNB_E_MALFORMED = -2,    /* a program is not a complete prefix tree                        */
+    DYNB_E_NOMEM = -3,        /* host allocation failed                                         */
+    DYNB_E_WORKSPACE = -4,    /* a caller-provided buffer is too small / plan not uploaded      */
+    DYNB_E_UNSUPPORTED = -5,  /* arity > 2, unknown dtype or flag, shape beyond kernel limits   */
+    DYNB_E_HIP = -6           /* a HIP runtime call failed                                      */
+};
+
+enum { DYNB_F32 = 0, DYNB_BF16 = 1 };
+
+/* Scheduling modes for dynbatch_plan (flags & DYNB_SCHED_MASK). */
+enum {
+    /* Methods / "Improved topological sort": label = distance from the root, equal labels are
+     * pooled over the whole minibatch and pools run deepest label first.                        */
+    DYNB_SCHED_IMPROVED = 0,
+    /* Methods / "Standard topological sort": each program is flattened into a queue that lists
+     * every node after its arguments; the minibatch is a b x s grid run column by column.      */
+    DYNB_SCHED_STANDARD = 1,
+    /* Results / IEP, the unbatched original: an explicit loop over examples, one module per
+     * call.  Same kernels, one launch per node; the comparison row for the speed-up.           */
+    DYNB_SCHED_NAIVE = 2,
+    DYNB_SCHED_MASK = 3
+};
+
+const char* dynb_last_error(void);
+
+/* ------------------------------------------------------------------------------------------- */
+/* Planner (host only; no GPU needed)                                                           */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct dynb_plan dynb_plan;
+
+/* Logical plan, independent of how the executor lays out memory.  Node id = prog_off[example] +
+ * position in that example's prefix sequence.  Pools ("buckets") are listed in execution order:
+ * IMPROVED — label descending, then function id ascending; STANDARD — column ascending, then
+ * function id ascending; NAIVE — one bucket per node, example by example in queue order.
+ * Members of a bucket are ascending node ids.  in0/in1 are the node ids of the members'
+ * arguments (-1 if absent), out is the member itself.  SCENE buckets (arity 0) are listed but
+ * cost no network call.  All arrays are owned by the plan and valid until dynbatch_plan_free. */
+typedef struct {
+    int32_t n_examples;
+    int32_t n_nodes;
+    int32_t n_levels;         /* number of distinct labels = 1 + max label over the minibatch   */
+    int32_t n_buckets;
+    int32_t n_compute_nodes;  /* nodes with arity > 0 = module evaluations                      */
+    int32_t n_launches;       /* kernel launch groups dynbatch_execute will issue               */
+    int32_t max_launch_nodes; /* largest number of compute nodes in one launch group            */
+    int32_t n_slots;          /* feature-map slots the executor needs in its workspace          */
+    const int32_t* node_level;   /* [n_nodes] label                                             */
+    const int32_t* node_type;    /* [n_nodes]                                                   */
+    const int32_t* child0;       /* [n_nodes] first argument or -1                              */
+    const int32_t* child1;       /* [n_nodes] second argument or -1                             */
+    const int32_t* root;         /* [n_examples]                                                */
+    const int32_t* bucket_level; /* [n_buckets]                                                 */
+    const int32_t* bucket_type;  /* [n_buckets]                                                 */
+    const int32_t* bucket_start; /* [n_buckets] offset into members/in0/in1/out                 */
+    const int32_t* bucket_count; /* [n_buckets]                                                 */
+    const int32_t* members;      /* [n_nodes]                                                   */
+    const int32_t* in0;          /* [n_nodes]                                                   */
+    const int32_t* in1;          /* [n_nodes]                                                   */
+    const int32_t* out;          /* [n_nodes]                                                   */
+} dynb_plan_view;
+
+/* Builds the plan for a minibatch of programs (Background / Visual Reasoning Programs: the fixed
+ * arities make the tree unique, it is assembled depth first; Methods: labelling and pooling).
+ *   prog      host  concatenated prefix sequences of function ids
+ *   prog_off  host  [B+1], prog_off[0] = 0, example i owns prog[prog_off[i] .. prog_off[i+1])
+ *   arity     host  [n_types] values 0, 1 or 2; any id with arity 0 is a SCENE-like leaf that
+ *                   outputs the example's feature map
+ *   flags     one DYNB_SCHED_* value
+ *   out       receives a library-owned plan; release with dynbatch_plan_free
+ * Errors: DYNB_E_INVAL (NULL, B <= 0, n_types <= 0, offsets not increasing from 0),
+ * DYNB_E_UNSUPPORTED (arity > 2, unknown flag), DYNB_E_MALFORMED (function id out of range, a
+ * sequence that ends before its tree is complete or has tokens left over, an empty sequence;
+ * the message names the first offending example), DYNB_E_NOMEM.  On error *out is NULL.         */
+int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
+                  int32_t n_types, uint32_t flags, dynb_plan** out);
+
+int dynbatch_plan_view(const dynb_plan* plan, dynb_plan_view* view);
+
+void dynbatch_plan_free(dynb_plan* plan);
+
+/* Bytes of device memory the plan's index lists need. */
+size_t dynbatch_plan_device_bytes(const dynb_plan* plan);
+
+/* Copies the index lists to `dev_buf` (device, >= dynbatch_plan_device_bytes, 16-byte aligned)
+ * on `stream`, once per plan.  The plan remembers dev_buf; it must stay valid and unmodified
+ * while the plan is executed.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small), DYNB_E_HIP.  */
+int dynbatch_plan_upload(dynb_plan* plan, void* dev_buf, size_t bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------- */
+/* Executor                                                                                      */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t C, H, W;
+    int32_t dtype;            /* DYNB_F32 or DYNB_BF16: element type of feats, out, workspace
+                                 slots and conv weights                                         */
+} dynb_shape;
+
+/* Per-function parameters, one block per function id (blocks of SCENE ids are never read).
+ * Unary function t:  y = ReLU(u + conv3x3_b(ReLU(conv3x3_a(u) + b3a)) + b3b),  u = its argument.
+ * Binary function t: same with u = ReLU(conv1x1(concat_C(arg0, arg1)) + b1); the first argument
+ * feeds input channels [0,C).  Convolutions are cross-correlations, stride 1, zero padding 1.   */
+typedef struct {
+    const void* w1;           /* device [n_types][C][2C]        dtype; may be NULL if no binary  */
+    const float* b1;          /* device [n_types][C]            fp32;  NULL = no bias            */
+    const void* w3a;          /* device [n_types][C][3][3][C]   dtype                            */
+    const float* b3a;         /* device [n_types][C]            fp32;  NULL = no bias            */
+    const void* w3b;          /* device [n_types][C][3][3][C]   dtype                            */
+    const float* b3b;         /* device [n_types][C]            fp32;  NULL = no bias            */
+} dynb_module_weights;
+
+/* Bytes of device workspace dynbatch_execute needs for this plan and shape (0 on bad input).   */
+size_t dynbatch_workspace_bytes(const dynb_plan* plan, const dynb_shape* shape);
+
+/* Executes the plan (Methods: each pool is run at once, one batched network call per function;
+ * Results / IEP: the "data stacking" that builds a pool's batch and returns its results is part
+ * of this call).  One launch group per label; inside it every workgroup looks up its node's
+ * function and parameter block.
+ *   feats      device [B][H][W][C]  the SCENE output of each example
+ *   out        device [B][H][W][C]  receives each example's root map
+ *   workspace  device, >= dynbatch_workspace_bytes, 256-byte aligned; contents are scratch
+ * The fast path (bf16, C = 128, 14 x 14) runs fused MFMA kernels; every other shape runs generic
+ * kernels with the same semantics.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (workspace too small
+ * or plan not uploaded), DYNB_E_UNSUPPORTED (dtype; w1 NULL with binary functions), DYNB_E_HIP. */
+int dynbatch_execute(const dynb_plan* plan, const dynb_shape* shape, const dynb_module_weights* w,
+                     const void* feats, void* out, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* ------------------------------------------------------------------------------------------- */
+/* Mixture of experts                                                                            */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t T;                /* tokens (the paper's b)                                         */
+    int32_t d;                /* model width                                                    */
+    int32_t h;                /* hidden units per expert                                        */
+    int32_t E;                /* experts (the paper's n)                                        */
+    int32_t k;                /* experts per token, 1 <= k <= min(E, 8)                         */
+    int32_t dtype;            /* DYNB_BF16 only                                                 */
+} moe_shape;
+
+/* Optional outputs of the routing stages; any pointer may be NULL.  All device memory.          */
+typedef struct {
+    float* logits;            /* [T][E]                                                         */
+    int32_t* topk_idx;        /* [T][k]  descending logit, equal logits -> lower expert first   */
+    float* topk_w;            /* [T][k]  softmax over the k kept logits                         */
+    int32_t* counts;          /* [E]                                                            */
+    int32_t* offsets;         /* [E+1]   exclusive prefix sum of counts                         */
+    int32_t* perm;            /* [T*k]   sorted position -> flat use id a = t*k + j             */
+    int32_t* inv;             /* [T*k]   flat use id -> sorted position                         */
+} moe_aux;
+
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* One sparsely gated MoE layer (Results / Sparsely Gated Mixture of Experts: the k*b known expert
+ * uses are grouped so that only n expert calls are made; experts are one-hidden-layer networks
+ * without biases, 2*h*n*d parameters in all).
+ *   logit[t][e] = x_t . Wg[e] + noise[t][e] * softplus(x_t . Wn[e])
+ *   keep the k largest logits per token, softmax over them
+ *   group the uses by expert with a stable counting sort (order inside a group = ascending t*k+j)
+ *   y = ReLU(xs . W1_e^T) . W2_e^T for each group; out_t = sum_j w[t][j] * y[use (t,j)]
+ *   x      device [T][d]      bf16
+ *   Wg,Wn  device [E][d]      bf16   (row e is expert e's gate vector; Wn may be NULL iff noise is)
+ *   noise  device [T][E]      fp32 or NULL (noiseless gate)
+ *   W1     device [E][h][d]   bf16   (row j of W1_e produces hidden unit j)
+ *   W2     device [E][d][h]   bf16   (row c of W2_e produces output channel c)
+ *   out    device [T][d]      bf16
+ *   aux    host struct of device pointers, or NULL
+ *   workspace device, >= moe_workspace_bytes, 256-byte aligned
+ * T = 0 succeeds without work.  Errors: DYNB_E_INVAL (NULL, k > E, k > 8, sizes <= 0, d or h not
+ * a multiple of 32), DYNB_E_WORKSPACE, DYNB_E_UNSUPPORTED (dtype), DYNB_E_HIP.                   */
+int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const void* Wn,
+                const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNBATCH_H */

@@ -1,0 +1,247 @@
+"""ctypes binding of libdynbatch.so: same names as the C ABI, argument marshalling only.
+
+PyTorch tensors provide device memory and the current HIP stream; every step of the two hot
+paths runs inside the library's kernels.  There is no fallback: if the library has not been
+built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+from types import SimpleNamespace
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdynbatch.so")
+
+DYNB_F32, DYNB_BF16 = 0, 1
+DYNB_SCHED_IMPROVED, DYNB_SCHED_STANDARD, DYNB_SCHED_NAIVE = 0, 1, 2
+ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
+          -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}
+
+EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_view", "dynbatch_plan_free",
+           "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
+           "dynbatch_execute", "moe_workspace_bytes", "moe_forward"]
+
+
+class DynbError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{ERRORS.get(code, code)}: {msg}")
+        self.code = code
+        self.name = ERRORS.get(code, str(code))
+
+
+I32P = ct.POINTER(ct.c_int32)
+
+
+class _PlanView(ct.Structure):
+    _fields_ = [(n, ct.c_int32) for n in ("n_examples", "n_nodes", "n_levels", "n_buckets", "n_compute_nodes",
+                                          "n_launches", "max_launch_nodes", "n_slots")] + \
+               [(n, I32P) for n in ("node_level", "node_type", "child0", "child1", "root", "bucket_level",
+                                    "bucket_type", "bucket_start", "bucket_count", "members", "in0", "in1", "out")]
+
+
+class _Shape(ct.Structure):
+    _fields_ = [("C", ct.c_int32), ("H", ct.c_int32), ("W", ct.c_int32), ("dtype", ct.c_int32)]
+
+
+class _Weights(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("w1", "b1", "w3a", "b3a", "w3b", "b3b")]
+
+
+class _MoeShape(ct.Structure):
+    _fields_ = [(n, ct.c_int32) for n in ("T", "d", "h", "E", "k", "dtype")]
+
+
+class _MoeAux(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = ct.CDLL(LIB_PATH)
+    L.dynb_last_error.restype = ct.c_char_p
+    L.dynbatch_plan.argtypes = [I32P, I32P, ct.c_int32, ct.POINTER(ct.c_uint8), ct.c_int32, ct.c_uint32,
+                                ct.POINTER(ct.c_void_p)]
+    L.dynbatch_plan_view.argtypes = [ct.c_void_p, ct.POINTER(_PlanView)]
+    L.dynbatch_plan_free.argtypes = [ct.c_void_p]
+    L.dynbatch_plan_free.restype = None
+    L.dynbatch_plan_device_bytes.argtypes = [ct.c_void_p]
+    L.dynbatch_plan_device_bytes.restype = ct.c_size_t
+    L.dynbatch_plan_upload.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynbatch_workspace_bytes.argtypes = [ct.c_void_p, ct.POINTER(_Shape)]
+    L.dynbatch_workspace_bytes.restype = ct.c_size_t
+    L.dynbatch_execute.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p,
+                                   ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.moe_workspace_bytes.argtypes = [ct.POINTER(_MoeShape)]
+    L.moe_workspace_bytes.restype = ct.c_size_t
+    L.moe_forward.argtypes = [ct.POINTER(_MoeShape), ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p,
+                              ct.c_void_p, ct.c_void_p, ct.POINTER(_MoeAux), ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    return L
+
+
+lib = _load()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise DynbError(rc, lib.dynb_last_error().decode())
+
+
+def _stream(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ct.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ct.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------------------------------ planner
+class Plan:
+    """Owner of a dynb_plan*; keeps the uploaded index-list buffer alive."""
+
+    def __init__(self, handle, B):
+        self.handle = handle
+        self.B = B
+        self.dev_buf = None
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib.dynbatch_plan_free(self.handle)
+            self.handle = None
+
+    free = __del__
+
+
+def dynbatch_plan(prog, prog_off, arity, flags: int = DYNB_SCHED_IMPROVED) -> Plan:
+    prog = np.ascontiguousarray(prog, dtype=np.int32)
+    prog_off = np.ascontiguousarray(prog_off, dtype=np.int32)
+    arity = np.ascontiguousarray(arity, dtype=np.uint8)
+    h = ct.c_void_p()
+    if len(prog) == 0:
+        prog = np.zeros(1, np.int32)      # keep the pointer non-NULL; lengths come from prog_off
+    _check(lib.dynbatch_plan(prog.ctypes.data_as(I32P), prog_off.ctypes.data_as(I32P), len(prog_off) - 1,
+                             arity.ctypes.data_as(ct.POINTER(ct.c_uint8)), len(arity), flags, ct.byref(h)))
+    return Plan(h, len(prog_off) - 1)
+
+
+def dynbatch_plan_view(plan: Plan) -> SimpleNamespace:
+    v = _PlanView()
+    _check(lib.dynbatch_plan_view(plan.handle, ct.byref(v)))
+
+    def arr(p, n):
+        return np.ctypeslib.as_array(p, shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
+
+    N, nb, B = v.n_nodes, v.n_buckets, v.n_examples
+    return SimpleNamespace(
+        n_examples=B, n_nodes=N, n_levels=v.n_levels, n_buckets=nb, n_compute_nodes=v.n_compute_nodes,
+        n_launches=v.n_launches, max_launch_nodes=v.max_launch_nodes, n_slots=v.n_slots,
+        node_level=arr(v.node_level, N), node_type=arr(v.node_type, N), child0=arr(v.child0, N),
+        child1=arr(v.child1, N), root=arr(v.root, B), bucket_level=arr(v.bucket_level, nb),
+        bucket_type=arr(v.bucket_type, nb), bucket_start=arr(v.bucket_start, nb),
+        bucket_count=arr(v.bucket_count, nb), members=arr(v.members, N), in0=arr(v.in0, N), in1=arr(v.in1, N),
+        out=arr(v.out, N))
+
+
+def dynbatch_plan_device_bytes(plan: Plan) -> int:
+    return int(lib.dynbatch_plan_device_bytes(plan.handle))
+
+
+def dynbatch_plan_upload(plan: Plan, dev_buf=None, stream=None):
+    import torch
+    n = dynbatch_plan_device_bytes(plan)
+    if dev_buf is None:
+        dev_buf = torch.empty(n, dtype=torch.uint8, device="cuda")
+    _check(lib.dynbatch_plan_upload(plan.handle, _ptr(dev_buf), dev_buf.numel() * dev_buf.element_size(), _stream(stream)))
+    plan.dev_buf = dev_buf
+    return dev_buf
+
+
+# ------------------------------------------------------------------------------------------ executor
+def _shape_of(feats) -> _Shape:
+    import torch
+    B, H, W, C = feats.shape
+    if feats.dtype == torch.float32:
+        dt = DYNB_F32
+    elif feats.dtype == torch.bfloat16:
+        dt = DYNB_BF16
+    else:
+        raise TypeError("feats must be float32 or bfloat16")
+    return _Shape(C, H, W, dt)
+
+
+def dynbatch_workspace_bytes(plan: Plan, C: int, H: int, W: int, dtype: int) -> int:
+    return int(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(_Shape(C, H, W, dtype))))
+
+
+def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None, stream=None):
+    """weights: dict with device tensors w1,b1,w3a,b3a,w3b,b3b (biases float32 or None; w1 may be None).
+    feats: device [B,H,W,C] float32 or bfloat16, contiguous.  Returns out [B,H,W,C]."""
+    import torch
+    assert feats.is_cuda and feats.is_contiguous() and feats.shape[0] == plan.B
+    shape = _shape_of(feats)
+    for key in ("w1", "w3a", "w3b"):
+        t = weights.get(key)
+        assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == feats.dtype), key
+    for key in ("b1", "b3a", "b3b"):
+        t = weights.get(key)
+        assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32), key
+    if out is None:
+        out = torch.empty_like(feats)
+    assert out.is_cuda and out.is_contiguous() and out.shape == feats.shape and out.dtype == feats.dtype
+    if workspace is None:
+        workspace = torch.empty(int(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(shape))), dtype=torch.uint8,
+                                device=feats.device)
+    w = _Weights(*[(t.data_ptr() if t is not None else None) for t in
+                   (weights.get(k) for k in ("w1", "b1", "w3a", "b3a", "w3b", "b3b"))])
+    _check(lib.dynbatch_execute(plan.handle, ct.byref(shape), ct.byref(w), _ptr(feats), _ptr(out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+# ------------------------------------------------------------------------------------------ MoE
+def moe_workspace_bytes(T: int, d: int, h: int, E: int, k: int, dtype: int = DYNB_BF16) -> int:
+    return int(lib.moe_workspace_bytes(ct.byref(_MoeShape(T, d, h, E, k, dtype))))
+
+
+def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = False, workspace=None, stream=None):
+    """x [T,d] bf16; Wg, Wn [E,d] bf16; noise [T,E] f32 or None; W1 [E,h,d]; W2 [E,d,h] bf16 (all device,
+    contiguous).  Returns out [T,d] bf16, or (out, aux namespace of device tensors) if want_aux."""
+    import torch
+    T, d = x.shape
+    E, h = W1.shape[0], W1.shape[1]
+    for t in (x, Wg, W1, W2):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+    assert Wg.shape == (E, d) and W1.shape == (E, h, d) and W2.shape == (E, d, h)
+    assert Wn is None or (Wn.is_cuda and Wn.is_contiguous() and Wn.dtype == torch.bfloat16 and Wn.shape == (E, d))
+    assert noise is None or (noise.is_cuda and noise.is_contiguous() and noise.dtype == torch.float32
+                             and noise.shape == (T, E))
+    shape = _MoeShape(T, d, h, E, k, DYNB_BF16)
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        n = int(lib.moe_workspace_bytes(ct.byref(shape)))
+        if n == 0:
+            _check(lib.moe_forward(ct.byref(shape), None, None, None, None, None, None, None, None, None, 0, None))
+        workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
+    aux_t, aux_c = None, None
+    if want_aux:
+        dev = x.device
+        aux_t = SimpleNamespace(
+            logits=torch.empty((T, E), dtype=torch.float32, device=dev),
+            topk_idx=torch.empty((T, k), dtype=torch.int32, device=dev),
+            topk_w=torch.empty((T, k), dtype=torch.float32, device=dev),
+            counts=torch.empty(E, dtype=torch.int32, device=dev),
+            offsets=torch.empty(E + 1, dtype=torch.int32, device=dev),
+            perm=torch.empty(T * k, dtype=torch.int32, device=dev),
+            inv=torch.empty(T * k, dtype=torch.int32, device=dev))
+        aux_c = _MoeAux(*[getattr(aux_t, n).data_ptr() for n in
+                          ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")])
+    _check(lib.moe_forward(ct.byref(shape), _ptr(x), _ptr(Wg), _ptr(Wn), _ptr(noise), _ptr(W1), _ptr(W2), _ptr(out),
+                           ct.byref(aux_c) if aux_c is not None else None, _ptr(workspace),
+                           workspace.numel() * workspace.element_size(), _stream(stream)))
+    return (out, aux_t) if want_aux else out

@@ -1,0 +1,466 @@
+// Sparsely gated mixture-of-experts layer with the paper's degenerate one-level batching
+// (Results / Sparsely Gated Mixture of Experts): the k*b expert uses known after gating are
+// grouped by expert so that each of the n experts is called once on its stacked rows.
+//
+// Stages (all on the caller's stream, no host synchronisation):
+//   gate      logits = x Wg^T + noise * softplus(x Wn^T)                 MFMA, fp32 accumulate
+//   top-k     k largest per token (ties -> lower expert), softmax        one wave per token
+//   group     stable counting sort of the T*k uses by expert             rank-by-prefix-sum, no
+//                                                                        order-dependent atomics
+//   permute   xs[pos] = x[perm[pos] / k]                                  HBM-bound copy
+//   experts   hid = ReLU(xs W1_e^T), y = hid W2_e^T per group             grouped MFMA GEMM, ragged
+//                                                                        and empty groups allowed
+//   combine   out[t] = sum_j w[t][j] * y[inv[t*k+j]]                      HBM-bound, fixed order
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <string>
+
+#include "device_utils.h"
+#include "plan_internal.h"
+
+using dynb::fail;
+
+#define HIP_TRY(expr, what)                                                                   \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(DYNB_E_HIP, std::string(what) + ": " + hipGetErrorString(e_));        \
+    } while (0)
+
+namespace {
+
+constexpr int SORT_BLOCK = 256;   // uses ranked together by one workgroup
+constexpr int TM = 64;            // rows of one grouped-GEMM tile
+constexpr int TN = 128;           // output features of one grouped-GEMM tile
+constexpr int MAX_K = 8;
+
+__device__ __forceinline__ bf16x8 ldg_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// ------------------------------------------------------------------------------------------ gate
+// Workgroup tile: 128 tokens x 64 experts; waves 2 x 2, each 64 tokens x 32 experts.
+__global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
+                                              const bf16_t* __restrict__ Wn, const float* __restrict__ noise,
+                                              float* __restrict__ logits, int T, int d, int E)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.y * 128 + (wave >> 1) * 64;
+    const int e0 = blockIdx.x * 64 + (wave & 1) * 32;
+    if (t0 >= T || e0 >= E) return;
+    const bf16_t* xr[4];
+    const bf16_t* gr[2];
+    const bf16_t* nr[2];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) xr[mt] = x + size_t(min(t0 + mt * 16 + r, T - 1)) * d + g * 8;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const size_t row = size_t(min(e0 + nt * 16 + r, E - 1)) * d + g * 8;
+        gr[nt] = Wg + row;
+        nr[nt] = noise ? Wn + row : Wg + row;
+    }
+    f32x4 ag[4][2], an[4][2];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) { ag[mt][nt] = f32x4{0, 0, 0, 0}; an[mt][nt] = f32x4{0, 0, 0, 0}; }
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        bf16x8 xf[4], gf[2], nf[2];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) xf[mt] = ldg_frag(xr[mt] + k0);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) { gf[nt] = ldg_frag(gr[nt] + k0); nf[nt] = ldg_frag(nr[nt] + k0); }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                ag[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], gf[nt], ag[mt][nt], 0, 0, 0);
+                if (noise) an[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], nf[nt], an[mt][nt], 0, 0, 0);
+            }
+    }
+    // lane holds tokens t0 + mt*16 + g*4 + i, expert e0 + nt*16 + r
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int e = e0 + nt * 16 + r;
+            if (e >= E) continue;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = t0 + mt * 16 + g * 4 + i;
+                if (t >= T) continue;
+                float v = ag[mt][nt][i];
+                if (noise) {
+                    const float z = an[mt][nt][i];
+                    const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
+                    v += noise[size_t(t) * E + e] * sp;
+                }
+                logits[size_t(t) * E + e] = v;
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------ top-k
+// One wave per token. Selection compares fp32 logits exactly: larger first, equal -> lower id.
+__global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, int32_t* __restrict__ topk_idx,
+                                              float* __restrict__ topk_w, int T, int E, int k)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const float* row = logits + size_t(t) * E;
+    int chosen[MAX_K];
+    float val[MAX_K];
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) { chosen[j] = -1; val[j] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) {
+        if (j < k) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+            for (int e = lane; e < E; e += 64) {
+                bool taken = false;
+#pragma unroll
+                for (int q = 0; q < MAX_K; ++q) taken |= (q < j && chosen[q] == e);
+                const float v = row[e];
+                if (!taken && (v > bv || (v == bv && e < bi) || bi == 0x7fffffff)) { bv = v; bi = e; }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+            }
+            chosen[j] = bi;
+            val[j] = bv;
+        }
+    }
+    float den = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) if (j < k) den += expf(val[j] - val[0]);
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j)
+        if (j < k && lane == j) {
+            topk_idx[size_t(t) * k + j] = chosen[j];
+            topk_w[size_t(t) * k + j] = expf(val[j] - val[0]) / den;
+        }
+}
+
+// ------------------------------------------------------------------------------------------ grouping
+__global__ void k_zero_i32(int32_t* p, size_t n)
+{
+    for (size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += size_t(gridDim.x) * blockDim.x) p[i] = 0;
+}
+
+// Block b ranks its 256 uses: lrank[a] = number of earlier uses in the block with the same expert;
+// blockcnt[e][b] = uses of expert e in block b (written by the last such use; array pre-zeroed).
+__global__ __launch_bounds__(SORT_BLOCK) void k_rank_blocks(const int32_t* __restrict__ idx, int32_t* __restrict__ lrank,
+                                                            int32_t* __restrict__ blockcnt, int A, int nblk)
+{
+    __shared__ int32_t se[SORT_BLOCK];
+    const int a = blockIdx.x * SORT_BLOCK + threadIdx.x;
+    const int e = a < A ? idx[a] : -1;
+    se[threadIdx.x] = e;
+    __syncthreads();
+    if (a >= A) return;
+    int before = 0, total = 0;
+    for (int j = 0; j < SORT_BLOCK; ++j) {
+        const bool same = (se[j] == e);
+        total += same;
+        before += same && (j < int(threadIdx.x));
+    }
+    lrank[a] = before;
+    if (before == total - 1) blockcnt[size_t(e) * nblk + blockIdx.x] = total;
+}
+
+// One wave per expert: exclusive scan of blockcnt[e][:] in place, counts[e] = total.
+__global__ __launch_bounds__(256) void k_scan_blocks(int32_t* __restrict__ blockcnt, int32_t* __restrict__ counts,
+                                                     int E, int nblk)
+{
+    const int lane = threadIdx.x & 63;
+    const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (e >= E) return;
+    int32_t* col = blockcnt + size_t(e) * nblk;
+    int carry = 0;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+        const int b = b0 + lane;
+        const int v = b < nblk ? col[b] : 0;
+        int inc = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(inc, off);
+            if (lane >= off) inc += o;
+        }
+        if (b < nblk) col[b] = carry + inc - v;
+        carry += __shfl(inc, 63);
+    }
+    if (lane == 0) counts[e] = carry;
+}
+
+// One wave: offsets = exclusive scan of counts; tile_start = exclusive scan of ceil(counts / TM).
+__global__ __launch_bounds__(64) void k_offsets(const int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                int32_t* __restrict__ tile_start, int E)
+{
+    const int lane = threadIdx.x;
+    int carry = 0, tcarry = 0;
+    for (int e0 = 0; e0 < E; e0 += 64) {
+        const int e = e0 + lane;
+        const int c = e < E ? counts[e] : 0;
+        const int tl = (c + TM - 1) / TM;
+        int inc = c, tinc = tl;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(inc, off);
+            const int to = __shfl_up(tinc, off);
+            if (lane >= off) { inc += o; tinc += to; }
+        }
+        if (e < E) { offsets[e] = carry + inc - c; tile_start[e] = tcarry + tinc - tl; }
+        carry += __shfl(inc, 63);
+        tcarry += __shfl(tinc, 63);
+    }
+    if (lane == 0) { offsets[E] = carry; tile_start[E] = tcarry; }
+}
+
+__global__ __launch_bounds__(SORT_BLOCK) void k_place(const int32_t* __restrict__ idx, const int32_t* __restrict__ lrank,
+                                                      const int32_t* __restrict__ blockoff, const int32_t* __restrict__ offsets,
+                                                      int32_t* __restrict__ perm, int32_t* __restrict__ inv, int A, int nblk)
+{
+    const int a = blockIdx.x * SORT_BLOCK + threadIdx.x;
+    if (a >= A) return;
+    const int e = idx[a];
+    const int pos = offsets[e] + blockoff[size_t(e) * nblk + blockIdx.x] + lrank[a];
+    perm[pos] = a;
+    inv[a] = pos;
+}
+
+// ------------------------------------------------------------------------------------------ permute / combine
+// One wave per sorted row; d is a multiple of 8 (16-byte chunks).
+__global__ __launch_bounds__(256) void k_permute(const bf16_t* __restrict__ x, const int32_t* __restrict__ perm,
+                                                 bf16_t* __restrict__ xs, int A, int d, int k)
+{
+    const int lane = threadIdx.x & 63;
+    const int pos = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pos >= A) return;
+    const int t = perm[pos] / k;
+    const u32x4* src = reinterpret_cast<const u32x4*>(x + size_t(t) * d);
+    u32x4* dst = reinterpret_cast<u32x4*>(xs + size_t(pos) * d);
+    for (int c = lane; c < d / 8; c += 64) dst[c] = src[c];
+}
+
+__global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, const int32_t* __restrict__ inv,
+                                                 const float* __restrict__ topk_w, bf16_t* __restrict__ out,
+                                                 int T, int d, int k)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int pos[MAX_K];
+    float w[MAX_K];
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j)
+        if (j < k) { pos[j] = inv[size_t(t) * k + j]; w[j] = topk_w[size_t(t) * k + j]; }
+    for (int c = lane; c < d / 8; c += 64) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j)
+            if (j < k) {
+                const u32x4 v = reinterpret_cast<const u32x4*>(y + size_t(pos[j]) * d)[c];
+                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] += w[j] * __uint_as_float(u[i] << 16);
+                    acc[2 * i + 1] += w[j] * __uint_as_float(u[i] & 0xffff0000u);
+                }
+            }
+        u32x4 o;
+        o.x = pack_bf16x2(acc[0], acc[1]);
+        o.y = pack_bf16x2(acc[2], acc[3]);
+        o.z = pack_bf16x2(acc[4], acc[5]);
+        o.w = pack_bf16x2(acc[6], acc[7]);
+        reinterpret_cast<u32x4*>(out + size_t(t) * d)[c] = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ grouped GEMM
+// out[row][n] = act( sum_k in[row][k] * W[e][n][k] ) for the rows of expert e.
+// One workgroup = one (row tile of <= 64 rows inside one group, 128 output features) pair; a group's
+// tiles are found from tile_start (prefix sum of ceil(count/64)), so ragged and empty groups cost
+// nothing beyond their real rows.  4 waves split the 128 features; inside a wave only the live
+// 16-row sub-tiles are multiplied.
+template <bool RELU>
+__global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
+                                                      bf16_t* __restrict__ out, const int32_t* __restrict__ offsets,
+                                                      const int32_t* __restrict__ tile_start, int E, int N, int K,
+                                                      int n_tiles_n)
+{
+    const int mtile = blockIdx.x / n_tiles_n;
+    const int ntile = blockIdx.x % n_tiles_n;
+    if (mtile >= tile_start[E]) return;
+    int lo = 0, hi = E;                          // largest e with tile_start[e] <= mtile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_start[mid] <= mtile) lo = mid; else hi = mid;
+    }
+    const int e = lo;
+    const int row0 = offsets[e] + (mtile - tile_start[e]) * TM;
+    const int rows = min(TM, offsets[e + 1] - row0);
+    const int mlive = (rows + 15) >> 4;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int n0 = ntile * TN + wave * 32;
+    if (n0 >= N) return;
+    const bf16_t* wr[2];
+    const bf16_t* ar[4];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) wr[nt] = W + (size_t(e) * N + min(n0 + nt * 16 + r, N - 1)) * K + g * 8;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) ar[mt] = in + size_t(row0 + min(mt * 16 + r, rows - 1)) * K + g * 8;
+    f32x4 acc[4][2];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
+    for (int k0 = 0; k0 < K; k0 += 32) {
+        bf16x8 wf[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) wf[nt] = ldg_frag(wr[nt] + k0);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+            if (mt < mlive) {
+                const bf16x8 af = ldg_frag(ar[mt] + k0);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], af, acc[mt][nt], 0, 0, 0);
+            }
+    }
+    // lane holds features n0 + nt*16 + g*4 .. +3 of row row0 + mt*16 + r
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int lr = mt * 16 + r;
+        if (lr >= rows) continue;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int n = n0 + nt * 16 + g * 4;
+            if (n >= N) continue;
+            f32x4 v = acc[mt][nt];
+            if (RELU) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+            u32x2 pk;
+            pk.x = pack_bf16x2(v.x, v.y);
+            pk.y = pack_bf16x2(v.z, v.w);
+            *reinterpret_cast<u32x2*>(out + size_t(row0 + lr) * N + n) = pk;
+        }
+    }
+}
+
+size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+struct Layout {
+    size_t logits, topk_idx, topk_w, counts, offsets, tile_start, perm, inv, lrank, blockcnt, xs, hid, y, total;
+    int nblk;
+};
+
+Layout layout(const moe_shape* s)
+{
+    Layout L;
+    const size_t T = size_t(s->T), E = size_t(s->E), A = T * size_t(s->k);
+    L.nblk = int((A + SORT_BLOCK - 1) / SORT_BLOCK);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(std::max<size_t>(bytes, 4)); return at; };
+    L.logits = take(T * E * 4);
+    L.topk_idx = take(A * 4);
+    L.topk_w = take(A * 4);
+    L.counts = take(E * 4);
+    L.offsets = take((E + 1) * 4);
+    L.tile_start = take((E + 1) * 4);
+    L.perm = take(A * 4);
+    L.inv = take(A * 4);
+    L.lrank = take(A * 4);
+    L.blockcnt = take(E * size_t(std::max(L.nblk, 1)) * 4);
+    L.xs = take(A * size_t(s->d) * 2);
+    L.hid = take(A * size_t(s->h) * 2);
+    L.y = take(A * size_t(s->d) * 2);
+    L.total = o;
+    return L;
+}
+
+int check_shape(const moe_shape* s, const char* who)
+{
+    if (!s) return fail(DYNB_E_INVAL, std::string(who) + ": NULL shape");
+    if (s->T < 0 || s->d <= 0 || s->h <= 0 || s->E <= 0 || s->k <= 0)
+        return fail(DYNB_E_INVAL, std::string(who) + ": sizes must be positive");
+    if (s->k > s->E) return fail(DYNB_E_INVAL, std::string(who) + ": k > E");
+    if (s->k > MAX_K) return fail(DYNB_E_INVAL, std::string(who) + ": k > 8");
+    if (s->d % 32 || s->h % 32) return fail(DYNB_E_INVAL, std::string(who) + ": d and h must be multiples of 32");
+    if (s->dtype != DYNB_BF16) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": only bf16");
+    if (size_t(s->T) * size_t(s->k) >= (size_t(1) << 30) || size_t(s->T) * size_t(s->E) >= (size_t(1) << 40))
+        return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": too many expert uses");
+    return DYNB_OK;
+}
+
+}  // namespace
+
+extern "C" size_t moe_workspace_bytes(const moe_shape* s)
+{
+    if (check_shape(s, "moe_workspace_bytes") != DYNB_OK) return 0;
+    return std::max<size_t>(layout(s).total, 256);
+}
+
+extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
+                           const void* W1, const void* W2, void* out, const moe_aux* aux, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    int rc = check_shape(s, "moe_forward");
+    if (rc != DYNB_OK) return rc;
+    if (s->T == 0) return DYNB_OK;
+    if (!x || !Wg || !W1 || !W2 || !out || !workspace) return fail(DYNB_E_INVAL, "moe_forward: NULL argument");
+    if (noise && !Wn) return fail(DYNB_E_INVAL, "moe_forward: noise given without Wn");
+    const Layout L = layout(s);
+    if (workspace_bytes < L.total) return fail(DYNB_E_WORKSPACE, "moe_forward: workspace too small");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(DYNB_E_INVAL, "moe_forward: workspace not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const int T = s->T, d = s->d, h = s->h, E = s->E, k = s->k, A = T * k;
+
+    float* logits = (aux && aux->logits) ? aux->logits : reinterpret_cast<float*>(ws + L.logits);
+    int32_t* topk_idx = (aux && aux->topk_idx) ? aux->topk_idx : reinterpret_cast<int32_t*>(ws + L.topk_idx);
+    float* topk_w = (aux && aux->topk_w) ? aux->topk_w : reinterpret_cast<float*>(ws + L.topk_w);
+    int32_t* counts = (aux && aux->counts) ? aux->counts : reinterpret_cast<int32_t*>(ws + L.counts);
+    int32_t* offsets = (aux && aux->offsets) ? aux->offsets : reinterpret_cast<int32_t*>(ws + L.offsets);
+    int32_t* perm = (aux && aux->perm) ? aux->perm : reinterpret_cast<int32_t*>(ws + L.perm);
+    int32_t* inv = (aux && aux->inv) ? aux->inv : reinterpret_cast<int32_t*>(ws + L.inv);
+    int32_t* tile_start = reinterpret_cast<int32_t*>(ws + L.tile_start);
+    int32_t* lrank = reinterpret_cast<int32_t*>(ws + L.lrank);
+    int32_t* blockcnt = reinterpret_cast<int32_t*>(ws + L.blockcnt);
+    bf16_t* xs = reinterpret_cast<bf16_t*>(ws + L.xs);
+    bf16_t* hid = reinterpret_cast<bf16_t*>(ws + L.hid);
+    bf16_t* y = reinterpret_cast<bf16_t*>(ws + L.y);
+    const bf16_t* xb = static_cast<const bf16_t*>(x);
+
+    // m1 gate
+    hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 127) / 128), dim3(256), 0, st, xb,
+                       static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
+    // m2 top-k + softmax
+    hipLaunchKernelGGL(k_topk, dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    // m3 stable counting sort
+    const size_t nbc = size_t(E) * L.nblk;
+    hipLaunchKernelGGL(k_zero_i32, dim3(unsigned(std::min<size_t>((nbc + 255) / 256, 2048))), dim3(256), 0, st, blockcnt, nbc);
+    hipLaunchKernelGGL(k_rank_blocks, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, A, L.nblk);
+    hipLaunchKernelGGL(k_scan_blocks, dim3((E + 3) / 4), dim3(256), 0, st, blockcnt, counts, E, L.nblk);
+    hipLaunchKernelGGL(k_offsets, dim3(1), dim3(64), 0, st, counts, offsets, tile_start, E);
+    hipLaunchKernelGGL(k_place, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, offsets, perm, inv, A, L.nblk);
+    // m4 permute
+    hipLaunchKernelGGL(k_permute, dim3((A + 3) / 4), dim3(256), 0, st, xb, perm, xs, A, d, k);
+    // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
+    const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
+    const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
+    if (max_mtiles * std::max(nt1, nt2) >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
+    hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned(max_mtiles * nt1)), dim3(256), 0, st, xs,
+                       static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
+    hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned(max_mtiles * nt2)), dim3(256), 0, st, hid,
+                       static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
+    // m6 combine
+    hipLaunchKernelGGL(k_combine, dim3((T + 3) / 4), dim3(256), 0, st, y, inv, topk_w, static_cast<bf16_t*>(out), T, d, k);
+    HIP_TRY(hipGetLastError(), "moe_forward");
+    return DYNB_OK;
+}

@@ -1,0 +1,43 @@
+// Internal representation of a plan, shared by the host planner and the GPU executor.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "dynbatch.h"
+
+// One module evaluation as the kernels see it.  src/dst >= 0 name a workspace slot; a negative
+// value v names example -1-v: as a source its feature map (the SCENE output), as a destination
+// its row of the output tensor (the node is that example's root).
+struct dynb_item {
+    int32_t src0;
+    int32_t src1;   // unused for unary functions
+    int32_t dst;
+    int32_t type;
+};
+
+struct dynb_launch {
+    int32_t start;  // first item
+    int32_t count;
+};
+
+struct dynb_plan {
+    int32_t B = 0, N = 0, D = 0, n_types = 0, mode = 0;
+    std::vector<uint8_t> arity;
+    std::vector<int32_t> level, type, child0, child1, root;
+    std::vector<int32_t> b_level, b_type, b_start, b_count, members, in0, in1, out;
+    std::vector<dynb_item> items;        // execution order
+    std::vector<dynb_launch> launches;
+    std::vector<int32_t> leaf_roots;     // examples whose whole program is one SCENE token
+    int32_t n_slots = 0, max_launch = 0;
+    bool has_binary = false;
+    void* dev_buf = nullptr;             // set by dynbatch_plan_upload
+    size_t dev_bytes = 0;
+};
+
+namespace dynb {
+void set_error(const std::string& msg);
+int fail(int code, const std::string& msg);
+}  // namespace dynb

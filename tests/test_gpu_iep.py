@@ -1,0 +1,148 @@
+"""Parity of dynbatch_execute (HIP) against the CPU oracle, through the C ABI.
+
+Tolerances (max |got - ref| / max |ref| per output tensor): 1e-4 for fp32 storage, 2e-2 for bf16
+storage with fp32 accumulation.
+"""
+import numpy as np
+import pytest
+
+from workloads import iep
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def dyn():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1707_02402_amd as d
+    return d
+
+
+@pytest.fixture(scope="module")
+def util():
+    from tests import gpu_util
+    return gpu_util
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2])
+def test_config0_fp32_all_schedules(dyn, util, oracle, flags):
+    w = iep.config0()
+    ref = oracle.iep_forward_workload(w)
+    got = util.iep_run(dyn, w, flags)
+    for i in range(w.B):
+        assert util.normwise(got[i], ref[i]) < TOL["f32"], i
+
+
+@pytest.mark.parametrize("dtype,C,H,W", [("f32", 5, 3, 7), ("bf16", 16, 6, 5), ("f32", 33, 9, 9), ("bf16", 128, 7, 7)])
+def test_generic_kernels_on_ragged_shapes(dyn, util, oracle, dtype, C, H, W):
+    w = iep.small_mixed(seed=C + H, B=9, C=C, H=H, W=W, dtype=dtype, min_len=1, max_len=9)
+    ref = oracle.iep_forward_workload(w)
+    got = util.iep_run(dyn, w)
+    for i in range(w.B):
+        assert util.normwise(got[i], ref[i]) < TOL[dtype], i
+        if len(w.program(i)) == 1:
+            assert (got[i] == w.feats[i]).all()
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2])
+def test_mfma_path_small_batch_every_element(dyn, util, oracle, flags):
+    """bf16, C=128, 14x14: 13 pixel tiles with a ragged last tile, unary and binary functions,
+    single-SCENE programs, odd batch so the two-node workgroups get a lone node."""
+    w = iep.small_mixed(seed=21, B=11, C=128, H=14, W=14, dtype="bf16", min_len=1, max_len=8)
+    assert (w.arity[w.prog] == 2).any() and (w.arity[w.prog] == 1).any()
+    ref = oracle.iep_forward_workload(w)
+    got = util.iep_run(dyn, w, flags)
+    for i in range(w.B):
+        assert util.normwise(got[i], ref[i]) < TOL["bf16"], (i, util.normwise(got[i], ref[i]))
+
+
+def test_mfma_path_wide_level_uses_two_nodes_per_workgroup(dyn, util, oracle):
+    """More than 512 nodes in one launch group selects the two-node kernel; sampled examples vs oracle."""
+    w = iep.small_mixed(seed=5, B=701, C=128, H=14, W=14, dtype="bf16", min_len=2, max_len=4)
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
+    assert v.max_launch_nodes > 512 and v.max_launch_nodes % 2 == 1
+    got = util.iep_run(dyn, w)
+    sample = [0, 1, 350, 699, 700]
+    ref = oracle.iep_forward_workload(w.subset(sample))
+    for j, i in enumerate(sample):
+        assert util.normwise(got[i], ref[j]) < TOL["bf16"], i
+    naive = util.iep_run(dyn, w.subset(sample), dyn.DYNB_SCHED_NAIVE)
+    assert (naive == got[sample]).all()          # batched == per-example, bit for bit
+
+
+def test_identity_kernels_are_exact_on_the_mfma_path(dyn, util):
+    """Unary module = 2x, binary module = 2(x0+x1) for identity kernels: exact powers of two in bf16."""
+    C = 128
+    g = np.random.default_rng(0)
+    arity = np.array([0, 1, 2], np.uint8)
+    progs = [np.array([1] * n + [0], np.int32) for n in (1, 4, 9)] + [iep.balanced_program(g, D, [2]) for D in (2, 4)]
+    off = np.zeros(len(progs) + 1, np.int32)
+    off[1:] = np.cumsum([len(p) for p in progs])
+    f = np.abs(iep.make_feats(1, len(progs), 14, 14, C, "bf16"))
+    w3 = np.zeros((3, C, 3, 3, C), np.float32)
+    w1 = np.zeros((3, C, 2 * C), np.float32)
+    for t in (1, 2):
+        w3[t, np.arange(C), 1, 1, np.arange(C)] = 1
+        w1[t, np.arange(C), np.arange(C)] = 1
+        w1[t, np.arange(C), C + np.arange(C)] = 1
+    w = iep.IepWorkload("closed-form", "bf16", arity, np.concatenate(progs), off, C, 14, 14, f, w1,
+                        np.zeros((3, C), np.float32), w3, np.zeros((3, C), np.float32), w3.copy(),
+                        np.zeros((3, C), np.float32))
+    got = util.iep_run(dyn, w)
+    for i, scale in enumerate([2.0, 16.0, 512.0, 4.0, 64.0]):
+        assert (got[i] == scale * f[i]).all(), i
+
+
+def test_config1_balanced_trees_sampled(dyn, util, oracle):
+    w = iep.config1()
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
+    assert v.n_levels == 5 and v.n_launches == 4 and v.n_compute_nodes == 960
+    got = util.iep_run(dyn, w)
+    sample = [0, 31, 63]
+    ref = oracle.iep_forward_workload(w.subset(sample))
+    for j, i in enumerate(sample):
+        assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
+    again = util.iep_run(dyn, w)
+    assert (again == got).all()                  # deterministic
+    assert np.isfinite(got).all() and (got >= 0).all()
+
+
+def test_config2_iep_shaped_sampled(dyn, util, oracle):
+    w = iep.config2()
+    got = util.iep_run(dyn, w)
+    lens = np.diff(w.prog_off)
+    sample = [int(np.argmax(lens)), int(np.argmin(lens)), 7, 128, 255]
+    ref = oracle.iep_forward_workload(w.subset(sample))
+    for j, i in enumerate(sample):
+        assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
+    # batched (improved sort) == standard sort == per-example loop, bit for bit, on a subset
+    sub = w.subset(range(0, 256, 16))
+    a = util.iep_run(dyn, sub, 0)
+    assert (a == got[::16]).all()
+    assert (util.iep_run(dyn, sub, 1) == a).all()
+    assert (util.iep_run(dyn, sub, 2) == a).all()
+    assert np.isfinite(got).all() and (got >= 0).all()
+
+
+def test_execute_error_paths(dyn, util):
+    import torch
+    w = iep.config0()
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity)
+    weights = util.iep_weights_dev(w)
+    feats = util.to_dev(w.feats, "f32")
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_execute(plan, weights, feats)
+    assert e.value.name == "DYNB_E_WORKSPACE"            # not uploaded
+    dyn.dynbatch_plan_upload(plan)
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_execute(plan, weights, feats, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.name == "DYNB_E_WORKSPACE"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_execute(plan, dict(weights, w1=None), feats)
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_plan_upload(plan, torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.name == "DYNB_E_WORKSPACE"

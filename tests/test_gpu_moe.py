@@ -1,0 +1,142 @@
+"""Parity of moe_forward (HIP) against the CPU oracle, through the C ABI, in stages:
+  (i)   gate logits within tolerance of the fp64 oracle;
+  (ii)  the oracle's top-k and grouping applied to the GPU's own fp32 logits must reproduce
+        topk_idx, counts, offsets, perm and inv bit for bit (float summation order cannot
+        flip a routing decision that is taken on identical fp32 values);
+  (iii) the oracle's expert + combine stage on that routing gives `out` within 2e-2;
+  (iv)  end to end from raw inputs, excluding tokens whose k-th and (k+1)-th logits are closer
+        than the logit tolerance.
+"""
+import numpy as np
+import pytest
+
+from workloads import moe
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 1e-4     # max |got - ref| / max |ref|: bf16 products are exact in fp32, K <= 1024 additions
+OUT_TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def dyn():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1707_02402_amd as d
+    return d
+
+
+@pytest.fixture(scope="module")
+def util():
+    from tests import gpu_util
+    return gpu_util
+
+
+def stack(m):
+    W1 = np.stack([m.expert_weights(e)[0] for e in range(m.E)])
+    W2 = np.stack([m.expert_weights(e)[1] for e in range(m.E)])
+    return W1, W2
+
+
+def check_routing(oracle, m, aux):
+    r = oracle.moe_route(aux["logits"], m.k)
+    for name in ("topk_idx", "counts", "offsets", "perm", "inv"):
+        got = aux[name]
+        assert got.dtype == np.int32 and (got == getattr(r, name)).all(), name
+    assert np.abs(aux["topk_w"] - r.topk_w).max() < 1e-5
+    return r
+
+
+@pytest.mark.parametrize("T,d,h,E,k,empty", [(300, 64, 96, 20, 3, 0.2), (257, 32, 32, 5, 5, 0.0), (1000, 128, 160, 70, 1, 0.1),
+                                              (64, 96, 64, 300, 8, 0.5), (1, 32, 32, 2, 2, 0.0)])
+def test_small_layers_every_element(dyn, util, oracle, T, d, h, E, k, empty):
+    m = moe.small(seed=T + E, T=T, d=d, h=h, E=E, k=k, empty_frac=empty)
+    W1, W2 = stack(m)
+    out, aux = util.moe_run(dyn, m, W1, W2)
+    ref_logits = oracle.moe_logits(m.x, m.Wg, m.Wn, m.noise)
+    assert util.normwise(aux["logits"], ref_logits) < LOGIT_TOL                      # (i)
+    r = check_routing(oracle, m, aux)                                                # (ii)
+    assert (r.counts[m.empty] == 0).all()
+    ref = oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)                       # (iii)
+    assert util.normwise(out, ref) < OUT_TOL
+    # (iv) end to end: tokens with a clear margin between the k-th and (k+1)-th logit must route identically
+    e2e = oracle.moe_forward(m.x, m.Wg, m.Wn, m.noise, W1, W2, k)
+    if k < E:
+        srt = np.sort(ref_logits, axis=1)[:, ::-1]
+        clear = (srt[:, k - 1] - srt[:, k]) > 4 * LOGIT_TOL * np.abs(ref_logits).max()
+    else:
+        clear = np.ones(T, bool)
+    assert clear.mean() > 0.5
+    assert (np.sort(e2e.topk_idx[clear], 1) == np.sort(r.topk_idx[clear], 1)).all()
+    assert util.normwise(out[clear], e2e.out[clear]) < OUT_TOL
+
+
+def test_noiseless_gate_and_ties(dyn, util, oracle):
+    """noise = NULL drops the softplus term; duplicated gate columns give exactly equal logits: lower id wins."""
+    m = moe.small(seed=9, T=128, d=64, h=64, E=16, k=4)
+    m.Wg[:, 8:] = m.Wg[:, :8]                    # expert e and e+8 tie on every token
+    W1, W2 = stack(m)
+    out, aux = util.moe_run(dyn, m, W1, W2, noise=False)
+    ref_logits = oracle.moe_logits(m.x, m.Wg, None, None)
+    assert util.normwise(aux["logits"], ref_logits) < LOGIT_TOL
+    assert (aux["logits"][:, 8:] == aux["logits"][:, :8]).all()
+    r = check_routing(oracle, m, aux)
+    assert (r.topk_idx[:, 0] < 8).all() and (r.topk_idx[:, 1] == r.topk_idx[:, 0] + 8).all()
+    assert util.normwise(out, oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)) < OUT_TOL
+
+
+def sampled_layer_check(dyn, util, oracle, m, n_sample):
+    import torch
+    W1b = np.empty((m.E, m.h, m.d), np.uint16)
+    W2b = np.empty((m.E, m.d, m.h), np.uint16)
+    m.all_expert_weights_bits(W1b, W2b, threads=16)
+    dev = util.moe_inputs_dev(m, np.zeros((1, 1, 1), np.float32), np.zeros((1, 1, 1), np.float32))
+    dev["W1"] = torch.from_numpy(W1b.view(np.int16)).cuda().view(torch.bfloat16)
+    dev["W2"] = torch.from_numpy(W2b.view(np.int16)).cuda().view(torch.bfloat16)
+    del W1b, W2b
+    out, aux = util.moe_run(dyn, m, dev=dev)
+    rows = np.random.default_rng(0).choice(m.T, n_sample, replace=False)
+    ref_logits = oracle.moe_logits(m.x[rows], m.Wg, m.Wn, m.noise[rows])
+    assert util.normwise(aux["logits"][rows], ref_logits) < LOGIT_TOL                # (i) sampled rows
+    r = check_routing(oracle, m, aux)                                                # (ii) whole layer
+    assert (r.counts[m.empty] == 0).all() and r.counts.sum() == m.A
+    assert (np.sort(aux["perm"]) == np.arange(m.A)).all()
+    for t in rows[:max(8, n_sample // 4)]:                                           # (iii) sampled tokens
+        ws = [m.expert_weights(int(e)) for e in r.topk_idx[t]]
+        ref = oracle.moe_token(m.x[t], r.topk_w[t], [a for a, _ in ws], [b for _, b in ws])
+        assert util.normwise(out[t], ref) < OUT_TOL, t
+    out2, aux2 = util.moe_run(dyn, m, dev=dev)
+    assert (out2 == out).all() and (aux2["perm"] == aux["perm"]).all()               # deterministic
+    return r
+
+
+def test_config3_sampled(dyn, util, oracle):
+    m = moe.config3()
+    r = sampled_layer_check(dyn, util, oracle, m, 64)
+    load = np.sort(r.counts)[::-1].astype(np.float64)
+    ok = load >= 8
+    slope = np.polyfit(np.log(np.arange(1, m.E + 1)[ok]), np.log(load[ok]), 1)[0]
+    assert abs(slope + 1.1) < 0.15
+
+
+def test_config4_sampled_with_empty_experts(dyn, util, oracle):
+    m = moe.config4()
+    r = sampled_layer_check(dyn, util, oracle, m, 32)
+    assert (r.counts == 0).sum() >= 51 and len(m.empty) == 51
+
+
+def test_moe_error_paths(dyn, util):
+    import torch
+    m = moe.small(seed=1, T=16, d=32, h=32, E=4, k=2)
+    W1, W2 = stack(m)
+    dev = util.moe_inputs_dev(m, W1, W2)
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], 5)
+    assert e.value.name == "DYNB_E_INVAL"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], 2,
+                        workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.name == "DYNB_E_WORKSPACE"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.moe_forward(dev["x"], dev["Wg"], None, dev["noise"], dev["W1"], dev["W2"], 2)
+    assert e.value.name == "DYNB_E_INVAL"

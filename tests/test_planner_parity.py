@@ -1,0 +1,113 @@
+"""The C++ planner against the plan oracle: every array of the plan view must be bit-identical.
+Host code only (no GPU needed)."""
+import ctypes as ct
+import os
+import re
+
+import numpy as np
+import pytest
+
+from workloads import iep
+
+FIELDS = ("node_level", "node_type", "child0", "child1", "root", "bucket_level", "bucket_type", "bucket_start",
+          "bucket_count", "members", "in0", "in1", "out")
+
+
+@pytest.fixture(scope="module")
+def dyn():
+    import paper_1707_02402_amd as d
+    return d
+
+
+def assert_same_plan(v, o):
+    assert (v.n_nodes, v.n_levels, v.n_buckets) == (o.n_nodes, o.n_levels, o.n_buckets)
+    for f in FIELDS:
+        a, b = getattr(v, f), getattr(o, f)
+        assert a.dtype == np.int32 and a.shape == b.shape and (a == b).all(), f
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("cfg", ["config0", "config1", "config2"])
+def test_plan_is_bit_exact_on_the_configs(dyn, oracle, cfg, mode):
+    w = getattr(iep, cfg)()
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, mode)
+    v = dyn.dynbatch_plan_view(plan)
+    assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=mode))
+    assert v.n_compute_nodes == w.n_module_evals
+    if mode == 0:
+        assert v.n_launches == v.n_levels - 1          # deepest label of these configs holds only SCENE leaves
+
+
+def test_plan_is_bit_exact_on_many_random_batches(dyn, oracle):
+    for seed in range(40):
+        w = iep.small_mixed(seed=seed, B=1 + seed % 9, C=1, H=1, W=1, dtype="f32", min_len=1, max_len=3 + seed)
+        for mode in (0, 1):
+            v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, mode))
+            assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=mode))
+
+
+def test_threaded_parse_of_a_large_batch(dyn, oracle):
+    w = iep.config2(B=2500)                          # > 32768 nodes: the planner uses several threads
+    assert len(w.prog) > (1 << 15)
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, 0))
+    o = oracle.plan(w.prog, w.prog_off, w.arity)
+    assert_same_plan(v, o)
+
+
+def test_naive_schedule_is_one_valid_call_per_node(dyn):
+    w = iep.config2(B=16)
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_SCHED_NAIVE))
+    assert v.n_buckets == v.n_nodes and (v.bucket_count == 1).all()
+    assert v.n_launches == w.n_module_evals and v.max_launch_nodes == 1
+    when = np.empty(v.n_nodes, np.int64)
+    when[v.members] = np.arange(v.n_nodes)
+    for child in (v.child0, v.child1):
+        has = child >= 0
+        assert (when[child[has]] < when[np.nonzero(has)[0]]).all()
+    ex = np.searchsorted(w.prog_off, v.members, side="right") - 1
+    assert (np.diff(ex) >= 0).all()                  # example by example
+
+
+def test_error_codes(dyn):
+    ar = np.array([0, 1, 2], np.uint8)
+    ok = np.array([1, 0], np.int32)
+    for bad in ([2, 0], [0, 0], [1], [7, 0], []):
+        prog = np.concatenate([ok, np.array(bad, np.int32), ok]).astype(np.int32)
+        off = np.array([0, 2, 2 + len(bad), 4 + len(bad)], np.int32)
+        with pytest.raises(dyn.DynbError) as e:
+            dyn.dynbatch_plan(prog, off, ar)
+        assert e.value.name == "DYNB_E_MALFORMED" and "example 1" in str(e.value)
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), np.array([0, 3], np.uint8))
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=16)
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_plan(ok, np.array([1, 2], np.int32), ar)
+    assert e.value.name == "DYNB_E_INVAL"
+    from paper_1707_02402_amd.binding import lib
+    assert lib.dynbatch_plan(None, None, 1, None, 1, 0, None) == -1
+    assert lib.dynbatch_workspace_bytes(None, None) == 0
+    assert lib.moe_workspace_bytes(None) == 0
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_1707_02402_amd.binding import EXPORTS, LIB_PATH
+    header = open(os.path.join(os.path.dirname(__file__), "..", "include", "dynbatch.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dynb_\w+|dynbatch_\w+|moe_\w+)\s*\(", header))
+    assert declared == set(EXPORTS)
+    L = ct.CDLL(LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_moe_shape_checks_need_no_gpu(dyn):
+    from paper_1707_02402_amd.binding import _MoeShape, lib
+    assert dyn.moe_workspace_bytes(64, 64, 64, 8, 2) > 0
+    for bad in ((64, 64, 64, 8, 9), (64, 64, 64, 4, 5), (64, 48, 64, 8, 2), (64, 64, 0, 8, 2)):
+        assert dyn.moe_workspace_bytes(*bad) == 0
+    # T = 0 succeeds without touching any pointer
+    assert lib.moe_forward(ct.byref(_MoeShape(0, 64, 64, 8, 2, 1)), None, None, None, None, None, None, None, None,
+                           None, 0, None) == 0
