@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamic-batching hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+  * program-tree engine, config 2 (256 IEP-shaped programs, 40 functions, C=128 @ 14x14, bf16):
+    dynbatch_plan (host) + dynbatch_plan_upload + dynbatch_execute;
+  * mixture-of-experts layer, config 4 (16384 tokens, d=1024, 1024 experts, h=2048, top-4,
+    Zipf(1.2) load, 5 % empty experts, bf16): moe_forward.
+Inputs are resident in HBM before the timed region.  `value` is module evaluations per second of
+the program-tree part (the metric's first half); the MoE half is in the "moe" object.
+
+Prints ONE JSON line (see the keys at the bottom of main()).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FLOP_UNARY = 2 * 2 * 196 * 128 * 1152            # two conv3x3, 196 pixels, 128 out, K = 9*128
+FLOP_BINARY = FLOP_UNARY + 2 * 196 * 128 * 256   # plus the conv1x1 over 2C channels
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--iep-config", choices=["config1", "config2"], default="config2")
+    ap.add_argument("--skip-moe", action="store_true")
+    ap.add_argument("--skip-naive", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--moe-config", choices=["config3", "config4"], default="config4")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists in it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1707_02402_amd as dyn
+    from tests import gpu_util as U
+    from workloads import iep, moe
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    K, Wm = args.steps, args.warmup
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+
+    # ------------------------------------------------------------------ program-tree engine
+    w = getattr(iep, args.iep_config)()
+    weights = U.iep_weights_dev(w)
+    feats = U.to_dev(w.feats, w.dtype)
+    out = torch.empty_like(feats)
+    plan0 = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity)
+    view = dyn.dynbatch_plan_view(plan0)
+    ws_bytes = max(dyn.dynbatch_workspace_bytes(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, f), w.C, w.H, w.W,
+                                                dyn.DYNB_BF16) for f in (dyn.DYNB_SCHED_IMPROVED, dyn.DYNB_SCHED_NAIVE))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    devbuf = torch.empty(dyn.dynbatch_plan_device_bytes(plan0) + 4096, dtype=torch.uint8, device="cuda")
+    n_evals = view.n_compute_nodes
+    n_binary = int((w.arity[w.prog] == 2).sum())
+    flops_step = (n_evals - n_binary) * FLOP_UNARY + n_binary * FLOP_BINARY
+    log(f"[bench] {w.name}: B={w.B} nodes={view.n_nodes} evals={n_evals} levels={view.n_levels} "
+        f"launches={view.n_launches} buckets={view.n_buckets}")
+
+    keep = []
+
+    def iep_step(flags=0, host_ms=None):
+        t0 = time.perf_counter()
+        plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
+        t1 = time.perf_counter()
+        dyn.dynbatch_plan_upload(plan, devbuf)
+        dyn.dynbatch_execute(plan, weights, feats, out, ws)
+        if host_ms is not None:
+            host_ms.append((t1 - t0) * 1e3)
+        keep.append(plan)
+
+    for _ in range(Wm):
+        iep_step()
+    torch.cuda.synchronize()
+    keep.clear()
+    plan_ms = []
+    t0 = time.perf_counter()
+    for _ in range(K):
+        iep_step(host_ms=plan_ms)
+    torch.cuda.synchronize()
+    iep_ms = (time.perf_counter() - t0) * 1e3 / K
+    keep.clear()
+
+    # execute only (plan reused), and per-launch-group GPU times from HIP events on the same stream
+    dyn.dynbatch_plan_upload(plan0, devbuf)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        dyn.dynbatch_execute(plan0, weights, feats, out, ws)
+    torch.cuda.synchronize()
+    exec_ms = (time.perf_counter() - t0) * 1e3 / K
+    dyn.dynb_timing_enable(True)
+    launch_ms, launch_n = [], 0
+    for _ in range(K):
+        dyn.dynbatch_execute(plan0, weights, feats, out, ws)
+        st = dyn.dynb_timing_read()
+        launch_ms.append(sum(ms for _, _, ms in st))
+        launch_n = len(st)
+    dyn.dynb_timing_enable(False)
+    kern_ms_step = float(np.mean(launch_ms))          # all module-kernel launches of one step
+    avg_launch_us = kern_ms_step * 1e3 / launch_n
+    achieved_tflops = flops_step / (kern_ms_step * 1e-3) / 1e12
+
+    naive = None
+    if not args.skip_naive:
+        iep_step(dyn.DYNB_SCHED_NAIVE)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        iep_step(dyn.DYNB_SCHED_NAIVE)
+        torch.cuda.synchronize()
+        naive_ms = (time.perf_counter() - t0) * 1e3
+        keep.clear()
+        naive = {"kind": "same kernels, one launch per node, example by example", "ms_per_step": round(naive_ms, 3),
+                 "module_evals_per_sec": round(n_evals / naive_ms * 1e3, 1), "speedup_batched": round(naive_ms / iep_ms, 2)}
+
+    # ------------------------------------------------------------------ mixture of experts
+    moe_res, moe_roof = None, []
+    if not args.skip_moe:
+        t0 = time.perf_counter()
+        m = getattr(moe, args.moe_config)()
+        W1b = np.empty((m.E, m.h, m.d), np.uint16)
+        W2b = np.empty((m.E, m.d, m.h), np.uint16)
+        m.all_expert_weights_bits(W1b, W2b, threads=16)
+        dev = U.moe_inputs_dev(m, np.zeros((1, 1, 1), np.float32), np.zeros((1, 1, 1), np.float32))
+        dev["W1"] = torch.from_numpy(W1b.view(np.int16)).cuda().view(torch.bfloat16)
+        dev["W2"] = torch.from_numpy(W2b.view(np.int16)).cuda().view(torch.bfloat16)
+        del W1b, W2b
+        log(f"[bench] {m.name}: inputs generated and uploaded in {time.perf_counter() - t0:.1f} s")
+        mws = torch.empty(dyn.moe_workspace_bytes(m.T, m.d, m.h, m.E, m.k), dtype=torch.uint8, device="cuda")
+        mout = torch.empty_like(dev["x"])
+
+        def moe_step():
+            dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, out=mout, workspace=mws)
+
+        for _ in range(Wm):
+            moe_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            moe_step()
+        torch.cuda.synchronize()
+        moe_ms = (time.perf_counter() - t0) * 1e3 / K
+        dyn.dynb_timing_enable(True)
+        stages = {n: [] for n in dyn.MOE_STAGES}
+        for _ in range(K):
+            moe_step()
+            for tag, _, ms in dyn.dynb_timing_read():
+                stages[dyn.MOE_STAGES[tag]].append(ms)
+        dyn.dynb_timing_enable(False)
+        stage_ms = {n: float(np.mean(v)) for n, v in stages.items()}
+        _, aux = dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, want_aux=True,
+                                 workspace=mws)
+        counts = aux.counts.cpu().numpy()
+        n_active = int((counts > 0).sum())
+        A = m.A
+        by_perm = m.T * m.d * 2 + A * m.d * 2 + A * 4
+        by_comb = A * m.d * 2 + m.T * m.d * 2 + A * 8
+        by_w = 2 * m.d * m.h * 2 * n_active                      # both layers' weights of every non-empty expert
+        by_ffn = by_w + A * (m.d + 2 * m.h + m.d) * 2             # + xs read, hid written and read, y written
+        fl_ffn = 4.0 * m.d * m.h * A
+        ffn_ms = stage_ms["ffn1"] + stage_ms["ffn2"]
+        moe_res = {"workload": m.name, "tokens_per_sec": round(m.T / moe_ms * 1e3, 1), "ms_per_step": round(moe_ms, 4),
+                   "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "active_experts": n_active,
+                   "max_expert_rows": int(counts.max())}
+        moe_roof = [
+            {"kernel": "k_permute", "bound": "hbm", "achieved": round(by_perm / stage_ms["permute"] / 1e6, 1),
+             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(by_perm / stage_ms["permute"] / 1e6 / PEAK_HBM_GBS, 4),
+             "traffic": None},
+            {"kernel": "k_combine", "bound": "hbm", "achieved": round(by_comb / stage_ms["combine"] / 1e6, 1),
+             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(by_comb / stage_ms["combine"] / 1e6 / PEAK_HBM_GBS, 4),
+             "traffic": None},
+            {"kernel": "k_grouped_gemm (both expert layers)", "bound": "hbm", "achieved": round(by_ffn / ffn_ms / 1e6, 1),
+             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(by_ffn / ffn_ms / 1e6 / PEAK_HBM_GBS, 4),
+             "mfma_tflops": round(fl_ffn / ffn_ms / 1e9, 1), "traffic": None},
+        ]
+
+    # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
+    cpu = None
+    if not args.skip_cpu:
+        import oracle
+        n_s = min(32, w.B)
+        sub = w.subset(range(0, w.B, w.B // n_s)[:n_s])
+        t0 = time.perf_counter()
+        oracle.iep_forward_workload(sub)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(sub.n_module_evals / dt, 2), "unit": "module_evals/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"{sub.B} of {w.B} examples of {w.name} ({sub.n_module_evals} module evaluations, "
+               f"{dt:.1f} s wall, fp64 per-example tree recursion)"}
+        if moe_res is not None:
+            rows = np.random.default_rng(0).choice(m.T, 48, replace=False)
+            idx = aux.topk_idx.cpu().numpy()
+            wts = aux.topk_w.cpu().numpy().astype(np.float64)
+            packs = {int(e): m.expert_weights(int(e)) for e in np.unique(idx[rows])}
+            t0 = time.perf_counter()
+            for t in rows:
+                oracle.moe_token(m.x[t], wts[t], [packs[int(e)][0] for e in idx[t]], [packs[int(e)][1] for e in idx[t]])
+            dt = time.perf_counter() - t0
+            cpu["moe"] = {"value": round(len(rows) / dt, 2), "unit": "tokens/s", "cores": 1,
+                          "sample": f"expert+combine stage of 48 of {m.T} tokens, one thread, {dt:.1f} s"}
+
+    res = {
+        "metric": "module_evals_per_sec", "value": round(n_evals / iep_ms * 1e3, 1), "unit": "module_evals/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(iep_ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "nodes": int(view.n_nodes), "module_evals": int(n_evals),
+                   "levels": int(view.n_levels), "launch_groups": int(view.n_launches), "C": w.C, "H": w.H, "W": w.W,
+                   "step": "dynbatch_plan + dynbatch_plan_upload + dynbatch_execute"},
+        "plan_host_ms": round(float(np.mean(plan_ms)), 4), "execute_only_ms": round(exec_ms, 4),
+        "execute_only_module_evals_per_sec": round(n_evals / exec_ms * 1e3, 1),
+        "roofline": {"kernel": "k_module_mfma", "bound": "mfma", "achieved": round(achieved_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "launches_per_step": launch_n, "avg_launch_us": round(avg_launch_us, 2),
+                     "flops_per_step": flops_step},
+        "rooflines_other": moe_roof, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
+        "paper_context": "paper reports ratios only: >14x cell execution (IEP, GTX 1080 Ti), up to 1000x (MoE, 11 GB card)",
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -213,6 +213,30 @@ int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const voi
                 const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------- */
+/* Per-stage timing (the paper reports "neural cell execution time" and "data stacking" apart   */
+/* from the whole forward pass: Results / IEP, Results / Sparsely Gated Mixture of Experts)      */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t tag;    /* dynbatch_execute: index of the launch group; moe_forward: stage id
+                       0 gate, 1 top-k, 2 grouping (counting sort), 3 permute, 4 expert layer 1,
+                       5 expert layer 2, 6 combine                                               */
+    int32_t units;  /* dynbatch_execute: module evaluations in the launch group; moe_forward: 0   */
+    float ms;       /* GPU time between the HIP events that bracket the stage                    */
+} dynb_stage_time;
+
+/* Switches event recording on (1) or off (0, the default) for the calling thread.  While on,
+ * dynbatch_execute and moe_forward record one HIP event per launch group / stage on the caller's
+ * stream; this costs a few microseconds per event, so leave it off when measuring throughput.  */
+int dynb_timing_enable(int on);
+
+/* Waits for the last timed call of this thread to finish on the GPU and returns its stages.
+ *   out       host [capacity]
+ *   n_out     host, receives the number of stages of the call (may exceed capacity)
+ * Errors: DYNB_E_INVAL, DYNB_E_HIP.                                                             */
+int dynb_timing_read(dynb_stage_time* out, int32_t capacity, int32_t* n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "D
 
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
-           "dynbatch_execute", "moe_workspace_bytes", "moe_forward"]
+           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "dynb_timing_enable", "dynb_timing_read"]
 
 
 class DynbError(RuntimeError):
@@ -54,6 +54,10 @@ class _MoeShape(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in ("T", "d", "h", "E", "k", "dtype")]
 
 
+class _StageTime(ct.Structure):
+    _fields_ = [("tag", ct.c_int32), ("units", ct.c_int32), ("ms", ct.c_float)]
+
+
 class _MoeAux(ct.Structure):
     _fields_ = [(n, ct.c_void_p) for n in ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")]
 
@@ -79,6 +83,8 @@ def _load():
     L.moe_workspace_bytes.restype = ct.c_size_t
     L.moe_forward.argtypes = [ct.POINTER(_MoeShape), ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p,
                               ct.c_void_p, ct.c_void_p, ct.POINTER(_MoeAux), ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynb_timing_enable.argtypes = [ct.c_int]
+    L.dynb_timing_read.argtypes = [ct.POINTER(_StageTime), ct.c_int32, ct.POINTER(ct.c_int32)]
     return L
 
 
@@ -245,3 +251,22 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
                            ct.byref(aux_c) if aux_c is not None else None, _ptr(workspace),
                            workspace.numel() * workspace.element_size(), _stream(stream)))
     return (out, aux_t) if want_aux else out
+
+
+# ------------------------------------------------------------------------------------------ timing
+MOE_STAGES = ("gate", "topk", "sort", "permute", "ffn1", "ffn2", "combine")
+
+
+def dynb_timing_enable(on: bool) -> None:
+    _check(lib.dynb_timing_enable(1 if on else 0))
+
+
+def dynb_timing_read():
+    """Stages of the last timed call: list of (tag, units, ms)."""
+    n = ct.c_int32(0)
+    _check(lib.dynb_timing_read(None, 0, ct.byref(n)))
+    if n.value == 0:
+        return []
+    buf = (_StageTime * n.value)()
+    _check(lib.dynb_timing_read(buf, n.value, ct.byref(n)))
+    return [(b.tag, b.units, b.ms) for b in buf]

@@ -17,6 +17,7 @@
 
 #include "device_utils.h"
 #include "plan_internal.h"
+#include "timing.h"
 
 using dynb::fail;
 
@@ -453,6 +454,7 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
     a.w1 = w->w1; a.b1 = w->b1; a.w3a = w->w3a; a.b3a = w->b3a; a.w3b = w->w3b; a.b3b = w->b3b;
     a.C = s->C; a.H = s->H; a.W = s->W;
     const unsigned bx = unsigned((chw + 255) / 256);
+    const bool timed = dynb::timing_on();
     for (const dynb_launch& l : p->launches) {
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
@@ -470,6 +472,7 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
             hipLaunchKernelGGL((k_gen_conv<T, false>), grid, dim3(256), 0, st, b);
             hipLaunchKernelGGL((k_gen_conv<T, true>), grid, dim3(256), 0, st, b);
         }
+        if (timed) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
     HIP_TRY(hipGetLastError(), "dynbatch_execute(generic kernels)");
     return DYNB_OK;
@@ -499,6 +502,7 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.w1 = static_cast<const bf16_t*>(w->w1); a.b1 = w->b1;
     a.w3a = static_cast<const bf16_t*>(w->w3a); a.b3a = w->b3a;
     a.w3b = static_cast<const bf16_t*>(w->w3b); a.b3b = w->b3b;
+    const bool timed = dynb::timing_on();
     for (const dynb_launch& l : p->launches) {
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
@@ -512,6 +516,7 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
             hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else
             hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
+        if (timed) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
     HIP_TRY(hipGetLastError(), "dynbatch_execute(mfma kernels)");
     return DYNB_OK;
@@ -533,6 +538,7 @@ extern "C" int dynbatch_execute(const dynb_plan* p, const dynb_shape* s, const d
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
 
+    if (dynb::timing_on()) dynb::timing_begin(st);
     if (!p->leaf_roots.empty()) {
         const size_t words = size_t(s->C) * s->H * s->W * elt_bytes(s->dtype) / 4;
         if ((size_t(s->C) * s->H * s->W * elt_bytes(s->dtype)) % 4) return fail(DYNB_E_UNSUPPORTED, "dynbatch_execute: odd-sized bf16 map");

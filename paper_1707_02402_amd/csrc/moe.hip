@@ -18,6 +18,7 @@
 
 #include "device_utils.h"
 #include "plan_internal.h"
+#include "timing.h"
 
 using dynb::fail;
 
@@ -437,11 +438,15 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
     bf16_t* y = reinterpret_cast<bf16_t*>(ws + L.y);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 
+    const bool timed = dynb::timing_on();
+    if (timed) dynb::timing_begin(st);
     // m1 gate
     hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 127) / 128), dim3(256), 0, st, xb,
                        static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
+    if (timed) dynb::timing_mark(st, dynb::ST_GATE, 0);
     // m2 top-k + softmax
     hipLaunchKernelGGL(k_topk, dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    if (timed) dynb::timing_mark(st, dynb::ST_TOPK, 0);
     // m3 stable counting sort
     const size_t nbc = size_t(E) * L.nblk;
     hipLaunchKernelGGL(k_zero_i32, dim3(unsigned(std::min<size_t>((nbc + 255) / 256, 2048))), dim3(256), 0, st, blockcnt, nbc);
@@ -449,18 +454,23 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
     hipLaunchKernelGGL(k_scan_blocks, dim3((E + 3) / 4), dim3(256), 0, st, blockcnt, counts, E, L.nblk);
     hipLaunchKernelGGL(k_offsets, dim3(1), dim3(64), 0, st, counts, offsets, tile_start, E);
     hipLaunchKernelGGL(k_place, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, offsets, perm, inv, A, L.nblk);
+    if (timed) dynb::timing_mark(st, dynb::ST_SORT, 0);
     // m4 permute
     hipLaunchKernelGGL(k_permute, dim3((A + 3) / 4), dim3(256), 0, st, xb, perm, xs, A, d, k);
+    if (timed) dynb::timing_mark(st, dynb::ST_PERMUTE, 0);
     // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
     const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
     if (max_mtiles * std::max(nt1, nt2) >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
     hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned(max_mtiles * nt1)), dim3(256), 0, st, xs,
                        static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
+    if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
     hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned(max_mtiles * nt2)), dim3(256), 0, st, hid,
                        static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
+    if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
     // m6 combine
     hipLaunchKernelGGL(k_combine, dim3((T + 3) / 4), dim3(256), 0, st, y, inv, topk_w, static_cast<bf16_t*>(out), T, d, k);
+    if (timed) dynb::timing_mark(st, dynb::ST_COMBINE, 0);
     HIP_TRY(hipGetLastError(), "moe_forward");
     return DYNB_OK;
 }
