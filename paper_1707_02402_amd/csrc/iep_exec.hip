@@ -161,33 +161,76 @@ __device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr)
     return *reinterpret_cast<const bf16x8*>(lds_raw + addr);
 }
 
-// one 3x3 convolution as 36 K-steps of 32 input channels: acc[mt][nt] += W[co, tap, ci] * X[pixel+tap, ci]
+// K-loop shared by the 3x3 convolutions (9 taps x 4 chunks of 32 input channels) and by each half
+// of the 1x1 convolution (centre tap only, 4 chunks):
+//     acc[mt][nt] += W[co, tap, chunk] * X[pixel + tap, chunk]
+// Software pipelined by hand.  The 13 activation fragments of a step live in one of two register
+// sets (xa / xb): while the MFMAs of a step read one set, the LDS reads of the next step fill the
+// other.  Weight fragments sit in a ring of four (indexed by the chunk number) and are fetched from
+// global memory two steps ahead.  The tap loop stays rolled: four steps per iteration return every
+// ring to the same phase at the back edge.
+template <int NT, bool CENTER_ONLY>
+__device__ __forceinline__ void kloop_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
+                                           const bf16_t* (&wrow)[NT])
+{
+    // wrow[nt] points at W[co = n0 + nt*16 + lane%16][tap 0][ci = (lane/16)*8]
+    constexpr int NTAP = CENTER_ONLY ? 1 : 9;
+    bf16x8 xa[mf::MT], xb[mf::MT], wf[4][NT];
+    auto tap_off = [](int tap) -> uint32_t {
+        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t(((tap / 3) * mf::HALO + (tap % 3)) * mf::PIX_BYTES);
+    };
+    auto load_x = [&](bf16x8 (&x)[mf::MT], uint32_t off) {
+#pragma unroll
+        for (int mt = 0; mt < mf::MT; ++mt) x[mt] = lds_read_frag(xaddr[mt] + off);
+    };
+    auto load_w = [&](bf16x8 (&w)[NT], int off) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) w[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + off);
+    };
+    auto mac = [&](const bf16x8 (&x)[mf::MT], const bf16x8 (&w)[NT]) {
+#pragma unroll
+        for (int mt = 0; mt < mf::MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt], x[mt], acc[mt][nt], 0, 0, 0);
+    };
+    load_w(wf[0], 0);
+    load_w(wf[1], 32);
+    load_x(xa, tap_off(0));
+#pragma unroll 1
+    for (int tap = 0; tap < NTAP; ++tap) {
+        const int ntap = tap + 1 < NTAP ? tap + 1 : tap;      // the last prefetch re-reads valid data
+        const uint32_t xo = tap_off(tap), nxo = tap_off(ntap);
+        const int wo = tap * mf::C, nwo = ntap * mf::C;
+        // the scheduler must not sink the prefetches back down to their first use
+        load_w(wf[2], wo + 64);
+        load_x(xb, xo + 64);
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xa, wf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(wf[3], wo + 96);
+        load_x(xa, xo + 128);
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xb, wf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(wf[0], nwo);
+        load_x(xb, xo + 192);
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xa, wf[2]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(wf[1], nwo + 32);
+        load_x(xa, nxo);
+        __builtin_amdgcn_sched_barrier(0);
+        mac(xb, wf[3]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int NT>
 __device__ __forceinline__ void conv3x3_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
                                              const bf16_t* (&wrow)[NT])
 {
-    // wrow[nt] points at W[co = n0 + nt*16 + lane%16][tap 0][ci = (lane/16)*8]
-    bf16x8 wf[2][NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) wf[0][nt] = *reinterpret_cast<const bf16x8*>(wrow[nt]);
-#pragma unroll
-    for (int step = 0; step < 36; ++step) {
-        const int tap = step >> 2, kc = step & 3;
-        const int cur = step & 1, nxt = cur ^ 1;
-        if (step + 1 < 36) {
-            const int woff = ((step + 1) >> 2) * mf::C + ((step + 1) & 3) * 32;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wf[nxt][nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + woff);
-        }
-        const uint32_t xoff = uint32_t(((tap / 3) * mf::HALO + (tap % 3)) * mf::PIX_BYTES + kc * 64);
-#pragma unroll
-        for (int mt = 0; mt < mf::MT; ++mt) {
-            const bf16x8 xf = lds_read_frag(xaddr[mt] + xoff);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[cur][nt], xf, acc[mt][nt], 0, 0, 0);
-        }
-    }
+    kloop_mfma<NT, false>(acc, xaddr, wrow);
 }
 
 // half of the 1x1 convolution over the concatenated arguments: 4 K-steps over the map now in LDS
@@ -195,20 +238,7 @@ template <int NT>
 __device__ __forceinline__ void conv1x1_half_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
                                                   const bf16_t* (&wrow)[NT])
 {
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
-        bf16x8 wf[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + kc * 32);
-        const uint32_t xoff = uint32_t(mf::CENTER + kc * 64);
-#pragma unroll
-        for (int mt = 0; mt < mf::MT; ++mt) {
-            const bf16x8 xf = lds_read_frag(xaddr[mt] + xoff);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf, acc[mt][nt], 0, 0, 0);
-        }
-    }
+    kloop_mfma<NT, true>(acc, xaddr, wrow);
 }
 
 // NPW = nodes per workgroup (1 or 2).  256 threads = 4 waves; a node is shared by 4/NPW waves,
