@@ -23,9 +23,22 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return bf16_t(u >> 16);
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return uint32_t(f32_to_bf16(lo)) | (uint32_t(f32_to_bf16(hi)) << 16);
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// ReLU on a packed bf16 pair: a negative bf16 is a negative int16, so a signed max with 0 clears it
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t p)
+{
+    const i16x2 z = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, p), z));
 }
 
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);

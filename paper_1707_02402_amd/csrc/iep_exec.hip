@@ -132,12 +132,29 @@ constexpr int C = 128;
 constexpr int S = 14;                    // spatial size
 constexpr int P = S * S;                 // 196 pixels
 constexpr int HALO = 16;                 // tile side with zero border
-constexpr int PIX_BYTES = 272;           // 128 channels bf16 + 16 bytes pad (bank spreading)
-constexpr int TILE_BYTES = HALO * HALO * PIX_BYTES;   // 69632
+constexpr int PIX_BYTES = 272;           // 128 channels bf16 + 16 bytes pad: 17 granules of 16 bytes
+// Row pitch in 16-byte granules is 16*17 + 14 = 286 = 14 (mod 16), so that the 16 consecutive
+// raster pixels of one MFMA fragment (which cross a 14-pixel image row) still fall on 16 distinct
+// granules mod 16, i.e. on all 64 LDS banks: pixel (y, x) sits at granule 14 y + x (mod 16).
+constexpr int ROW_BYTES = HALO * PIX_BYTES + 14 * 16;  // 4576
+constexpr int TILE_BYTES = HALO * ROW_BYTES;           // 73216
 constexpr int MT = 13;                   // pixel tiles of 16: 208 >= 196
-constexpr int CENTER = (HALO + 1) * PIX_BYTES;         // (+1,+1) from the top-left tap
+constexpr int CENTER = ROW_BYTES + PIX_BYTES;           // (+1,+1) from the top-left tap
 constexpr int MAP_BYTES = P * C * 2;     // 50176
 }  // namespace mf
+
+// Development aid, compiled in only with -DDYNB_PHASE_CLOCKS: lane 0 of every wave stores the
+// shader clock at the phase boundaries of k_module_mfma into a caller-provided device buffer.
+#ifdef DYNB_PHASE_CLOCKS
+__device__ long long* g_phase_clk = nullptr;      // [workgroup][wave][16]
+#define PHASE(i)                                                                             \
+    do {                                                                                     \
+        if ((threadIdx.x & 63) == 0 && g_phase_clk)                                          \
+            g_phase_clk[(size_t(blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
+    } while (0)
+#else
+#define PHASE(i) do {} while (0)
+#endif
 
 struct MfArgs {
     const dynb_item* items;
@@ -177,7 +194,7 @@ __device__ __forceinline__ void kloop_mfma(f32x4 (&acc)[mf::MT][NT], const uint3
     constexpr int NTAP = CENTER_ONLY ? 1 : 9;
     bf16x8 xa[mf::MT], xb[mf::MT], wf[4][NT];
     auto tap_off = [](int tap) -> uint32_t {
-        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t(((tap / 3) * mf::HALO + (tap % 3)) * mf::PIX_BYTES);
+        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t((tap / 3) * mf::ROW_BYTES + (tap % 3) * mf::PIX_BYTES);
     };
     auto load_x = [&](bf16x8 (&x)[mf::MT], uint32_t off) {
 #pragma unroll
@@ -187,12 +204,18 @@ __device__ __forceinline__ void kloop_mfma(f32x4 (&acc)[mf::MT][NT], const uint3
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) w[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + off);
     };
-    auto mac = [&](const bf16x8 (&x)[mf::MT], const bf16x8 (&w)[NT]) {
+    // One K-step: the MFMAs of pixel tile mt read xc[mt]; the LDS read that fills xn[mt] for the next
+    // step is issued right before them, so LDS traffic is spread evenly under the MFMAs instead of
+    // arriving as a burst of 13 reads.  The fences keep the scheduler from regrouping the pairs.
+    auto step = [&](const bf16x8 (&xc)[mf::MT], bf16x8 (&xn)[mf::MT], uint32_t noff, const bf16x8 (&w)[NT]) {
 #pragma unroll
-        for (int mt = 0; mt < mf::MT; ++mt)
+        for (int mt = 0; mt < mf::MT; ++mt) {
+            xn[mt] = lds_read_frag(xaddr[mt] + noff);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt], x[mt], acc[mt][nt], 0, 0, 0);
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt], xc[mt], acc[mt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     load_w(wf[0], 0);
     load_w(wf[1], 32);
@@ -202,27 +225,18 @@ __device__ __forceinline__ void kloop_mfma(f32x4 (&acc)[mf::MT][NT], const uint3
         const int ntap = tap + 1 < NTAP ? tap + 1 : tap;      // the last prefetch re-reads valid data
         const uint32_t xo = tap_off(tap), nxo = tap_off(ntap);
         const int wo = tap * mf::C, nwo = ntap * mf::C;
-        // the scheduler must not sink the prefetches back down to their first use
         load_w(wf[2], wo + 64);
-        load_x(xb, xo + 64);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xa, wf[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        step(xa, xb, xo + 64, wf[0]);
         load_w(wf[3], wo + 96);
-        load_x(xa, xo + 128);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xb, wf[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        step(xb, xa, xo + 128, wf[1]);
         load_w(wf[0], nwo);
-        load_x(xb, xo + 192);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xa, wf[2]);
-        __builtin_amdgcn_sched_barrier(0);
+        step(xa, xb, xo + 192, wf[2]);
         load_w(wf[1], nwo + 32);
-        load_x(xa, nxo);
         __builtin_amdgcn_sched_barrier(0);
-        mac(xb, wf[3]);
-        __builtin_amdgcn_sched_barrier(0);
+        step(xb, xa, nxo, wf[3]);
     }
 }
 
@@ -260,6 +274,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     const int first = logical * NPW;
     if (first >= a.count) return;
 
+    PHASE(0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int node_local = wave / WPN;
     const bool active = first + node_local < a.count;                 // wave-uniform
@@ -271,12 +286,24 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 
     // ---- gather: zero border once, then the argument map into the centre of the halo tile
     const int tl = tid % NTHR;
+    // all global loads of the map are issued before the first LDS write, so one memory latency is paid
     auto stage = [&](const bf16_t* src) {
+        constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
         const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
-        for (int c = tl; c < P * 16; c += NTHR) {
-            const int p = c >> 4, part = c & 15;
-            const uint32_t addr = tile + uint32_t(((p / S + 1) * HALO + p % S + 1) * PIX_BYTES + part * 16);
-            *reinterpret_cast<u32x4*>(lds_raw + addr) = s4[c];
+        u32x4 tmp[NIT];
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tl + i * NTHR;
+            if (c < P * 16) tmp[i] = s4[c];
+        }
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tl + i * NTHR;
+            if (c < P * 16) {
+                const int p = c >> 4, part = c & 15;
+                const uint32_t addr = tile + uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + part * 16);
+                *reinterpret_cast<u32x4*>(lds_raw + addr) = tmp[i];
+            }
         }
     };
     if (active) {
@@ -286,7 +313,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
             if (q < 16) { row = 0; col = q; }
             else if (q < 32) { row = HALO - 1; col = q - 16; }
             else { row = 1 + ((q - 32) >> 1); col = ((q - 32) & 1) ? HALO - 1 : 0; }
-            *reinterpret_cast<u32x4*>(lds_raw + tile + uint32_t((row * HALO + col) * PIX_BYTES + part * 16)) =
+            *reinterpret_cast<u32x4*>(lds_raw + tile + uint32_t(row * ROW_BYTES + col * PIX_BYTES + part * 16)) =
                 u32x4{0u, 0u, 0u, 0u};
         }
         stage(it.src0 >= 0 ? a.slots + size_t(it.src0) * (P * C) : a.feats + size_t(-1 - it.src0) * (P * C));
@@ -297,7 +324,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int p = min(mt * 16 + r, P - 1);
-        xaddr[mt] = tile + uint32_t(((p / S) * HALO + p % S) * PIX_BYTES + g * 16);
+        xaddr[mt] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + g * 16);
     }
     const int cbase = n0 + g * 4;          // first of this lane's 4 output channels inside tile nt: + nt*16
     f32x4 acc[MT][NT];
@@ -321,15 +348,17 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
                     const uint32_t addr = xaddr[mt] - uint32_t(g * 16) + CENTER + uint32_t((cbase + nt * 16) * 2);
                     const f32x4 v = acc[mt][nt];
                     u32x2 pk;
-                    pk.x = pack_bf16x2(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f));
-                    pk.y = pack_bf16x2(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
+                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
                     *reinterpret_cast<u32x2*>(lds_raw + addr) = pk;
                 }
             }
         }
     };
 
+    PHASE(1);
     __syncthreads();
+    PHASE(2);
 
     // ---- binary functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the same tile
     if (a.any_binary) {                                   // uniform over the launch group
@@ -355,6 +384,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     }
 
     // ---- first conv3x3 + ReLU, result replaces the tile; the old centre values become the residual
+    PHASE(3);
     const bf16_t* wrow[NT];
     if (active) {
 #pragma unroll
@@ -363,7 +393,9 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         init_bias(a.b3a);
         conv3x3_mfma<NT>(acc, xaddr, wrow);
     }
+    PHASE(4);
     __syncthreads();
+    PHASE(5);
     if (active) {
         f32x4 bias2[NT];
 #pragma unroll
@@ -380,8 +412,8 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
                     const u32x2 res = *reinterpret_cast<const u32x2*>(lds_raw + addr);
                     const f32x4 v = acc[mt][nt];
                     u32x2 pk;
-                    pk.x = pack_bf16x2(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f));
-                    pk.y = pack_bf16x2(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
+                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
                     *reinterpret_cast<u32x2*>(lds_raw + addr) = pk;
                     f32x4 nv;
                     nv.x = __uint_as_float(res.x << 16) + bias2[nt].x;
@@ -393,7 +425,9 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
             }
         }
     }
+    PHASE(6);
     __syncthreads();
+    PHASE(7);
 
     // ---- second conv3x3 on top of (residual + bias), ReLU, scatter
     if (active) {
@@ -401,6 +435,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         for (int nt = 0; nt < NT; ++nt)
             wrow[nt] = a.w3b + (size_t(it.type) * C + n0 + nt * 16 + r) * (9 * C) + g * 8;
         conv3x3_mfma<NT>(acc, xaddr, wrow);
+        PHASE(8);
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -410,13 +445,14 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
                 for (int nt = 0; nt < NT; ++nt) {
                     const f32x4 v = acc[mt][nt];
                     u32x2 pk;
-                    pk.x = pack_bf16x2(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f));
-                    pk.y = pack_bf16x2(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
+                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
                     *reinterpret_cast<u32x2*>(dst + size_t(p) * C + cbase + nt * 16) = pk;
                 }
             }
         }
     }
+    PHASE(9);
 }
 
 size_t elt_bytes(int dtype) { return dtype == DYNB_BF16 ? 2 : 4; }
@@ -426,6 +462,14 @@ bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 1
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 }  // namespace
+
+#ifdef DYNB_PHASE_CLOCKS
+extern "C" int dynb_debug_phase_clocks(void* device_buf)
+{
+    long long* p = static_cast<long long*>(device_buf);
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_phase_clk), &p, sizeof(p)) == hipSuccess ? DYNB_OK : DYNB_E_HIP;
+}
+#endif
 
 // Device buffer layout of an uploaded plan: items | leaf-root example ids | arity table
 static size_t plan_items_bytes(const dynb_plan* p) { return align256(p->items.size() * sizeof(dynb_item)); }
