@@ -13,6 +13,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 #include <string>
 
 #include "device_utils.h"
@@ -138,7 +139,6 @@ constexpr int PIX_BYTES = 272;           // 128 channels bf16 + 16 bytes pad: 17
 // granules mod 16, i.e. on all 64 LDS banks: pixel (y, x) sits at granule 14 y + x (mod 16).
 constexpr int ROW_BYTES = HALO * PIX_BYTES + 14 * 16;  // 4576
 constexpr int TILE_BYTES = HALO * ROW_BYTES;           // 73216
-constexpr int MT = 13;                   // pixel tiles of 16: 208 >= 196
 constexpr int CENTER = ROW_BYTES + PIX_BYTES;           // (+1,+1) from the top-left tap
 constexpr int MAP_BYTES = P * C * 2;     // 50176
 }  // namespace mf
@@ -151,6 +151,8 @@ __device__ long long* g_phase_clk = nullptr;      // [workgroup][wave][16]
     do {                                                                                     \
         if ((threadIdx.x & 63) == 0 && g_phase_clk)                                          \
             g_phase_clk[(size_t(blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
+        if ((threadIdx.x & 63) == 0 && g_phase_clk && ((i) == 0 || (i) == 9))                 \
+            g_phase_clk[(size_t(blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + 10 + ((i) != 0)] = wall_clock64(); \
     } while (0)
 #else
 #define PHASE(i) do {} while (0)
@@ -178,92 +180,133 @@ __device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr)
     return *reinterpret_cast<const bf16x8*>(lds_raw + addr);
 }
 
-// K-loop shared by the 3x3 convolutions (9 taps x 4 chunks of 32 input channels) and by each half
-// of the 1x1 convolution (centre tap only, 4 chunks):
-//     acc[mt][nt] += W[co, tap, chunk] * X[pixel + tap, chunk]
-// Software pipelined by hand.  The 13 activation fragments of a step live in one of two register
-// sets (xa / xb): while the MFMAs of a step read one set, the LDS reads of the next step fill the
-// other.  Weight fragments sit in a ring of four (indexed by the chunk number) and are fetched from
-// global memory two steps ahead.  The tap loop stays rolled: four steps per iteration return every
-// ring to the same phase at the back edge.
-template <int NT, bool CENTER_ONLY>
-__device__ __forceinline__ void kloop_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
-                                           const bf16_t* (&wrow)[NT])
+// ---- MFMA tiling ------------------------------------------------------------------------------
+// v_mfma_f32_32x32x16_bf16 is the efficient bf16 instruction of gfx950 (measured: ~2.1 PFLOP/s chip
+// wide, against ~1.5 for the 16x16x32 form), so a convolution is tiled as
+//     D[32 channels][32 pixels] += W[32 channels][16 k] * X[16 k][32 pixels]
+// with the weights as the A operand and the activations as the B operand: a lane then ends up with
+// four runs of four consecutive channels of one pixel, which it can store as 8-byte pieces.
+// 196 pixels make 7 pixel tiles (224 rows, the last 28 are padding).  A wave always owns 64 output
+// channels (2 channel tiles) so that every activation fragment read from LDS feeds two MFMAs; LDS
+// delivers 128 B/clk per CU and would otherwise be the limit.
+//
+// K order.  Within a tap the 128 input channels are consumed in 8 steps of 16; lane half h = lane/32
+// supplies channels h*64 + j*8 .. +7 in step j (any pairing works as long as both operands agree).
+// Weight fragments.  In the caller's [Cout][kh][kw][Cin] layout one fragment load would touch 64
+// different cache lines (32 rows x 2 halves), which makes the vector L1 the bottleneck.  The
+// weights are therefore repacked (k_pack_weights) into fragment order
+//     [function][channel tile 4][tap][step 8][lane 64][8 bf16]
+// so that the 64 lanes of a fragment load read one contiguous kilobyte.
+constexpr int MT7 = 7;
+
+namespace mf {
+constexpr int FRAG = 512;   // elements of one packed weight fragment: 64 lanes x 8 bf16 = 1 KB
+}
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// dst[function][tile][tap][j][lane][i] = src[function][co = tile*32 + rho(lane%32)][tap][ci = (lane/32)*64 + j*8 + i]
+// one thread per 16-byte piece; ntap = 9 for a conv3x3, 2 for the two halves of the conv1x1 over 2C inputs.
+// rho permutes the channels inside a tile: MFMA output row m = 8b + 4h + c (accumulator element 4b + c
+// of lane half h) is given channel 16h + 4b + c, so that the 16 accumulator elements of a lane are 16
+// consecutive channels and leave the kernel as two 16-byte stores.
+__global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int n_types, int ntap)
 {
-    // wrow[nt] points at W[co = n0 + nt*16 + lane%16][tap 0][ci = (lane/16)*8]
-    constexpr int NTAP = CENTER_ONLY ? 1 : 9;
-    bf16x8 xa[mf::MT], xb[mf::MT], wf[4][NT];
-    auto tap_off = [](int tap) -> uint32_t {
-        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t((tap / 3) * mf::ROW_BYTES + (tap % 3) * mf::PIX_BYTES);
-    };
-    auto load_x = [&](bf16x8 (&x)[mf::MT], uint32_t off) {
-#pragma unroll
-        for (int mt = 0; mt < mf::MT; ++mt) x[mt] = lds_read_frag(xaddr[mt] + off);
-    };
-    auto load_w = [&](bf16x8 (&w)[NT], int off) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) w[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + off);
-    };
-    // One K-step: the MFMAs of pixel tile mt read xc[mt]; the LDS read that fills xn[mt] for the next
-    // step is issued right before them, so LDS traffic is spread evenly under the MFMAs instead of
-    // arriving as a burst of 13 reads.  The fences keep the scheduler from regrouping the pairs.
-    auto step = [&](const bf16x8 (&xc)[mf::MT], bf16x8 (&xn)[mf::MT], uint32_t noff, const bf16x8 (&w)[NT]) {
-#pragma unroll
-        for (int mt = 0; mt < mf::MT; ++mt) {
-            xn[mt] = lds_read_frag(xaddr[mt] + noff);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt], xc[mt], acc[mt][nt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    load_w(wf[0], 0);
-    load_w(wf[1], 32);
-    load_x(xa, tap_off(0));
-#pragma unroll 1
-    for (int tap = 0; tap < NTAP; ++tap) {
-        const int ntap = tap + 1 < NTAP ? tap + 1 : tap;      // the last prefetch re-reads valid data
-        const uint32_t xo = tap_off(tap), nxo = tap_off(ntap);
-        const int wo = tap * mf::C, nwo = ntap * mf::C;
-        load_w(wf[2], wo + 64);
-        __builtin_amdgcn_sched_barrier(0);
-        step(xa, xb, xo + 64, wf[0]);
-        load_w(wf[3], wo + 96);
-        __builtin_amdgcn_sched_barrier(0);
-        step(xb, xa, xo + 128, wf[1]);
-        load_w(wf[0], nwo);
-        __builtin_amdgcn_sched_barrier(0);
-        step(xa, xb, xo + 192, wf[2]);
-        load_w(wf[1], nwo + 32);
-        __builtin_amdgcn_sched_barrier(0);
-        step(xb, xa, nxo, wf[3]);
+    const size_t total = size_t(n_types) * 4 * ntap * 8 * 64;
+    for (size_t q = size_t(blockIdx.x) * blockDim.x + threadIdx.x; q < total; q += size_t(gridDim.x) * blockDim.x) {
+        const int lane = int(q & 63), j = int((q >> 6) & 7);
+        const size_t rest = q >> 9;
+        const int tap = int(rest % ntap), tile = int((rest / ntap) & 3);
+        const size_t type = rest / (size_t(ntap) * 4);
+        const int m = lane & 31;
+        const int co = tile * 32 + ((m >> 2) & 1) * 16 + (m >> 3) * 4 + (m & 3), ci0 = (lane >> 5) * 64 + j * 8;
+        dst[q] = src[(((type * 128 + co) * ntap + tap) * 128 + ci0) >> 3];
     }
 }
 
-template <int NT>
-__device__ __forceinline__ void conv3x3_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
-                                             const bf16_t* (&wrow)[NT])
+// acc[t][nt] += W * X over one 3x3 convolution (9 taps) or, CENTER_ONLY, over 128 channels of the
+// centre tap (one half of the 1x1 convolution).  Software pipelined by hand: the activation
+// fragments live in a ring of four register sets (one per step), the LDS reads that fill the set of
+// the step after next are interleaved one by one with the MFMAs of the current step, and the weight
+// fragments of all 8 steps
+// of a tap sit in registers: each is re-fetched from global memory one step after its last use,
+// i.e. 7 steps (> 1800 clocks) ahead of its next use.  Scheduler fences keep that order.
+template <int MTW, bool CENTER_ONLY>
+__device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t (&xaddr)[MTW], int mcount,
+                                           const bf16_t* (&wrow)[2])
 {
-    kloop_mfma<NT, false>(acc, xaddr, wrow);
+    // wrow[nt] points at this lane's 8 values of the first fragment of channel tile nt in the packed
+    // weights; fragment (tap, j) follows at (tap*8 + j) * 512 elements
+    constexpr int NTAP = CENTER_ONLY ? 1 : 9;
+    bf16x8 x[4][MTW], wf[8][2];
+    auto tap_off = [](int tap) -> uint32_t {
+        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t((tap / 3) * mf::ROW_BYTES + (tap % 3) * mf::PIX_BYTES);
+    };
+    auto load_w = [&](bf16x8 (&w)[2], int off) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) w[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + off);
+    };
+    // One K-step: the MFMAs of pixel tile t read xc[t]; the LDS read that fills xn[t] for the step
+    // after next is issued right before them, so LDS traffic is spread evenly under the MFMAs.
+    // The weight slot used by the previous step is refilled after the first pixel tile: issuing that
+    // load directly behind the MFMAs that still read the slot would stall the wave until they retire.
+    auto step = [&](const bf16x8 (&xc)[MTW], bf16x8 (&xn)[MTW], uint32_t noff, const bf16x8 (&w)[2],
+                    bf16x8 (&wrefill)[2], int refill_off) {
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            if (t < mcount) {
+                xn[t] = lds_read_frag(xaddr[t] + noff);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[nt], xc[t], acc[t][nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (t == 0) {
+                load_w(wrefill, refill_off);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // The prologue issues its loads in exactly the order the loop body does (fences again), so that
+    // the wait counts the compiler derives for the loop entry and for the back edge agree and stay
+    // as loose as the ring allows.  Slot 7 is filled by the first step of the loop.
+#pragma unroll
+    for (int j = 0; j < 7; ++j) {
+        load_w(wf[j], j * mf::FRAG);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            if (t < mcount) x[jj][t] = lds_read_frag(xaddr[t] + tap_off(0) + jj * 16);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll 1
+    for (int tap = 0; tap < NTAP; ++tap) {
+        const int ntap = tap + 1 < NTAP ? tap + 1 : tap;      // the last prefetches re-read valid data
+        const uint32_t xo = tap_off(tap), nxo = tap_off(ntap);
+        const int wo = tap * 8 * mf::FRAG, nwo = ntap * 8 * mf::FRAG;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            step(x[j & 3], x[(j + 2) & 3], j + 2 < 8 ? xo + (j + 2) * 16 : nxo + (j + 2 - 8) * 16, wf[j],
+                 wf[(j + 7) & 7], j == 0 ? wo + 7 * mf::FRAG : nwo + (j - 1) * mf::FRAG);
+    }
 }
 
-// half of the 1x1 convolution over the concatenated arguments: 4 K-steps over the map now in LDS
-template <int NT>
-__device__ __forceinline__ void conv1x1_half_mfma(f32x4 (&acc)[mf::MT][NT], const uint32_t (&xaddr)[mf::MT],
-                                                  const bf16_t* (&wrow)[NT])
-{
-    kloop_mfma<NT, true>(acc, xaddr, wrow);
-}
-
-// NPW = nodes per workgroup (1 or 2).  256 threads = 4 waves; a node is shared by 4/NPW waves,
-// each owning 128/(4/NPW) output channels for all 196 pixels.
-template <int NPW>
+// WM = waves along the pixel dimension of one node.
+//   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles
+//           each): best throughput, used for wide launch groups.
+//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 4 or 3 pixel tiles): about half
+//           the latency per node, used when the launch group has fewer nodes than the chip has CUs.
+template <int WM>
 __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 {
     using namespace mf;
-    constexpr int WPN = 4 / NPW;          // waves per node
-    constexpr int NT = 8 / WPN;           // 16-channel tiles per wave
-    constexpr int NTHR = 64 * WPN;        // threads that stage one node
+    constexpr int NPW = (WM == 1) ? 2 : 1;    // nodes per workgroup
+    constexpr int WPN = 4 / NPW;              // waves per node
+    constexpr int MTW = (WM == 1) ? 7 : 4;    // pixel tiles per wave (upper bound)
+    constexpr int NTHR = 64 * WPN;            // threads that stage one node
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
     // Workgroup -> position in the launch group.  Consecutive workgroup ids land on different
@@ -276,17 +319,19 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 
     PHASE(0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int node_local = wave / WPN;
+    const int node_local = wave / WPN, wi = wave % WPN;
     const bool active = first + node_local < a.count;                 // wave-uniform
     const dynb_item it = a.items[active ? first + node_local : first];
     const bool binary = active && a.arity[it.type] == 2;
     const uint32_t tile = uint32_t(node_local) * TILE_BYTES;
-    const int r = lane & 15, g = lane >> 4;
-    const int n0 = (wave % WPN) * NT * 16;
+    const int r = lane & 31, h = lane >> 5;
+    const int n0 = (wi & 1) * 64;             // first output channel of this wave
+    const int m0 = (wi >> 1) * MTW;           // first pixel tile of this wave
+    const int mcount = (WM == 1) ? MT7 : (MT7 - m0 < MTW ? MT7 - m0 : MTW);
 
-    // ---- gather: zero border once, then the argument map into the centre of the halo tile
-    const int tl = tid % NTHR;
+    // ---- gather: zero border once, then the argument map into the centre of the halo tile;
     // all global loads of the map are issued before the first LDS write, so one memory latency is paid
+    const int tl = tid % NTHR;
     auto stage = [&](const bf16_t* src) {
         constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
         const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
@@ -319,41 +364,56 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         stage(it.src0 >= 0 ? a.slots + size_t(it.src0) * (P * C) : a.feats + size_t(-1 - it.src0) * (P * C));
     }
 
-    // per-lane LDS addresses: top-left tap of the pixel this lane feeds to the MFMA B operand
-    uint32_t xaddr[MT];
+    // per-lane LDS addresses: top-left tap of the pixel this lane feeds to the MFMA B operand,
+    // already advanced to this lane half's 64-channel run
+    uint32_t xaddr[MTW];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int p = min(mt * 16 + r, P - 1);
-        xaddr[mt] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + g * 16);
+    for (int t = 0; t < MTW; ++t) {
+        const int p = min((m0 + t) * 32 + r, P - 1);
+        xaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
     }
-    const int cbase = n0 + g * 4;          // first of this lane's 4 output channels inside tile nt: + nt*16
-    f32x4 acc[MT][NT];
+    // this lane's 16 accumulator elements of channel tile nt are channels n0 + nt*32 + 16*h + (0..15)
+    // (the packed weights carry the matching row permutation)
+    const int cbase = n0 + 16 * h;
+    f32x16 acc[MTW][2];
 
-    auto init_bias = [&](const float* b) {
+    auto init_bias = [&](const float* bias) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (b) v = *reinterpret_cast<const f32x4*>(b + size_t(it.type) * C + cbase + nt * 16);
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = v;
-        }
+            for (int b = 0; b < 4; ++b) {
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + cbase + nt * 32 + b * 4);
+#pragma unroll
+                for (int t = 0; t < MTW; ++t) {
+                    acc[t][nt][4 * b + 0] = v.x; acc[t][nt][4 * b + 1] = v.y;
+                    acc[t][nt][4 * b + 2] = v.z; acc[t][nt][4 * b + 3] = v.w;
+                }
+            }
+    };
+    // byte address of this lane's centre pixel of tile t (channel 0)
+    auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
+    // ReLU(acc[t][nt][8q .. 8q+7]) as 8 packed bf16 (q = 0, 1)
+    auto packed = [&](int t, int nt, int q) -> u32x4 {
+        u32x4 pk;
+        pk.x = relu_bf16x2(pack_bf16x2(acc[t][nt][8 * q + 0], acc[t][nt][8 * q + 1]));
+        pk.y = relu_bf16x2(pack_bf16x2(acc[t][nt][8 * q + 2], acc[t][nt][8 * q + 3]));
+        pk.z = relu_bf16x2(pack_bf16x2(acc[t][nt][8 * q + 4], acc[t][nt][8 * q + 5]));
+        pk.w = relu_bf16x2(pack_bf16x2(acc[t][nt][8 * q + 6], acc[t][nt][8 * q + 7]));
+        return pk;
     };
     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
     auto write_tile = [&]() {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (mt * 16 + r < P) {
+        for (int t = 0; t < MTW; ++t)
+            if (t < mcount && (m0 + t) * 32 + r < P) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const uint32_t addr = xaddr[mt] - uint32_t(g * 16) + CENTER + uint32_t((cbase + nt * 16) * 2);
-                    const f32x4 v = acc[mt][nt];
-                    u32x2 pk;
-                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
-                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
-                    *reinterpret_cast<u32x2*>(lds_raw + addr) = pk;
-                }
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((cbase + nt * 32 + q * 8) * 2)) =
+                            packed(t, nt, q);
             }
-        }
     };
 
     PHASE(1);
@@ -362,21 +422,21 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 
     // ---- binary functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the same tile
     if (a.any_binary) {                                   // uniform over the launch group
-        const bf16_t* w1row[NT];
+        const bf16_t* w1row[2];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            w1row[nt] = a.w1 + (size_t(it.type) * C + n0 + nt * 16 + r) * (2 * C) + g * 8;
+        for (int nt = 0; nt < 2; ++nt)
+            w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
         if (binary) {
             init_bias(a.b1);
-            conv1x1_half_mfma<NT>(acc, xaddr, w1row);
+            kloop_mfma<MTW, true>(acc, xaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
         __syncthreads();
         if (binary) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) w1row[nt] += C;
-            conv1x1_half_mfma<NT>(acc, xaddr, w1row);
+            for (int nt = 0; nt < 2; ++nt) w1row[nt] += 8 * FRAG;
+            kloop_mfma<MTW, true>(acc, xaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) write_tile();
@@ -385,45 +445,44 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 
     // ---- first conv3x3 + ReLU, result replaces the tile; the old centre values become the residual
     PHASE(3);
-    const bf16_t* wrow[NT];
+    const bf16_t* wrow[2];
     if (active) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            wrow[nt] = a.w3a + (size_t(it.type) * C + n0 + nt * 16 + r) * (9 * C) + g * 8;
+        for (int nt = 0; nt < 2; ++nt)
+            wrow[nt] = a.w3a + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
         init_bias(a.b3a);
-        conv3x3_mfma<NT>(acc, xaddr, wrow);
+        kloop_mfma<MTW, false>(acc, xaddr, mcount, wrow);
     }
     PHASE(4);
     __syncthreads();
     PHASE(5);
     if (active) {
-        f32x4 bias2[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            bias2[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (a.b3b) bias2[nt] = *reinterpret_cast<const f32x4*>(a.b3b + size_t(it.type) * C + cbase + nt * 16);
-        }
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (mt * 16 + r < P) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const uint32_t addr = xaddr[mt] - uint32_t(g * 16) + CENTER + uint32_t((cbase + nt * 16) * 2);
-                    const u32x2 res = *reinterpret_cast<const u32x2*>(lds_raw + addr);
-                    const f32x4 v = acc[mt][nt];
-                    u32x2 pk;
-                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
-                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
-                    *reinterpret_cast<u32x2*>(lds_raw + addr) = pk;
-                    f32x4 nv;
-                    nv.x = __uint_as_float(res.x << 16) + bias2[nt].x;
-                    nv.y = __uint_as_float(res.x & 0xffff0000u) + bias2[nt].y;
-                    nv.z = __uint_as_float(res.y << 16) + bias2[nt].z;
-                    nv.w = __uint_as_float(res.y & 0xffff0000u) + bias2[nt].w;
-                    acc[mt][nt] = nv;
+            for (int q = 0; q < 2; ++q) {
+                f32x4 blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
+                if (a.b3b) {
+                    const float* bp = a.b3b + size_t(it.type) * C + cbase + nt * 32 + q * 8;
+                    blo = *reinterpret_cast<const f32x4*>(bp);
+                    bhi = *reinterpret_cast<const f32x4*>(bp + 4);
                 }
+#pragma unroll
+                for (int t = 0; t < MTW; ++t)
+                    if (t < mcount && (m0 + t) * 32 + r < P) {
+                        const uint32_t addr = centre(t) + uint32_t((cbase + nt * 32 + q * 8) * 2);
+                        const u32x4 res = *reinterpret_cast<const u32x4*>(lds_raw + addr);
+                        *reinterpret_cast<u32x4*>(lds_raw + addr) = packed(t, nt, q);
+                        acc[t][nt][8 * q + 0] = __uint_as_float(res.x << 16) + blo.x;
+                        acc[t][nt][8 * q + 1] = __uint_as_float(res.x & 0xffff0000u) + blo.y;
+                        acc[t][nt][8 * q + 2] = __uint_as_float(res.y << 16) + blo.z;
+                        acc[t][nt][8 * q + 3] = __uint_as_float(res.y & 0xffff0000u) + blo.w;
+                        acc[t][nt][8 * q + 4] = __uint_as_float(res.z << 16) + bhi.x;
+                        acc[t][nt][8 * q + 5] = __uint_as_float(res.z & 0xffff0000u) + bhi.y;
+                        acc[t][nt][8 * q + 6] = __uint_as_float(res.w << 16) + bhi.z;
+                        acc[t][nt][8 * q + 7] = __uint_as_float(res.w & 0xffff0000u) + bhi.w;
+                    }
             }
-        }
     }
     PHASE(6);
     __syncthreads();
@@ -432,23 +491,20 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     // ---- second conv3x3 on top of (residual + bias), ReLU, scatter
     if (active) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            wrow[nt] = a.w3b + (size_t(it.type) * C + n0 + nt * 16 + r) * (9 * C) + g * 8;
-        conv3x3_mfma<NT>(acc, xaddr, wrow);
+        for (int nt = 0; nt < 2; ++nt)
+            wrow[nt] = a.w3b + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
+        kloop_mfma<MTW, false>(acc, xaddr, mcount, wrow);
         PHASE(8);
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int p = mt * 16 + r;
-            if (p < P) {
+        for (int t = 0; t < MTW; ++t) {
+            const int p = (m0 + t) * 32 + r;
+            if (t < mcount && p < P) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const f32x4 v = acc[mt][nt];
-                    u32x2 pk;
-                    pk.x = relu_bf16x2(pack_bf16x2(v.x, v.y));
-                    pk.y = relu_bf16x2(pack_bf16x2(v.z, v.w));
-                    *reinterpret_cast<u32x2*>(dst + size_t(p) * C + cbase + nt * 16) = pk;
-                }
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        *reinterpret_cast<u32x4*>(dst + size_t(p) * C + cbase + nt * 32 + q * 8) = packed(t, nt, q);
             }
         }
     }
@@ -460,6 +516,9 @@ size_t elt_bytes(int dtype) { return dtype == DYNB_BF16 ? 2 : 4; }
 bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 128 && s->H == 14 && s->W == 14; }
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// packed copies of w3a, w3b (9 taps each) and w1 (2 halves), 128 x 128 bf16 per tap and function
+size_t packed_weight_bytes(int n_types) { return size_t(n_types) * (9 + 9 + 2) * 128 * 128 * 2; }
 
 }  // namespace
 
@@ -510,7 +569,9 @@ extern "C" size_t dynbatch_workspace_bytes(const dynb_plan* p, const dynb_shape*
     const size_t map = size_t(s->C) * s->H * s->W * elt_bytes(s->dtype);    // slots are packed
     size_t n = size_t(p->n_slots);
     if (!fast_shape(s)) n += 2 * size_t(p->max_launch);                       // u and mid of one launch group
-    return std::max<size_t>(align256(n * map), 256);
+    size_t bytes = align256(n * map);
+    if (fast_shape(s)) bytes += packed_weight_bytes(p->n_types);              // weights in MFMA fragment order
+    return std::max<size_t>(bytes, 256);
 }
 
 template <typename T>
@@ -559,12 +620,12 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
     if (!(attr_set.load() >> (dev & 63) & 1)) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
-                "hipFuncSetAttribute(k_module_mfma<1>)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<2>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<2>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<1>)");
         attr_set.fetch_or(uint64_t(1) << (dev & 63));
     }
     const char* d = static_cast<const char*>(p->dev_buf);
@@ -573,23 +634,44 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.feats = static_cast<const bf16_t*>(feats);
     a.out = static_cast<bf16_t*>(out);
     a.slots = reinterpret_cast<bf16_t*>(ws);
-    a.w1 = static_cast<const bf16_t*>(w->w1); a.b1 = w->b1;
-    a.w3a = static_cast<const bf16_t*>(w->w3a); a.b3a = w->b3a;
-    a.w3b = static_cast<const bf16_t*>(w->w3b); a.b3b = w->b3b;
+    // repack the weights into fragment order behind the slots (about 0.6 MB per function)
+    const size_t tap_bytes = size_t(p->n_types) * 128 * 128 * 2;
+    char* pk = ws + align256(size_t(p->n_slots) * mf::P * mf::C * 2);
+    bf16_t* pk3a = reinterpret_cast<bf16_t*>(pk);
+    bf16_t* pk3b = reinterpret_cast<bf16_t*>(pk + 9 * tap_bytes);
+    bf16_t* pk1 = reinterpret_cast<bf16_t*>(pk + 18 * tap_bytes);
+    {
+        const unsigned g9 = unsigned(std::min<size_t>((size_t(p->n_types) * 4 * 9 * 512 + 255) / 256, 4096));
+        hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3a),
+                           reinterpret_cast<u32x4*>(pk3a), p->n_types, 9);
+        hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3b),
+                           reinterpret_cast<u32x4*>(pk3b), p->n_types, 9);
+        if (w->w1)
+            hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w1),
+                               reinterpret_cast<u32x4*>(pk1), p->n_types, 2);
+    }
+    a.w1 = pk1; a.b1 = w->b1;
+    a.w3a = pk3a; a.b3a = w->b3a;
+    a.w3b = pk3b; a.b3b = w->b3b;
     const bool timed = dynb::timing_on();
     for (const dynb_launch& l : p->launches) {
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
         a.any_binary = 0;
         for (int i = 0; i < l.count; ++i) a.any_binary |= (p->arity[p->items[l.start + i].type] == 2);
-        // two nodes per workgroup once the launch group has more nodes than the chip has CUs twice over
-        const int npw = (l.count > 512) ? 2 : 1;
+        // one node per workgroup (lower latency) while the launch group fits the chip's 256 CUs,
+        // two nodes per workgroup (higher throughput per CU) beyond that
+        int wm = (l.count <= 256) ? 2 : 1;
+#ifdef DYNB_PHASE_CLOCKS
+        if (const char* f = getenv("DYNB_FORCE_WM")) wm = atoi(f);
+#endif
+        const int npw = (wm == 1) ? 2 : 1;
         const int nwg = (l.count + npw - 1) / npw;
         const unsigned grid = unsigned((nwg + 7) / 8 * 8);
-        if (npw == 1)
-            hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        if (wm == 2)
+            hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else
-            hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
+            hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
         if (timed) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
     HIP_TRY(hipGetLastError(), "dynbatch_execute(mfma kernels)");
