@@ -284,17 +284,110 @@ __global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, c
 }
 
 // ------------------------------------------------------------------------------------------ grouped GEMM
+// Tile body: out[row0 .. row0+rows)[nb .. nb+128) = act(in[rows][K] . We[n][K]^T), ML = live 16-row tiles.
+//
+// Operands go through LDS in K-chunks of 64.  Loading MFMA fragments straight from global memory
+// makes every lane of a load touch its own 16 bytes of a different row, and the vector L1 then
+// retires about one lane per clock (measured: ~16 B/clk per CU, which capped this kernel at 2 ms
+// per layer).  Staged loads instead let 8 neighbouring lanes read one row's 128 contiguous bytes;
+// the fragments are then cut out of LDS with ds_read_b128 (row pitch 144 bytes, conflict free).
+// The next chunk is fetched into registers while the current one is multiplied, so with 4-5
+// workgroups per CU about 100 KB of weight reads stay in flight per CU.
+constexpr int KC = 64;                 // K-chunk
+constexpr int LDP = KC + 8;            // LDS row pitch in elements (144 bytes)
+
+template <bool RELU, int ML>
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const bf16_t* __restrict__ We,
+                                          bf16_t* __restrict__ out, int row0, int rows, int nb, int N, int K,
+                                          bf16_t* Ws, bf16_t* Xs)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int part = tid & 7;                      // 16-byte piece of a 128-byte chunk row
+    // staging assignments: 4 weight rows and (rows up to 64) 2 activation rows per thread
+    const bf16_t* wsrc[4];
+    const bf16_t* xsrc[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wsrc[i] = We + size_t(min(nb + (tid >> 3) + i * 32, N - 1)) * K + part * 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) xsrc[i] = in + size_t(row0 + min((tid >> 3) + i * 32, rows - 1)) * K + part * 8;
+    const bool x_needed[2] = {true, ML > 2};       // rows 32..63 only exist in 4-tile bodies
+    u32x4 wreg[4], xreg[2];
+    auto fetch = [&](int kc) {
+        const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 32: the last chunk may be half empty
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            wreg[i] = inside ? *reinterpret_cast<const u32x4*>(wsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (x_needed[i])
+                xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
+    };
+    f32x4 acc[ML][2];
+#pragma unroll
+    for (int mt = 0; mt < ML; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
+    const int nchunk = (K + KC - 1) / KC;
+    fetch(0);
+    for (int kc = 0; kc < nchunk; ++kc) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<u32x4*>(Ws + ((tid >> 3) + i * 32) * LDP + part * 8) = wreg[i];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (x_needed[i]) *reinterpret_cast<u32x4*>(Xs + ((tid >> 3) + i * 32) * LDP + part * 8) = xreg[i];
+        __syncthreads();
+        if (kc + 1 < nchunk) fetch(kc + 1);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            bf16x8 wf[2], xf[ML];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                wf[nt] = *reinterpret_cast<const bf16x8*>(Ws + (wave * 32 + nt * 16 + r) * LDP + kk * 32 + g * 8);
+#pragma unroll
+            for (int mt = 0; mt < ML; ++mt)
+                xf[mt] = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * LDP + kk * 32 + g * 8);
+#pragma unroll
+            for (int mt = 0; mt < ML; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[mt], acc[mt][nt], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // lane holds features n0 + nt*16 + g*4 .. +3 of row row0 + mt*16 + r
+    const int n0 = nb + wave * 32;
+#pragma unroll
+    for (int mt = 0; mt < ML; ++mt) {
+        const int lr = mt * 16 + r;
+        if (lr >= rows) continue;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int n = n0 + nt * 16 + g * 4;
+            if (n >= N) continue;
+            const f32x4 v = acc[mt][nt];
+            u32x2 pk;
+            pk.x = pack_bf16x2(v.x, v.y);
+            pk.y = pack_bf16x2(v.z, v.w);
+            if (RELU) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }
+            *reinterpret_cast<u32x2*>(out + size_t(row0 + lr) * N + n) = pk;
+        }
+    }
+}
+
 // out[row][n] = act( sum_k in[row][k] * W[e][n][k] ) for the rows of expert e.
 // One workgroup = one (row tile of <= 64 rows inside one group, 128 output features) pair; a group's
 // tiles are found from tile_start (prefix sum of ceil(count/64)), so ragged and empty groups cost
-// nothing beyond their real rows.  4 waves split the 128 features; inside a wave only the live
-// 16-row sub-tiles are multiplied.
+// nothing beyond their real rows.  4 waves split the 128 features; only the live 16-row sub-tiles
+// are multiplied.  N must be a multiple of 4 (it is: d and h are multiples of 32).
 template <bool RELU>
 __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ offsets,
                                                       const int32_t* __restrict__ tile_start, int E, int N, int K,
                                                       int n_tiles_n)
 {
+    __shared__ __attribute__((aligned(16))) bf16_t Ws[TN * LDP];
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[TM * LDP];
     const int mtile = blockIdx.x / n_tiles_n;
     const int ntile = blockIdx.x % n_tiles_n;
     if (mtile >= tile_start[E]) return;
@@ -307,51 +400,11 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__
     const int row0 = offsets[e] + (mtile - tile_start[e]) * TM;
     const int rows = min(TM, offsets[e + 1] - row0);
     const int mlive = (rows + 15) >> 4;
-
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
-    const int n0 = ntile * TN + wave * 32;
-    if (n0 >= N) return;
-    const bf16_t* wr[2];
-    const bf16_t* ar[4];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) wr[nt] = W + (size_t(e) * N + min(n0 + nt * 16 + r, N - 1)) * K + g * 8;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) ar[mt] = in + size_t(row0 + min(mt * 16 + r, rows - 1)) * K + g * 8;
-    f32x4 acc[4][2];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
-    for (int k0 = 0; k0 < K; k0 += 32) {
-        bf16x8 wf[2];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) wf[nt] = ldg_frag(wr[nt] + k0);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-            if (mt < mlive) {
-                const bf16x8 af = ldg_frag(ar[mt] + k0);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], af, acc[mt][nt], 0, 0, 0);
-            }
-    }
-    // lane holds features n0 + nt*16 + g*4 .. +3 of row row0 + mt*16 + r
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int lr = mt * 16 + r;
-        if (lr >= rows) continue;
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int n = n0 + nt * 16 + g * 4;
-            if (n >= N) continue;
-            f32x4 v = acc[mt][nt];
-            if (RELU) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-            u32x2 pk;
-            pk.x = pack_bf16x2(v.x, v.y);
-            pk.y = pack_bf16x2(v.z, v.w);
-            *reinterpret_cast<u32x2*>(out + size_t(row0 + lr) * N + n) = pk;
-        }
-    }
+    const bf16_t* We = W + size_t(e) * N * K;
+    const int nb = ntile * TN;
+    if (mlive <= 1) gemm_tile<RELU, 1>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
+    else if (mlive == 2) gemm_tile<RELU, 2>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
+    else gemm_tile<RELU, 4>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
 }
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
