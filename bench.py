@@ -56,6 +56,13 @@ def main():
     K, Wm = args.steps, args.warmup
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
 
+    # one plain 1 GiB device-to-device copy: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
+    cal_src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     # ------------------------------------------------------------------ program-tree engine
     w = getattr(iep, args.iep_config)()
     weights = U.iep_weights_dev(w)
@@ -214,6 +221,23 @@ def main():
             cpu["moe"] = {"value": round(len(rows) / dt, 2), "unit": "tokens/s", "cores": 1,
                           "sample": f"expert+combine stage of 48 of {m.T} tokens, one thread, {dt:.1f} s"}
 
+    # HBM-side bytes per launch as measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): counters
+    # cannot be read from inside this process, so the committed measurement is quoted
+    traffic = None
+    moe_traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath) and args.iep_config == "config2":
+        tj = json.load(open(tpath))
+        traffic = round(tj["k_module_mfma"]["bytes_per_launch"])
+        if args.moe_config == "config4":
+            moe_traffic = {k_: round(v["fetch_bytes"] + v["write_bytes"]) for k_, v in tj["moe"].items()}
+    for r_ in moe_roof:
+        key = r_["kernel"].split(" ")[0]
+        if key == "k_grouped_gemm" and "k_grouped_gemm<true>" in moe_traffic:
+            r_["traffic"] = moe_traffic["k_grouped_gemm<true>"] + moe_traffic["k_grouped_gemm<false>"]
+        elif key in moe_traffic:
+            r_["traffic"] = moe_traffic[key]
+
     res = {
         "metric": "module_evals_per_sec", "value": round(n_evals / iep_ms * 1e3, 1), "unit": "module_evals/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(iep_ms, 4), "higher_is_better": True,
@@ -225,7 +249,7 @@ def main():
         "execute_only_module_evals_per_sec": round(n_evals / exec_ms * 1e3, 1),
         "roofline": {"kernel": "k_module_mfma", "bound": "mfma", "achieved": round(achieved_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "launches_per_step": launch_n, "avg_launch_us": round(avg_launch_us, 2),
+                     "traffic": traffic, "launches_per_step": launch_n, "avg_launch_us": round(avg_launch_us, 2),
                      "flops_per_step": flops_step},
         "rooflines_other": moe_roof, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
         "paper_context": "paper reports ratios only: >14x cell execution (IEP, GTX 1080 Ti), up to 1000x (MoE, 11 GB card)",
