@@ -7,7 +7,7 @@
 //   top-k     k largest per token (ties -> lower expert), softmax        one wave per token
 //   group     stable counting sort of the T*k uses by expert             rank-by-prefix-sum, no
 //                                                                        order-dependent atomics
-//   permute   xs[pos] = x[perm[pos] / k]                                  HBM-bound copy
+//   permute   xs[inv[t*k+j]] = x[t]  (= xs[pos] = x[perm[pos] / k])       HBM-bound scatter
 //   experts   hid = ReLU(xs W1_e^T), y = hid W2_e^T per group             grouped MFMA GEMM, ragged
 //                                                                        and empty groups allowed
 //   combine   out[t] = sum_j w[t][j] * y[inv[t*k+j]]                      HBM-bound, fixed order
@@ -234,17 +234,37 @@ __global__ __launch_bounds__(SORT_BLOCK) void k_place(const int32_t* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------ permute / combine
-// One wave per sorted row; d is a multiple of 8 (16-byte chunks).
-__global__ __launch_bounds__(256) void k_permute(const bf16_t* __restrict__ x, const int32_t* __restrict__ perm,
-                                                 bf16_t* __restrict__ xs, int A, int d, int k)
+// xs[inv[t*k + j]] = x[t] for j < k: one wave per token reads the row once and scatters it to the
+// token's k places in the expert-sorted order (reading by sorted position instead would fetch every
+// token row k times, since a token's uses sit in k different groups).  d is a multiple of 8.
+__global__ __launch_bounds__(256) void k_permute(const bf16_t* __restrict__ x, const int32_t* __restrict__ inv,
+                                                 bf16_t* __restrict__ xs, int T, int d, int k)
 {
     const int lane = threadIdx.x & 63;
-    const int pos = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (pos >= A) return;
-    const int t = perm[pos] / k;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int pos[MAX_K];
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) pos[j] = j < k ? inv[size_t(t) * k + j] : 0;
     const u32x4* src = reinterpret_cast<const u32x4*>(x + size_t(t) * d);
-    u32x4* dst = reinterpret_cast<u32x4*>(xs + size_t(pos) * d);
-    for (int c = lane; c < d / 8; c += 64) dst[c] = src[c];
+    for (int c0 = 0; c0 < d / 8; c0 += 256) {
+        u32x4 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = c0 + i * 64 + lane;
+            if (c < d / 8) v[i] = src[c];
+        }
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j)
+            if (j < k) {
+                u32x4* dst = reinterpret_cast<u32x4*>(xs + size_t(pos[j]) * d);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = c0 + i * 64 + lane;
+                    if (c < d / 8) dst[c] = v[i];
+                }
+            }
+    }
 }
 
 __global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, const int32_t* __restrict__ inv,
@@ -388,8 +408,13 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__
 {
     __shared__ __attribute__((aligned(16))) bf16_t Ws[TN * LDP];
     __shared__ __attribute__((aligned(16))) bf16_t Xs[TM * LDP];
-    const int mtile = blockIdx.x / n_tiles_n;
-    const int ntile = blockIdx.x % n_tiles_n;
+    // Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2).  Keep the
+    // feature tiles of one row tile, which all read the same activation rows, on one XCD so that they
+    // share its L2 instead of fetching the rows eight times.
+    // Row tile m goes to XCD m % 8, so live and surplus row tiles are spread evenly over the XCDs.
+    const int slot = blockIdx.x >> 3;
+    const int mtile = (slot / n_tiles_n) * 8 + (blockIdx.x & 7);
+    const int ntile = slot % n_tiles_n;
     if (mtile >= tile_start[E]) return;
     int lo = 0, hi = E;                          // largest e with tile_start[e] <= mtile
     while (hi - lo > 1) {
@@ -509,16 +534,16 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
     hipLaunchKernelGGL(k_place, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, offsets, perm, inv, A, L.nblk);
     if (timed) dynb::timing_mark(st, dynb::ST_SORT, 0);
     // m4 permute
-    hipLaunchKernelGGL(k_permute, dim3((A + 3) / 4), dim3(256), 0, st, xb, perm, xs, A, d, k);
+    hipLaunchKernelGGL(k_permute, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv, xs, T, d, k);
     if (timed) dynb::timing_mark(st, dynb::ST_PERMUTE, 0);
     // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
     const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
     if (max_mtiles * std::max(nt1, nt2) >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
-    hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned(max_mtiles * nt1)), dim3(256), 0, st, xs,
+    hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt1)), dim3(256), 0, st, xs,
                        static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
     if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
-    hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned(max_mtiles * nt2)), dim3(256), 0, st, hid,
+    hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt2)), dim3(256), 0, st, hid,
                        static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
     if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
     // m6 combine
