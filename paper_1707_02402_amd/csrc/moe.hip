@@ -39,69 +39,91 @@ constexpr int MAX_K = 8;
 __device__ __forceinline__ bf16x8 ldg_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
 // ------------------------------------------------------------------------------------------ gate
-// Workgroup tile: 128 tokens x 64 experts; waves 2 x 2, each 64 tokens x 32 experts.
+// Workgroup tile: 64 tokens x 64 experts, both gate matrices at once.  Operands are staged through
+// LDS in K-chunks of 64 with coalesced 128-byte row reads (see the grouped GEMM below for why), the
+// next chunk is prefetched into registers.  Wave w owns experts [16w, 16w+16) of the tile for all
+// 64 tokens: 4 token tiles x (clean, noise) accumulators.
+constexpr int GKC = 64;                // K-chunk
+constexpr int GLDP = GKC + 8;          // LDS row pitch in elements (144 bytes, conflict free)
+
 __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
                                               const bf16_t* __restrict__ Wn, const float* __restrict__ noise,
                                               float* __restrict__ logits, int T, int d, int E)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
-    const int t0 = blockIdx.y * 128 + (wave >> 1) * 64;
-    const int e0 = blockIdx.x * 64 + (wave & 1) * 32;
-    if (t0 >= T || e0 >= E) return;
-    const bf16_t* xr[4];
-    const bf16_t* gr[2];
-    const bf16_t* nr[2];
+    __shared__ __attribute__((aligned(16))) bf16_t Ws[128 * GLDP];   // rows 0..63 Wg, 64..127 Wn
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[64 * GLDP];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.y * 64, e0 = blockIdx.x * 64;
+    const int part = tid & 7, srow = tid >> 3;          // staging: 32 rows x 8 pieces of 16 bytes per pass
+    const bf16_t* wsrc[4];
+    const bf16_t* xsrc[2];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) xr[mt] = x + size_t(min(t0 + mt * 16 + r, T - 1)) * d + g * 8;
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const size_t row = size_t(min(e0 + nt * 16 + r, E - 1)) * d + g * 8;
-        gr[nt] = Wg + row;
-        nr[nt] = noise ? Wn + row : Wg + row;
+    for (int i = 0; i < 2; ++i) {
+        const size_t row = size_t(min(e0 + srow + i * 32, E - 1)) * d + part * 8;
+        wsrc[i] = Wg + row;
+        wsrc[2 + i] = (noise ? Wn : Wg) + row;
+        xsrc[i] = x + size_t(min(t0 + srow + i * 32, T - 1)) * d + part * 8;
     }
-    f32x4 ag[4][2], an[4][2];
+    u32x4 wreg[4], xreg[2];
+    auto fetch = [&](int kc) {
+        const bool inside = kc * GKC + part * 8 < d;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            wreg[i] = inside ? *reinterpret_cast<const u32x4*>(wsrc[i] + kc * GKC) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * GKC) : u32x4{0u, 0u, 0u, 0u};
+    };
+    f32x4 ag[4], an[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) { ag[mt] = f32x4{0, 0, 0, 0}; an[mt] = f32x4{0, 0, 0, 0}; }
+    const int nchunk = (d + GKC - 1) / GKC;
+    fetch(0);
+    for (int kc = 0; kc < nchunk; ++kc) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(Ws + (srow + i * 32) * GLDP + part * 8) = wreg[i];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(Xs + (srow + i * 32) * GLDP + part * 8) = xreg[i];
+        __syncthreads();
+        if (kc + 1 < nchunk) fetch(kc + 1);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 gf = *reinterpret_cast<const bf16x8*>(Ws + (wave * 16 + r) * GLDP + kk * 32 + g * 8);
+            const bf16x8 nf = *reinterpret_cast<const bf16x8*>(Ws + (64 + wave * 16 + r) * GLDP + kk * 32 + g * 8);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * GLDP + kk * 32 + g * 8);
+                ag[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, gf, ag[mt], 0, 0, 0);
+                if (noise) an[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, nf, an[mt], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+    // lane holds tokens t0 + mt*16 + g*4 + i, expert e0 + wave*16 + r
+    const int e = e0 + wave * 16 + r;
+    if (e >= E) return;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) { ag[mt][nt] = f32x4{0, 0, 0, 0}; an[mt][nt] = f32x4{0, 0, 0, 0}; }
-    for (int k0 = 0; k0 < d; k0 += 32) {
-        bf16x8 xf[4], gf[2], nf[2];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) xf[mt] = ldg_frag(xr[mt] + k0);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) { gf[nt] = ldg_frag(gr[nt] + k0); nf[nt] = ldg_frag(nr[nt] + k0); }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                ag[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], gf[nt], ag[mt][nt], 0, 0, 0);
-                if (noise) an[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], nf[nt], an[mt][nt], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            const int t = t0 + mt * 16 + g * 4 + i;
+            if (t >= T) continue;
+            float v = ag[mt][i];
+            if (noise) {
+                const float z = an[mt][i];
+                const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
+                v += noise[size_t(t) * E + e] * sp;
             }
-    }
-    // lane holds tokens t0 + mt*16 + g*4 + i, expert e0 + nt*16 + r
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int e = e0 + nt * 16 + r;
-            if (e >= E) continue;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = t0 + mt * 16 + g * 4 + i;
-                if (t >= T) continue;
-                float v = ag[mt][nt][i];
-                if (noise) {
-                    const float z = an[mt][nt][i];
-                    const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
-                    v += noise[size_t(t) * E + e] * sp;
-                }
-                logits[size_t(t) * E + e] = v;
-            }
+            logits[size_t(t) * E + e] = v;
         }
 }
 
 // ------------------------------------------------------------------------------------------ top-k
 // One wave per token. Selection compares fp32 logits exactly: larger first, equal -> lower id.
+// The row is read once into registers (lane l holds experts l, l+64, ...; up to NV*64 experts) and the
+// k selection rounds run on registers with a wave-wide argmax; NV = 0 re-reads the row every round
+// (any E).
+template <int NV>
 __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, int32_t* __restrict__ topk_idx,
                                               float* __restrict__ topk_w, int T, int E, int k)
 {
@@ -109,6 +131,15 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const float* row = logits + size_t(t) * E;
+    float reg[NV > 0 ? NV : 1];
+    uint32_t taken = 0;                      // bit i: this lane's i-th value was already selected
+    if (NV > 0) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = lane + 64 * i;
+            reg[i] = e < E ? row[e] : 0.f;
+        }
+    }
     int chosen[MAX_K];
     float val[MAX_K];
 #pragma unroll
@@ -118,12 +149,21 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
         if (j < k) {
             float bv = -INFINITY;
             int bi = 0x7fffffff;
-            for (int e = lane; e < E; e += 64) {
-                bool taken = false;
+            if (NV > 0) {
 #pragma unroll
-                for (int q = 0; q < MAX_K; ++q) taken |= (q < j && chosen[q] == e);
-                const float v = row[e];
-                if (!taken && (v > bv || (v == bv && e < bi) || bi == 0x7fffffff)) { bv = v; bi = e; }
+                for (int i = 0; i < NV; ++i) {
+                    const int e = lane + 64 * i;
+                    const float v = reg[i];
+                    if (e < E && !((taken >> i) & 1u) && (v > bv || bi == 0x7fffffff)) { bv = v; bi = e; }
+                }
+            } else {
+                for (int e = lane; e < E; e += 64) {
+                    bool was = false;
+#pragma unroll
+                    for (int q = 0; q < MAX_K; ++q) was |= (q < j && chosen[q] == e);
+                    const float v = row[e];
+                    if (!was && (v > bv || bi == 0x7fffffff)) { bv = v; bi = e; }
+                }
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) {
@@ -133,6 +173,7 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
             }
             chosen[j] = bi;
             val[j] = bv;
+            if (NV > 0 && (bi & 63) == lane) taken |= 1u << (bi >> 6);
         }
     }
     float den = 0.f;
@@ -466,6 +507,7 @@ Layout layout(const moe_shape* s)
 int check_shape(const moe_shape* s, const char* who)
 {
     if (!s) return fail(DYNB_E_INVAL, std::string(who) + ": NULL shape");
+    if (size_t(s->T) > size_t(65535) * 64) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": more than 4194240 tokens");
     if (s->T < 0 || s->d <= 0 || s->h <= 0 || s->E <= 0 || s->k <= 0)
         return fail(DYNB_E_INVAL, std::string(who) + ": sizes must be positive");
     if (s->k > s->E) return fail(DYNB_E_INVAL, std::string(who) + ": k > E");
@@ -519,11 +561,18 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
     const bool timed = dynb::timing_on();
     if (timed) dynb::timing_begin(st);
     // m1 gate
-    hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 127) / 128), dim3(256), 0, st, xb,
+    hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 63) / 64), dim3(256), 0, st, xb,
                        static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
     if (timed) dynb::timing_mark(st, dynb::ST_GATE, 0);
     // m2 top-k + softmax
-    hipLaunchKernelGGL(k_topk, dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    if (E <= 4 * 64)
+        hipLaunchKernelGGL((k_topk<4>), dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    else if (E <= 16 * 64)
+        hipLaunchKernelGGL((k_topk<16>), dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    else if (E <= 32 * 64)
+        hipLaunchKernelGGL((k_topk<32>), dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
+    else
+        hipLaunchKernelGGL((k_topk<0>), dim3((T + 3) / 4), dim3(256), 0, st, logits, topk_idx, topk_w, T, E, k);
     if (timed) dynb::timing_mark(st, dynb::ST_TOPK, 0);
     // m3 stable counting sort
     const size_t nbc = size_t(E) * L.nblk;

@@ -48,7 +48,8 @@ def check_routing(oracle, m, aux):
 
 
 @pytest.mark.parametrize("T,d,h,E,k,empty", [(300, 64, 96, 20, 3, 0.2), (257, 32, 32, 5, 5, 0.0), (1000, 128, 160, 70, 1, 0.1),
-                                              (64, 96, 64, 300, 8, 0.5), (1, 32, 32, 2, 2, 0.0)])
+                                              (64, 96, 64, 300, 8, 0.5), (1, 32, 32, 2, 2, 0.0),
+                                              (24, 32, 32, 2100, 3, 0.0)])
 def test_small_layers_every_element(dyn, util, oracle, T, d, h, E, k, empty):
     m = moe.small(seed=T + E, T=T, d=d, h=h, E=E, k=k, empty_frac=empty)
     W1, W2 = stack(m)
