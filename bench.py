@@ -182,9 +182,25 @@ def main():
         by_ffn = by_w + A * (m.d + 2 * m.h + m.d) * 2             # + xs read, hid written and read, y written
         fl_ffn = 4.0 * m.d * m.h * A
         ffn_ms = stage_ms["ffn1"] + stage_ms["ffn2"]
+        moe_naive = None
+        if not args.skip_naive:
+            stride = 16
+            dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, out=mout, workspace=mws,
+                            naive_stride=stride * 8)                      # warm-up of the host loop path
+            torch.cuda.synchronize()
+            dyn.dynb_timing_enable(True)
+            dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, out=mout, workspace=mws,
+                            naive_stride=stride)
+            nst = {dyn.MOE_STAGES[tag]: ms for tag, _, ms in dyn.dynb_timing_read()}
+            dyn.dynb_timing_enable(False)
+            sampled = nst["ffn1"] + nst["ffn2"]
+            moe_naive = {"kind": "same kernels, one expert call (2 launches) per (token, expert) use from a host loop",
+                         "sample": f"every {stride}th of {A} uses executed, time scaled by {stride}",
+                         "expert_stage_ms_sampled": round(sampled, 3), "expert_stage_ms_est": round(sampled * stride, 2),
+                         "speedup_batched_expert_stage": round(sampled * stride / ffn_ms, 1)}
         moe_res = {"workload": m.name, "tokens_per_sec": round(m.T / moe_ms * 1e3, 1), "ms_per_step": round(moe_ms, 4),
                    "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "active_experts": n_active,
-                   "max_expert_rows": int(counts.max())}
+                   "max_expert_rows": int(counts.max()), "naive_gpu": moe_naive}
         moe_roof = [
             {"kernel": "k_permute", "bound": "hbm", "achieved": round(by_perm / stage_ms["permute"] / 1e6, 1),
              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(by_perm / stage_ms["permute"] / 1e6 / PEAK_HBM_GBS, 4),

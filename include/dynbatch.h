@@ -213,6 +213,19 @@ int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const voi
                 const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* The unbatched comparison row of Results / Sparsely Gated Mixture of Experts ("the naive
+ * implementation loops over and executes the kb experts independently"): gate, top-k, grouping and
+ * permute as in moe_forward, then one expert call (both layers, same kernels, one row) per use,
+ * issued from a host loop, then combine.  Synchronises the stream once to read the group sizes.
+ *   use_stride  >= 1; 1 executes every use and gives the same `out` as moe_forward; a larger
+ *               value executes only every use_stride-th use (a timing sample: `out` is then
+ *               not meaningful).
+ * Other arguments and errors as moe_forward; DYNB_E_INVAL for use_stride < 1.                     */
+int moe_forward_naive(const moe_shape* shape, const void* x, const void* Wg, const void* Wn,
+                      const float* noise, const void* W1, const void* W2, void* out,
+                      const moe_aux* aux, void* workspace, size_t workspace_bytes, void* stream,
+                      int32_t use_stride);
+
 /* ------------------------------------------------------------------------------------------- */
 /* Per-stage timing (the paper reports "neural cell execution time" and "data stacking" apart   */
 /* from the whole forward pass: Results / IEP, Results / Sparsely Gated Mixture of Experts)      */

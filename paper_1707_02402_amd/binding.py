@@ -22,7 +22,8 @@ ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "D
 
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
-           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "dynb_timing_enable", "dynb_timing_read"]
+           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_naive", "dynb_timing_enable",
+           "dynb_timing_read"]
 
 
 class DynbError(RuntimeError):
@@ -83,6 +84,7 @@ def _load():
     L.moe_workspace_bytes.restype = ct.c_size_t
     L.moe_forward.argtypes = [ct.POINTER(_MoeShape), ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p,
                               ct.c_void_p, ct.c_void_p, ct.POINTER(_MoeAux), ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.moe_forward_naive.argtypes = L.moe_forward.argtypes + [ct.c_int32]
     L.dynb_timing_enable.argtypes = [ct.c_int]
     L.dynb_timing_read.argtypes = [ct.POINTER(_StageTime), ct.c_int32, ct.POINTER(ct.c_int32)]
     return L
@@ -214,9 +216,11 @@ def moe_workspace_bytes(T: int, d: int, h: int, E: int, k: int, dtype: int = DYN
     return int(lib.moe_workspace_bytes(ct.byref(_MoeShape(T, d, h, E, k, dtype))))
 
 
-def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = False, workspace=None, stream=None):
+def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = False, workspace=None, stream=None,
+                naive_stride: int = 0):
     """x [T,d] bf16; Wg, Wn [E,d] bf16; noise [T,E] f32 or None; W1 [E,h,d]; W2 [E,d,h] bf16 (all device,
-    contiguous).  Returns out [T,d] bf16, or (out, aux namespace of device tensors) if want_aux."""
+    contiguous).  Returns out [T,d] bf16, or (out, aux namespace of device tensors) if want_aux.
+    naive_stride >= 1 calls moe_forward_naive (one expert call per use) instead."""
     import torch
     T, d = x.shape
     E, h = W1.shape[0], W1.shape[1]
@@ -247,9 +251,13 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
             inv=torch.empty(T * k, dtype=torch.int32, device=dev))
         aux_c = _MoeAux(*[getattr(aux_t, n).data_ptr() for n in
                           ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")])
-    _check(lib.moe_forward(ct.byref(shape), _ptr(x), _ptr(Wg), _ptr(Wn), _ptr(noise), _ptr(W1), _ptr(W2), _ptr(out),
-                           ct.byref(aux_c) if aux_c is not None else None, _ptr(workspace),
-                           workspace.numel() * workspace.element_size(), _stream(stream)))
+    args = (ct.byref(shape), _ptr(x), _ptr(Wg), _ptr(Wn), _ptr(noise), _ptr(W1), _ptr(W2), _ptr(out),
+            ct.byref(aux_c) if aux_c is not None else None, _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream))
+    if naive_stride:
+        _check(lib.moe_forward_naive(*args, naive_stride))
+    else:
+        _check(lib.moe_forward(*args))
     return (out, aux_t) if want_aux else out
 
 

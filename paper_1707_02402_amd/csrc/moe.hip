@@ -15,6 +15,7 @@
 
 #include <algorithm>
 #include <string>
+#include <vector>
 
 #include "device_utils.h"
 #include "plan_internal.h"
@@ -527,9 +528,16 @@ extern "C" size_t moe_workspace_bytes(const moe_shape* s)
     return std::max<size_t>(layout(s).total, 256);
 }
 
-extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
-                           const void* W1, const void* W2, void* out, const moe_aux* aux, void* workspace,
-                           size_t workspace_bytes, void* stream)
+__global__ void k_unit_group(int32_t* p)      // offsets {0,1} and tile table {0,1} of a one-row group
+{
+    if (threadIdx.x < 4) p[threadIdx.x] = threadIdx.x & 1;
+}
+
+// naive_stride = 0: batched layer.  naive_stride >= 1: the expert stage is run one use at a time
+// (every naive_stride-th use), which needs the group sizes on the host.
+static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
+                   const void* W1, const void* W2, void* out, const moe_aux* aux, void* workspace,
+                   size_t workspace_bytes, void* stream, int naive_stride)
 {
     int rc = check_shape(s, "moe_forward");
     if (rc != DYNB_OK) return rc;
@@ -589,15 +597,50 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
     const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
     if (max_mtiles * std::max(nt1, nt2) >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
-    hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt1)), dim3(256), 0, st, xs,
-                       static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
-    if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
-    hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt2)), dim3(256), 0, st, hid,
-                       static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
-    if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
+    if (naive_stride <= 0) {
+        hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt1)), dim3(256), 0, st, xs,
+                           static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
+        if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
+        hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt2)), dim3(256), 0, st, hid,
+                           static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
+        if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
+    } else {
+        // the paper's naive version: loop over the k*b expert uses, one expert call (two layers) per use
+        std::vector<int32_t> off(size_t(E) + 1);
+        int32_t* unit = lrank;                                // free again after k_place
+        hipLaunchKernelGGL(k_unit_group, dim3(1), dim3(64), 0, st, unit);
+        HIP_TRY(hipMemcpyAsync(off.data(), offsets, off.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st), "moe_forward_naive");
+        HIP_TRY(hipStreamSynchronize(st), "moe_forward_naive");
+        const bf16_t* w1 = static_cast<const bf16_t*>(W1);
+        const bf16_t* w2 = static_cast<const bf16_t*>(W2);
+        for (int e = 0; e < E; ++e)
+            for (int pos = off[e]; pos < off[e + 1]; ++pos) {
+                if (pos % naive_stride) continue;
+                hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(8 * nt1), dim3(256), 0, st, xs + size_t(pos) * d,
+                                   w1 + size_t(e) * h * d, hid + size_t(pos) * h, unit, unit + 2, 1, h, d, nt1);
+                hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(8 * nt2), dim3(256), 0, st, hid + size_t(pos) * h,
+                                   w2 + size_t(e) * d * h, y + size_t(pos) * d, unit, unit + 2, 1, d, h, nt2);
+            }
+        if (timed) { dynb::timing_mark(st, dynb::ST_FFN1, 0); dynb::timing_mark(st, dynb::ST_FFN2, 0); }
+    }
     // m6 combine
     hipLaunchKernelGGL(k_combine, dim3((T + 3) / 4), dim3(256), 0, st, y, inv, topk_w, static_cast<bf16_t*>(out), T, d, k);
     if (timed) dynb::timing_mark(st, dynb::ST_COMBINE, 0);
     HIP_TRY(hipGetLastError(), "moe_forward");
     return DYNB_OK;
+}
+
+extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
+                           const void* W1, const void* W2, void* out, const moe_aux* aux, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    return moe_run(s, x, Wg, Wn, noise, W1, W2, out, aux, workspace, workspace_bytes, stream, 0);
+}
+
+extern "C" int moe_forward_naive(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
+                                 const void* W1, const void* W2, void* out, const moe_aux* aux, void* workspace,
+                                 size_t workspace_bytes, void* stream, int32_t use_stride)
+{
+    if (use_stride < 1) return fail(DYNB_E_INVAL, "moe_forward_naive: use_stride must be >= 1");
+    return moe_run(s, x, Wg, Wn, noise, W1, W2, out, aux, workspace, workspace_bytes, stream, use_stride);
 }

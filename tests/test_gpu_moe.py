@@ -126,6 +126,18 @@ def test_config4_sampled_with_empty_experts(dyn, util, oracle):
     assert (r.counts == 0).sum() >= 51 and len(m.empty) == 51
 
 
+def test_naive_per_use_loop_equals_batched_layer(dyn, util):
+    """Results / MoE: the naive version loops over the k*b uses; same kernels, so the same bits."""
+    m = moe.small(seed=12, T=90, d=64, h=96, E=9, k=3, empty_frac=0.2)
+    W1, W2 = stack(m)
+    dev = util.moe_inputs_dev(m, W1, W2)
+    a = dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k)
+    b = dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, naive_stride=1)
+    assert (util.to_host(a) == util.to_host(b)).all()
+    with pytest.raises(dyn.DynbError):
+        dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, naive_stride=-1)
+
+
 def test_moe_error_paths(dyn, util):
     import torch
     m = moe.small(seed=1, T=16, d=32, h=32, E=4, k=2)
