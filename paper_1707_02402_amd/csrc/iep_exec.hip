@@ -294,19 +294,23 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
     }
 }
 
-// WM = waves along the pixel dimension of one node.
+// WM selects how a node is spread over waves and workgroups.
 //   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles
-//           each): best throughput, used for wide launch groups.
-//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 4 or 3 pixel tiles): about half
-//           the latency per node, used when the launch group has fewer nodes than the chip has CUs.
+//           each): best throughput per CU, used for the widest launch groups.
+//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 4 or 3 pixel tiles).
+//   WM = 3: half a node per workgroup: output rows 0..6 or 7..13.  The workgroup convolves an 8-row
+//           window (rows 0..7 or 6..13: the second conv needs one row of the first conv's output
+//           beyond its own rows), i.e. 112 pixels = 4 pixel tiles, 2 per wave.  Two CUs share a node,
+//           which halves the latency of narrow launch groups at the price of 8/7 of the MFMA work.
 template <int WM>
 __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 {
     using namespace mf;
     constexpr int NPW = (WM == 1) ? 2 : 1;    // nodes per workgroup
     constexpr int WPN = 4 / NPW;              // waves per node
-    constexpr int MTW = (WM == 1) ? 7 : 4;    // pixel tiles per wave (upper bound)
+    constexpr int MTW = (WM == 1) ? 7 : (WM == 2 ? 4 : 2);    // pixel tiles per wave (upper bound)
     constexpr int NTHR = 64 * WPN;            // threads that stage one node
+    constexpr bool HALF = (WM == 3);
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
     // Workgroup -> position in the launch group.  Consecutive workgroup ids land on different
@@ -314,8 +318,13 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     // a function's weights stay in as few L2s as possible.
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int first = logical * NPW;
+    const int first = HALF ? (logical >> 1) : logical * NPW;
     if (first >= a.count) return;
+    // pixel window of this workgroup: image rows [wrow0, wrow0 + wrows); output rows [orow0, orow1)
+    const int wrow0 = HALF ? (logical & 1) * 6 : 0;
+    constexpr int wrows = HALF ? 8 : S;
+    constexpr int NPIX = wrows * S;           // 196 or 112
+    const int orow0 = HALF ? (logical & 1) * 7 : 0, orow1 = HALF ? orow0 + 7 : S;
 
     PHASE(0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -327,24 +336,29 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     const int r = lane & 31, h = lane >> 5;
     const int n0 = (wi & 1) * 64;             // first output channel of this wave
     const int m0 = (wi >> 1) * MTW;           // first pixel tile of this wave
-    const int mcount = (WM == 1) ? MT7 : (MT7 - m0 < MTW ? MT7 - m0 : MTW);
+    const int mcount = (WM == 2) ? (MT7 - m0 < MTW ? MT7 - m0 : MTW) : MTW;
 
     // ---- gather: zero border once, then the argument map into the centre of the halo tile;
     // all global loads of the map are issued before the first LDS write, so one memory latency is paid
     const int tl = tid % NTHR;
     auto stage = [&](const bf16_t* src) {
-        constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
+        // rows of the argument map that the window's 3x3 taps can touch
+        const int srow0 = wrow0 > 0 ? wrow0 - 1 : 0;
+        const int srow1 = wrow0 + wrows + 1 < S ? wrow0 + wrows + 1 : S;
+        constexpr int MAXPIECES = (HALF ? 9 : S) * S * 16;
+        constexpr int NIT = (MAXPIECES + NTHR - 1) / NTHR;
+        const int c_lo = srow0 * S * 16, c_hi = srow1 * S * 16;
         const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
         u32x4 tmp[NIT];
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = tl + i * NTHR;
-            if (c < P * 16) tmp[i] = s4[c];
+            const int c = c_lo + tl + i * NTHR;
+            if (c < c_hi) tmp[i] = s4[c];
         }
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = tl + i * NTHR;
-            if (c < P * 16) {
+            const int c = c_lo + tl + i * NTHR;
+            if (c < c_hi) {
                 const int p = c >> 4, part = c & 15;
                 const uint32_t addr = tile + uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + part * 16);
                 *reinterpret_cast<u32x4*>(lds_raw + addr) = tmp[i];
@@ -369,7 +383,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
     uint32_t xaddr[MTW];
 #pragma unroll
     for (int t = 0; t < MTW; ++t) {
-        const int p = min((m0 + t) * 32 + r, P - 1);
+        const int p = wrow0 * S + min((m0 + t) * 32 + r, NPIX - 1);
         xaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
     }
     // this lane's 16 accumulator elements of channel tile nt are channels n0 + nt*32 + 16*h + (0..15)
@@ -402,33 +416,30 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         pk.w = relu_bf16x2(pack_bf16x2(acc[t][nt][8 * q + 6], acc[t][nt][8 * q + 7]));
         return pk;
     };
-    // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
-    auto write_tile = [&]() {
-#pragma unroll
-        for (int t = 0; t < MTW; ++t)
-            if (t < mcount && (m0 + t) * 32 + r < P) {
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((cbase + nt * 32 + q * 8) * 2)) =
-                            packed(t, nt, q);
-            }
-    };
 
     PHASE(1);
     __syncthreads();
     PHASE(2);
 
-    // ---- binary functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the same tile
+    // ---- binary functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the same tile.
+    // The first conv3x3 reads u one row beyond the window, so in half-node mode the 1x1 runs on its
+    // own 9-row window (rows 0..8 or 5..13: 126 pixels, still 4 tiles).
     if (a.any_binary) {                                   // uniform over the launch group
+        const int urow0 = HALF ? (wrow0 > 0 ? wrow0 - 1 : 0) : 0;
+        constexpr int UPIX = HALF ? 9 * S : P;
+        uint32_t uaddr[MTW];
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            const int p = urow0 * S + min((m0 + t) * 32 + r, UPIX - 1);
+            uaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
+        }
         const bf16_t* w1row[2];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
             w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
         if (binary) {
             init_bias(a.b1);
-            kloop_mfma<MTW, true>(acc, xaddr, mcount, w1row);
+            kloop_mfma<MTW, true>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
@@ -436,10 +447,21 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         if (binary) {
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) w1row[nt] += 8 * FRAG;
-            kloop_mfma<MTW, true>(acc, xaddr, mcount, w1row);
+            kloop_mfma<MTW, true>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
-        if (binary) write_tile();
+        if (binary) {                                     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
+#pragma unroll
+            for (int t = 0; t < MTW; ++t)
+                if (t < mcount && (m0 + t) * 32 + r < UPIX) {
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                        for (int q = 0; q < 2; ++q)
+                            *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
+                                                      uint32_t((cbase + nt * 32 + q * 8) * 2)) = packed(t, nt, q);
+                }
+        }
         __syncthreads();
     }
 
@@ -469,7 +491,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
                 }
 #pragma unroll
                 for (int t = 0; t < MTW; ++t)
-                    if (t < mcount && (m0 + t) * 32 + r < P) {
+                    if (t < mcount && (m0 + t) * 32 + r < NPIX) {
                         const uint32_t addr = centre(t) + uint32_t((cbase + nt * 32 + q * 8) * 2);
                         const u32x4 res = *reinterpret_cast<const u32x4*>(lds_raw + addr);
                         *reinterpret_cast<u32x4*>(lds_raw + addr) = packed(t, nt, q);
@@ -498,8 +520,9 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            const int p = (m0 + t) * 32 + r;
-            if (t < mcount && p < P) {
+            const int pl = (m0 + t) * 32 + r;
+            const int p = wrow0 * S + pl;
+            if (t < mcount && pl < NPIX && p >= orow0 * S && p < orow1 * S) {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -623,6 +646,9 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<2>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<3>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<3>)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<1>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<1>)");
@@ -659,16 +685,17 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         a.count = l.count;
         a.any_binary = 0;
         for (int i = 0; i < l.count; ++i) a.any_binary |= (p->arity[p->items[l.start + i].type] == 2);
-        // one node per workgroup (lower latency) while the launch group fits the chip's 256 CUs,
-        // two nodes per workgroup (higher throughput per CU) beyond that
-        int wm = (l.count <= 256) ? 2 : 1;
+        // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
+        // workgroup up to 256 nodes, two nodes per workgroup (highest throughput per CU) beyond that
+        int wm = (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
 #ifdef DYNB_PHASE_CLOCKS
         if (const char* f = getenv("DYNB_FORCE_WM")) wm = atoi(f);
 #endif
-        const int npw = (wm == 1) ? 2 : 1;
-        const int nwg = (l.count + npw - 1) / npw;
+        const int nwg = (wm == 1) ? (l.count + 1) / 2 : (wm == 2) ? l.count : 2 * l.count;
         const unsigned grid = unsigned((nwg + 7) / 8 * 8);
-        if (wm == 2)
+        if (wm == 3)
+            hipLaunchKernelGGL((k_module_mfma<3>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        else if (wm == 2)
             hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else
             hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
