@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--iep-config", choices=["config1", "config2"], default="config2")
+    ap.add_argument("--no-balance", action="store_true", help="plain improved sort, no pull-forward of nodes")
     ap.add_argument("--skip-moe", action="store_true")
     ap.add_argument("--skip-naive", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -68,10 +69,11 @@ def main():
     weights = U.iep_weights_dev(w)
     feats = U.to_dev(w.feats, w.dtype)
     out = torch.empty_like(feats)
-    plan0 = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity)
+    plan_flags = dyn.DYNB_SCHED_IMPROVED | (0 if args.no_balance else dyn.DYNB_PLAN_BALANCE)
+    plan0 = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, plan_flags)
     view = dyn.dynbatch_plan_view(plan0)
     ws_bytes = max(dyn.dynbatch_workspace_bytes(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, f), w.C, w.H, w.W,
-                                                dyn.DYNB_BF16) for f in (dyn.DYNB_SCHED_IMPROVED, dyn.DYNB_SCHED_NAIVE))
+                                                dyn.DYNB_BF16) for f in (plan_flags, dyn.DYNB_SCHED_NAIVE))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     devbuf = torch.empty(dyn.dynbatch_plan_device_bytes(plan0) + 4096, dtype=torch.uint8, device="cuda")
     n_evals = view.n_compute_nodes
@@ -82,7 +84,7 @@ def main():
 
     keep = []
 
-    def iep_step(flags=0, host_ms=None):
+    def iep_step(flags=plan_flags, host_ms=None):
         t0 = time.perf_counter()
         plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
         t1 = time.perf_counter()
@@ -260,7 +262,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "nodes": int(view.n_nodes), "module_evals": int(n_evals),
                    "levels": int(view.n_levels), "launch_groups": int(view.n_launches), "C": w.C, "H": w.H, "W": w.W,
-                   "step": "dynbatch_plan + dynbatch_plan_upload + dynbatch_execute"},
+                   "step": "dynbatch_plan + dynbatch_plan_upload + dynbatch_execute",
+                   "schedule": "improved topological sort" + ("" if args.no_balance else " + balanced launch groups")},
         "plan_host_ms": round(float(np.mean(plan_ms)), 4), "execute_only_ms": round(exec_ms, 4),
         "execute_only_module_evals_per_sec": round(n_evals / exec_ms * 1e3, 1),
         "roofline": {"kernel": "k_module_mfma", "bound": "mfma", "achieved": round(achieved_tflops, 2),

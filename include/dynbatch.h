@@ -57,7 +57,13 @@ enum {
     /* Results / IEP, the unbatched original: an explicit loop over examples, one module per
      * call.  Same kernels, one launch per node; the comparison row for the speed-up.           */
     DYNB_SCHED_NAIVE = 2,
-    DYNB_SCHED_MASK = 3
+    DYNB_SCHED_MASK = 3,
+    /* Optional, with DYNB_SCHED_IMPROVED only (ignored otherwise): balance the launch groups.  The
+     * label of a node is the latest group it can run in; nodes whose arguments are ready earlier are
+     * pulled forward out of groups wider than the chip's 256 CUs into earlier groups with idle CUs
+     * (Discussion: "optimize the order of dependency execution").  The logical plan (labels, pools)
+     * is unchanged; only node_launch and the executor's work lists differ.                       */
+    DYNB_PLAN_BALANCE = 4
 };
 
 const char* dynb_last_error(void);
@@ -97,6 +103,7 @@ typedef struct {
     const int32_t* in0;          /* [n_nodes]                                                   */
     const int32_t* in1;          /* [n_nodes]                                                   */
     const int32_t* out;          /* [n_nodes]                                                   */
+    const int32_t* node_launch;  /* [n_nodes] launch group that executes the node, -1 for SCENE   */
 } dynb_plan_view;
 
 /* Builds the plan for a minibatch of programs (Background / Visual Reasoning Programs: the fixed
@@ -105,7 +112,7 @@ typedef struct {
  *   prog_off  host  [B+1], prog_off[0] = 0, example i owns prog[prog_off[i] .. prog_off[i+1])
  *   arity     host  [n_types] values 0, 1 or 2; any id with arity 0 is a SCENE-like leaf that
  *                   outputs the example's feature map
- *   flags     one DYNB_SCHED_* value
+ *   flags     one DYNB_SCHED_* value, optionally | DYNB_PLAN_BALANCE
  *   out       receives a library-owned plan; release with dynbatch_plan_free
  * Errors: DYNB_E_INVAL (NULL, B <= 0, n_types <= 0, offsets not increasing from 0),
  * DYNB_E_UNSUPPORTED (arity > 2, unknown flag), DYNB_E_MALFORMED (function id out of range, a

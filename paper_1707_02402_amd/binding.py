@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdynbatch.so")
 
 DYNB_F32, DYNB_BF16 = 0, 1
 DYNB_SCHED_IMPROVED, DYNB_SCHED_STANDARD, DYNB_SCHED_NAIVE = 0, 1, 2
+DYNB_PLAN_BALANCE = 4
 ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
           -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}
 
@@ -40,7 +41,8 @@ class _PlanView(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in ("n_examples", "n_nodes", "n_levels", "n_buckets", "n_compute_nodes",
                                           "n_launches", "max_launch_nodes", "n_slots")] + \
                [(n, I32P) for n in ("node_level", "node_type", "child0", "child1", "root", "bucket_level",
-                                    "bucket_type", "bucket_start", "bucket_count", "members", "in0", "in1", "out")]
+                                    "bucket_type", "bucket_start", "bucket_count", "members", "in0", "in1", "out",
+                                    "node_launch")]
 
 
 class _Shape(ct.Structure):
@@ -152,7 +154,7 @@ def dynbatch_plan_view(plan: Plan) -> SimpleNamespace:
         child1=arr(v.child1, N), root=arr(v.root, B), bucket_level=arr(v.bucket_level, nb),
         bucket_type=arr(v.bucket_type, nb), bucket_start=arr(v.bucket_start, nb),
         bucket_count=arr(v.bucket_count, nb), members=arr(v.members, N), in0=arr(v.in0, N), in1=arr(v.in1, N),
-        out=arr(v.out, N))
+        out=arr(v.out, N), node_launch=arr(v.node_launch, N))
 
 
 def dynbatch_plan_device_bytes(plan: Plan) -> int:

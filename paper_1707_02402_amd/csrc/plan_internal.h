@@ -28,6 +28,7 @@ struct dynb_plan {
     std::vector<uint8_t> arity;
     std::vector<int32_t> level, type, child0, child1, root;
     std::vector<int32_t> b_level, b_type, b_start, b_count, members, in0, in1, out;
+    std::vector<int32_t> node_launch;    // launch group that executes each node (-1 for SCENE leaves)
     std::vector<dynb_item> items;        // execution order
     std::vector<dynb_launch> launches;
     std::vector<int32_t> leaf_roots;     // examples whose whole program is one SCENE token

@@ -86,7 +86,8 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     if (out) *out = nullptr;
     if (!prog || !prog_off || !arity || !out) return fail(DYNB_E_INVAL, "dynbatch_plan: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
+    const bool balance = (flags & DYNB_PLAN_BALANCE) != 0;
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
     if (mode > DYNB_SCHED_NAIVE) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown scheduling mode");
     for (int32_t t = 0; t < n_types; ++t)
@@ -189,55 +190,136 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
             p->in0[s] = p->child0[n]; p->in1[s] = p->child1[n]; p->out[s] = n;
         }
 
-        // ---- executor work lists: items in execution order, slots, launch groups
-        std::vector<int32_t> slot(N, -1);
-        std::vector<int32_t> exec_rank(N, -1);
-        int32_t n_compute = 0;
+        // ---- executor work lists: items in execution order, launch groups, slots
+        // 1. launch group of every compute node, in the logical order of the pools
+        p->node_launch.assign(N, -1);
+        std::vector<int32_t> order;                       // compute nodes in execution order
+        int32_t n_launch = 0;
         {
-            // compute width per label (IMPROVED ping-pong) and overall
-            std::vector<int32_t> width(D, 0);
-            for (int32_t n = 0; n < N; ++n)
-                if (arity[p->type[n]] > 0) { ++width[p->level[n]]; ++n_compute; }
-            int32_t maxw = 0;
-            for (int32_t l = 0; l < D; ++l) maxw = std::max(maxw, width[l]);
-            std::vector<int32_t> rank_in_level(D, 0);
-            int32_t running = 0;
-            p->items.reserve(n_compute);
-            int32_t cur_label = -1, cur_example = -1;
+            int32_t cur_label = -1;
             for (int32_t s = 0; s < N; ++s) {
                 const int32_t n = p->members[s];
-                const int32_t t = p->type[n];
-                if (arity[t] == 0) continue;
-                if (arity[t] == 2) p->has_binary = true;
+                if (arity[p->type[n]] == 0) continue;
+                if (arity[p->type[n]] == 2) p->has_binary = true;
+                if (mode == DYNB_SCHED_NAIVE || p->level[n] != cur_label) { ++n_launch; cur_label = p->level[n]; }
+                p->node_launch[n] = n_launch - 1;
+                order.push_back(n);
+            }
+        }
+        const int32_t n_compute = int32_t(order.size());
+        auto is_compute = [&](int32_t c) { return c >= 0 && arity[p->type[c]] > 0; };
+
+        // 2. optional balancing of the improved sort.  A label only fixes the LATEST launch group a
+        // node may run in; a node whose arguments finish early can run earlier.  Launch groups with
+        // more nodes than the chip has CUs (256) cost a second round, so nodes are pulled forward out
+        // of such groups into earlier groups that have idle CUs (earliest deadline first).  The paper
+        // mentions this freedom ("optimize the order of dependency execution") and leaves it aside.
+        if (improved && balance && n_launch > 1) {
+            const int32_t S = n_launch;
+            constexpr int32_t CUS = 256, HALF_CUS = 128;
+            std::vector<int32_t> remaining(S, 0), pending(N, 0), ready_at(N, 0), assigned(N, -1), parent(N, -1);
+            for (int32_t n : order) {
+                ++remaining[p->node_launch[n]];
+                for (int32_t c : {p->child0[n], p->child1[n]})
+                    if (is_compute(c)) { ++pending[n]; parent[c] = n; }
+            }
+            // `order` is grouped by deadline already; only groups that overflow the chip give nodes away
+            std::vector<int32_t> first_of(S + 1, 0);
+            for (int32_t n : order) ++first_of[p->node_launch[n] + 1];
+            for (int32_t L = 0; L < S; ++L) first_of[L + 1] += first_of[L];
+            std::vector<char> wide(S, 0);
+            std::vector<int32_t> wide_list;
+            for (int32_t L = 0; L < S; ++L)
+                if (remaining[L] > CUS) { wide[L] = 1; wide_list.push_back(L); }
+            std::vector<std::vector<int32_t>> ready(S);
+            for (int32_t L : wide_list) ready[L].reserve(remaining[L]);
+            for (int32_t n : order)
+                if (pending[n] == 0 && wide[p->node_launch[n]]) ready[p->node_launch[n]].push_back(n);
+            auto assign = [&](int32_t n, int32_t s) {
+                assigned[n] = s;
+                --remaining[p->node_launch[n]];
+                const int32_t q = parent[n];
+                if (q >= 0) {
+                    ready_at[q] = std::max(ready_at[q], s + 1);
+                    if (--pending[q] == 0 && wide[p->node_launch[q]]) ready[p->node_launch[q]].push_back(q);
+                }
+            };
+            for (int32_t s = 0; s < S; ++s) {
+                int32_t here = 0;
+                for (int32_t i = first_of[s]; i < first_of[s + 1]; ++i)
+                    if (assigned[order[i]] < 0) { assign(order[i], s); ++here; }
+                // fill up to the next size class of the executor, never into a slower one
+                const int32_t cap = here <= HALF_CUS ? HALF_CUS : (here <= CUS ? CUS : here);
+                for (int32_t L : wide_list) {
+                    if (here >= cap) break;
+                    if (L <= s || remaining[L] <= CUS) continue;
+                    auto& pool = ready[L];
+                    size_t keep = 0;
+                    for (size_t i = 0; i < pool.size(); ++i) {
+                        const int32_t n = pool[i];
+                        if (here < cap && remaining[L] > CUS && ready_at[n] <= s) { assign(n, s); ++here; }
+                        else pool[keep++] = n;
+                    }
+                    pool.resize(keep);
+                }
+            }
+            for (int32_t n : order) p->node_launch[n] = assigned[n];
+            // execution order: launch group, then function id (weights stay hot), then node id
+            std::vector<int32_t> start(size_t(S) * n_types + 1, 0);
+            auto key = [&](int32_t n) { return size_t(p->node_launch[n]) * n_types + size_t(p->type[n]); };
+            for (int32_t n : order) ++start[key(n) + 1];
+            for (size_t q = 0; q + 1 < start.size(); ++q) start[q + 1] += start[q];
+            std::vector<int32_t> sorted(order.size());
+            for (int32_t n = 0; n < N; ++n)                       // ascending node id inside a (group, function) run
+                if (p->node_launch[n] >= 0) sorted[start[key(n)]++] = n;
+            order.swap(sorted);
+        }
+
+        // 3. slots and items
+        std::vector<int32_t> slot(N, -1);
+        {
+            const bool pingpong = improved && !balance;
+            int32_t maxw = 0, running = 0;
+            std::vector<int32_t> rank_in_level(D, 0);
+            if (pingpong) {
+                std::vector<int32_t> width(D, 0);
+                for (int32_t n : order) ++width[p->level[n]];
+                for (int32_t l = 0; l < D; ++l) maxw = std::max(maxw, width[l]);
+            }
+            std::vector<int32_t> free_slots, release;     // balanced plans recycle slots through a free list
+            p->items.reserve(n_compute);
+            int32_t cur = -1;
+            for (int32_t n : order) {
+                if (p->node_launch[n] != cur) {
+                    // slots of arguments consumed by the previous group may be reused from here on
+                    free_slots.insert(free_slots.end(), release.begin(), release.end());
+                    release.clear();
+                    p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0});
+                    cur = p->node_launch[n];
+                }
                 const bool is_root = (n == p->root[example[n]]);
-                if (improved) {
+                if (pingpong) {
                     // arguments of a label-l node all sit at label l+1: two alternating halves suffice
                     slot[n] = (p->level[n] & 1) * maxw + rank_in_level[p->level[n]]++;
                 } else if (!is_root) {
-                    slot[n] = running++;
+                    if (improved && !free_slots.empty()) { slot[n] = free_slots.back(); free_slots.pop_back(); }
+                    else slot[n] = running++;
                 }
                 auto src = [&](int32_t c) -> int32_t {
                     if (c < 0) return 0;
-                    return arity[p->type[c]] == 0 ? -1 - example[c] : slot[c];
+                    if (!is_compute(c)) return -1 - example[c];
+                    if (improved && !pingpong) release.push_back(slot[c]);
+                    return slot[c];
                 };
                 dynb_item it;
                 it.src0 = src(p->child0[n]);
                 it.src1 = src(p->child1[n]);
                 it.dst = is_root ? -1 - example[n] : slot[n];
-                it.type = t;
-                // launch groups: one per label (IMPROVED, STANDARD) or one per node (NAIVE)
-                bool new_group;
-                if (mode == DYNB_SCHED_NAIVE) new_group = true;
-                else new_group = (p->level[n] != cur_label);
-                (void)cur_example;
-                if (new_group) {
-                    p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0});
-                    cur_label = p->level[n];
-                }
+                it.type = p->type[n];
                 ++p->launches.back().count;
                 p->items.push_back(it);
             }
-            p->n_slots = improved ? 2 * maxw : running;
+            p->n_slots = pingpong ? 2 * maxw : running;
             for (const auto& l : p->launches) p->max_launch = std::max(p->max_launch, l.count);
         }
         for (int32_t i = 0; i < B; ++i)
@@ -261,6 +343,7 @@ extern "C" int dynbatch_plan_view(const dynb_plan* p, dynb_plan_view* v)
     v->n_launches = int32_t(p->launches.size());
     v->max_launch_nodes = p->max_launch;
     v->n_slots = p->n_slots;
+    v->node_launch = p->node_launch.data();
     v->node_level = p->level.data();
     v->node_type = p->type.data();
     v->child0 = p->child0.data();

@@ -124,6 +124,7 @@ def test_config2_iep_shaped_sampled(dyn, util, oracle):
     assert (a == got[::16]).all()
     assert (util.iep_run(dyn, sub, 1) == a).all()
     assert (util.iep_run(dyn, sub, 2) == a).all()
+    assert (util.iep_run(dyn, w, dyn.DYNB_PLAN_BALANCE) == got).all()      # balanced launch groups: same bits
     assert np.isfinite(got).all() and (got >= 0).all()
 
 

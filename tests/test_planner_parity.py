@@ -54,6 +54,28 @@ def test_threaded_parse_of_a_large_batch(dyn, oracle):
     assert_same_plan(v, o)
 
 
+def test_balanced_launch_groups_are_a_valid_schedule(dyn, oracle):
+    """DYNB_PLAN_BALANCE may only move nodes to earlier launch groups, never before their arguments,
+    and leaves the logical plan (labels, pools) untouched."""
+    w = iep.config2()
+    plain = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, 0))
+    bal = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_PLAN_BALANCE))
+    assert_same_plan(bal, oracle.plan(w.prog, w.prog_off, w.arity))
+    compute = w.arity[bal.node_type] > 0
+    assert (bal.node_launch[~compute] == -1).all() and (bal.node_launch[compute] >= 0).all()
+    assert (bal.node_launch <= plain.node_launch).all()              # the label is the latest group
+    for child in (bal.child0, bal.child1):
+        has = (child >= 0) & compute
+        kids = child[has]
+        ck = w.arity[bal.node_type[kids]] > 0
+        assert (bal.node_launch[kids[ck]] < bal.node_launch[np.nonzero(has)[0][ck]]).all()
+    sizes_plain = np.bincount(plain.node_launch[compute])
+    sizes_bal = np.bincount(bal.node_launch[compute])
+    assert sizes_bal.sum() == sizes_plain.sum() == w.n_module_evals and len(sizes_bal) == len(sizes_plain)
+    assert (sizes_plain > 256).sum() > 0 and (sizes_bal > 256).sum() < (sizes_plain > 256).sum()
+    assert bal.n_launches == plain.n_launches and bal.n_slots <= plain.n_compute_nodes
+
+
 def test_naive_schedule_is_one_valid_call_per_node(dyn):
     w = iep.config2(B=16)
     v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_SCHED_NAIVE))
