@@ -223,42 +223,71 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
                 for (int32_t c : {p->child0[n], p->child1[n]})
                     if (is_compute(c)) { ++pending[n]; parent[c] = n; }
             }
-            // `order` is grouped by deadline already; only groups that overflow the chip give nodes away
+            // `order` is grouped by deadline already.  Size classes of the executor: up to 128 nodes a
+            // group runs with two CUs per node, up to 256 with one, beyond that in two rounds.
             std::vector<int32_t> first_of(S + 1, 0);
             for (int32_t n : order) ++first_of[p->node_launch[n] + 1];
             for (int32_t L = 0; L < S; ++L) first_of[L + 1] += first_of[L];
-            std::vector<char> wide(S, 0);
-            std::vector<int32_t> wide_list;
+            std::vector<int32_t> size_at(S, 0);             // nodes currently scheduled in a group
+            std::vector<char> gives(S, 0);                  // groups above the smallest size class
+            std::vector<int32_t> givers;
             for (int32_t L = 0; L < S; ++L)
-                if (remaining[L] > CUS) { wide[L] = 1; wide_list.push_back(L); }
+                if (remaining[L] > HALF_CUS) { gives[L] = 1; givers.push_back(L); }
             std::vector<std::vector<int32_t>> ready(S);
-            for (int32_t L : wide_list) ready[L].reserve(remaining[L]);
+            for (int32_t L : givers) ready[L].reserve(remaining[L]);
             for (int32_t n : order)
-                if (pending[n] == 0 && wide[p->node_launch[n]]) ready[p->node_launch[n]].push_back(n);
+                if (pending[n] == 0 && gives[p->node_launch[n]]) ready[p->node_launch[n]].push_back(n);
             auto assign = [&](int32_t n, int32_t s) {
                 assigned[n] = s;
+                ++size_at[s];
                 --remaining[p->node_launch[n]];
                 const int32_t q = parent[n];
                 if (q >= 0) {
                     ready_at[q] = std::max(ready_at[q], s + 1);
-                    if (--pending[q] == 0 && wide[p->node_launch[q]]) ready[p->node_launch[q]].push_back(q);
+                    if (--pending[q] == 0 && gives[p->node_launch[q]]) ready[p->node_launch[q]].push_back(q);
                 }
             };
+            // pass 0: every node at its deadline unless it is pulled forward out of a group wider than
+            // the chip (those come down to 256); earlier groups are filled up to their size class
             for (int32_t s = 0; s < S; ++s) {
-                int32_t here = 0;
                 for (int32_t i = first_of[s]; i < first_of[s + 1]; ++i)
-                    if (assigned[order[i]] < 0) { assign(order[i], s); ++here; }
-                // fill up to the next size class of the executor, never into a slower one
+                    if (assigned[order[i]] < 0) assign(order[i], s);
+                const int32_t here = size_at[s];
                 const int32_t cap = here <= HALF_CUS ? HALF_CUS : (here <= CUS ? CUS : here);
-                for (int32_t L : wide_list) {
-                    if (here >= cap) break;
+                for (int32_t L : givers) {
+                    if (size_at[s] >= cap) break;
                     if (L <= s || remaining[L] <= CUS) continue;
                     auto& pool = ready[L];
                     size_t keep = 0;
                     for (size_t i = 0; i < pool.size(); ++i) {
                         const int32_t n = pool[i];
-                        if (here < cap && remaining[L] > CUS && ready_at[n] <= s) { assign(n, s); ++here; }
+                        if (size_at[s] < cap && remaining[L] > CUS && ready_at[n] <= s) assign(n, s);
                         else pool[keep++] = n;
+                    }
+                    pool.resize(keep);
+                }
+            }
+            // pass 1: with the room that is left below 128, bring groups of 129..256 nodes down to 128,
+            // earliest deadline first (ready_at is a safe upper bound: arguments only ever move earlier)
+            std::vector<std::vector<int32_t>> at(S);
+            for (int32_t L : givers)
+                if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].reserve(size_at[L]);
+            for (int32_t n : order) {
+                const int32_t L = assigned[n];
+                if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].push_back(n);
+            }
+            for (int32_t s = 0; s < S; ++s) {
+                if (size_at[s] >= HALF_CUS) continue;
+                for (int32_t L : givers) {
+                    if (size_at[s] >= HALF_CUS) break;
+                    if (L <= s || size_at[L] <= HALF_CUS || size_at[L] > CUS) continue;
+                    auto& pool = at[L];
+                    size_t keep = 0;
+                    for (size_t i = 0; i < pool.size(); ++i) {
+                        const int32_t n = pool[i];
+                        if (size_at[s] < HALF_CUS && size_at[L] > HALF_CUS && ready_at[n] <= s) {
+                            assigned[n] = s; ++size_at[s]; --size_at[L];
+                        } else pool[keep++] = n;
                     }
                     pool.resize(keep);
                 }
