@@ -36,6 +36,8 @@ constexpr int SORT_BLOCK = 256;   // uses ranked together by one workgroup
 constexpr int TM = 64;            // rows of one grouped-GEMM tile
 constexpr int TN = 128;           // output features of one grouped-GEMM tile
 constexpr int MAX_K = 8;
+constexpr int MG = 8;             // row tiles of one expert that walk the feature tiles together
+constexpr int XCD_CHUNK = 128;    // consecutive grouped-GEMM tiles dealt to one XCD
 
 __device__ __forceinline__ bf16x8 ldg_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -364,24 +366,26 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
                                           bf16_t* Ws, bf16_t* Xs)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const int part = tid & 7;                      // 16-byte piece of a 128-byte chunk row
-    // staging assignments: 4 weight rows and (rows up to 64) 2 activation rows per thread
-    const bf16_t* wsrc[4];
-    const bf16_t* xsrc[2];
+    constexpr int PARTS = KC / 8;                  // 16-byte pieces of one chunk row
+    constexpr int RPP = 256 / PARTS;               // rows staged per pass of the workgroup
+    constexpr int WPASS = TN / RPP, XPASS = TM / RPP;
+    const int part = tid % PARTS, prow = tid / PARTS;
+    // staging assignments: WPASS weight rows and up to XPASS activation rows per thread
+    const bf16_t* wsrc[WPASS];
+    const bf16_t* xsrc[XPASS];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wsrc[i] = We + size_t(min(nb + (tid >> 3) + i * 32, N - 1)) * K + part * 8;
+    for (int i = 0; i < WPASS; ++i) wsrc[i] = We + size_t(min(nb + prow + i * RPP, N - 1)) * K + part * 8;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) xsrc[i] = in + size_t(row0 + min((tid >> 3) + i * 32, rows - 1)) * K + part * 8;
-    const bool x_needed[2] = {true, ML > 2};       // rows 32..63 only exist in 4-tile bodies
-    u32x4 wreg[4], xreg[2];
+    for (int i = 0; i < XPASS; ++i) xsrc[i] = in + size_t(row0 + min(prow + i * RPP, rows - 1)) * K + part * 8;
+    u32x4 wreg[WPASS], xreg[XPASS];
     auto fetch = [&](int kc) {
-        const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 32: the last chunk may be half empty
+        const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 32: the last chunk may be partly empty
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < WPASS; ++i)
             wreg[i] = inside ? *reinterpret_cast<const u32x4*>(wsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            if (x_needed[i])
+        for (int i = 0; i < XPASS; ++i)
+            if (i * RPP < ML * 16)                    // only rows of live 16-row sub-tiles
                 xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
     };
     f32x4 acc[ML][2];
@@ -393,15 +397,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
     fetch(0);
     for (int kc = 0; kc < nchunk; ++kc) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4*>(Ws + ((tid >> 3) + i * 32) * LDP + part * 8) = wreg[i];
+        for (int i = 0; i < WPASS; ++i)
+            *reinterpret_cast<u32x4*>(Ws + (prow + i * RPP) * LDP + part * 8) = wreg[i];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            if (x_needed[i]) *reinterpret_cast<u32x4*>(Xs + ((tid >> 3) + i * 32) * LDP + part * 8) = xreg[i];
+        for (int i = 0; i < XPASS; ++i)
+            if (i * RPP < ML * 16) *reinterpret_cast<u32x4*>(Xs + (prow + i * RPP) * LDP + part * 8) = xreg[i];
         __syncthreads();
         if (kc + 1 < nchunk) fetch(kc + 1);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < KC / 32; ++kk) {
             bf16x8 wf[2], xf[ML];
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
@@ -446,25 +450,34 @@ template <bool RELU>
 __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ offsets,
                                                       const int32_t* __restrict__ tile_start, int E, int N, int K,
-                                                      int n_tiles_n)
+                                                      int n_tiles_n, int chunk)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Ws[TN * LDP];
     __shared__ __attribute__((aligned(16))) bf16_t Xs[TM * LDP];
-    // Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2).  Keep the
-    // feature tiles of one row tile, which all read the same activation rows, on one XCD so that they
-    // share its L2 instead of fetching the rows eight times.
-    // Row tile m goes to XCD m % 8, so live and surplus row tiles are spread evenly over the XCDs.
-    const int slot = blockIdx.x >> 3;
-    const int mtile = (slot / n_tiles_n) * 8 + (blockIdx.x & 7);
-    const int ntile = slot % n_tiles_n;
-    if (mtile >= tile_start[E]) return;
-    int lo = 0, hi = E;                          // largest e with tile_start[e] <= mtile
+    // Tiles are numbered expert by expert; inside an expert, row tiles are taken in groups of MG, and
+    // inside a group the row tiles that share one feature tile are adjacent (feature tile outer, row
+    // tile inner), so a weight tile is fetched from HBM once and then found in L2 by the other row
+    // tiles of its group.  Consecutive workgroup ids land on different XCDs (8 of them, each with
+    // its own L2), so the numbering is dealt to the XCDs in runs of `chunk` tiles: everything that
+    // shares weights or activation rows stays behind one L2.
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const long long lin = (long long)(j / chunk * 8 + xcd) * chunk + j % chunk;
+    if (lin >= (long long)tile_start[E] * n_tiles_n) return;
+    const int lin_m = int(lin / n_tiles_n);
+    int lo = 0, hi = E;                          // largest e with tile_start[e] <= lin_m
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (tile_start[mid] <= mtile) lo = mid; else hi = mid;
+        if (tile_start[mid] <= lin_m) lo = mid; else hi = mid;
     }
     const int e = lo;
-    const int row0 = offsets[e] + (mtile - tile_start[e]) * TM;
+    const int mt_e = tile_start[e + 1] - tile_start[e];
+    const int i = int(lin - (long long)tile_start[e] * n_tiles_n);   // tile of this expert, 0 .. mt_e * n_tiles_n
+    const int mg = i / (MG * n_tiles_n);
+    const int rem = i - mg * MG * n_tiles_n;
+    const int gsize = min(MG, mt_e - mg * MG);
+    const int ntile = rem / gsize;
+    const int mtile = mg * MG + rem % gsize;
+    const int row0 = offsets[e] + mtile * TM;
     const int rows = min(TM, offsets[e + 1] - row0);
     const int mlive = (rows + 15) >> 4;
     const bf16_t* We = W + size_t(e) * N * K;
@@ -596,13 +609,14 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
     const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
-    if (max_mtiles * std::max(nt1, nt2) >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
+    if (max_mtiles * std::max(nt1, nt2) + 8ll * XCD_CHUNK >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
     if (naive_stride <= 0) {
-        hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt1)), dim3(256), 0, st, xs,
-                           static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1);
+        const long long span = 8ll * XCD_CHUNK;
+        hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles * nt1 + span - 1) / span * span)), dim3(256), 0, st,
+                           xs, static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1, XCD_CHUNK);
         if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
-        hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles + 7) / 8 * 8 * nt2)), dim3(256), 0, st, hid,
-                           static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2);
+        hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles * nt2 + span - 1) / span * span)), dim3(256), 0, st,
+                           hid, static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2, XCD_CHUNK);
         if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
     } else {
         // the paper's naive version: loop over the k*b expert uses, one expert call (two layers) per use
@@ -616,10 +630,10 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
         for (int e = 0; e < E; ++e)
             for (int pos = off[e]; pos < off[e + 1]; ++pos) {
                 if (pos % naive_stride) continue;
-                hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(8 * nt1), dim3(256), 0, st, xs + size_t(pos) * d,
-                                   w1 + size_t(e) * h * d, hid + size_t(pos) * h, unit, unit + 2, 1, h, d, nt1);
-                hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(8 * nt2), dim3(256), 0, st, hid + size_t(pos) * h,
-                                   w2 + size_t(e) * d * h, y + size_t(pos) * d, unit, unit + 2, 1, d, h, nt2);
+                hipLaunchKernelGGL((k_grouped_gemm<true>), dim3((nt1 + 7) / 8 * 8), dim3(256), 0, st, xs + size_t(pos) * d,
+                                   w1 + size_t(e) * h * d, hid + size_t(pos) * h, unit, unit + 2, 1, h, d, nt1, 1);
+                hipLaunchKernelGGL((k_grouped_gemm<false>), dim3((nt2 + 7) / 8 * 8), dim3(256), 0, st, hid + size_t(pos) * h,
+                                   w2 + size_t(e) * d * h, y + size_t(pos) * d, unit, unit + 2, 1, d, h, nt2, 1);
             }
         if (timed) { dynb::timing_mark(st, dynb::ST_FFN1, 0); dynb::timing_mark(st, dynb::ST_FFN2, 0); }
     }
