@@ -239,16 +239,20 @@ int moe_forward_naive(const moe_shape* shape, const void* x, const void* Wg, con
 /* ------------------------------------------------------------------------------------------- */
 
 typedef struct {
-    int32_t tag;    /* dynbatch_execute: index of the launch group; moe_forward: stage id
+    int32_t tag;    /* dynbatch_execute: index of the launch group, -2 for set-up; moe_forward: stage id
                        0 gate, 1 top-k, 2 grouping (counting sort), 3 permute, 4 expert layer 1,
                        5 expert layer 2, 6 combine                                               */
     int32_t units;  /* dynbatch_execute: module evaluations in the launch group; moe_forward: 0   */
     float ms;       /* GPU time between the HIP events that bracket the stage                    */
 } dynb_stage_time;
 
-/* Switches event recording on (1) or off (0, the default) for the calling thread.  While on,
- * dynbatch_execute and moe_forward record one HIP event per launch group / stage on the caller's
- * stream; this costs a few microseconds per event, so leave it off when measuring throughput.  */
+/* Switches event recording for the calling thread: 0 off (the default), 1 one HIP event per
+ * launch group (dynbatch_execute) or stage (moe_forward) on the caller's stream, 2 as 1 for
+ * moe_forward but a single pair of events around all launch groups of dynbatch_execute (one
+ * stage, tag 0, units = all module evaluations), which keeps the event records themselves out of
+ * the measured interval.  In both modes dynbatch_execute first reports its set-up work (weight
+ * repacking, copies of single-leaf programs) as a stage with tag -2.  An event costs a few
+ * microseconds, so leave timing off when measuring throughput.  Errors: DYNB_E_INVAL.           */
 int dynb_timing_enable(int on);
 
 /* Waits for the last timed call of this thread to finish on the GPU and returns its stages.

@@ -267,8 +267,9 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
 MOE_STAGES = ("gate", "topk", "sort", "permute", "ffn1", "ffn2", "combine")
 
 
-def dynb_timing_enable(on: bool) -> None:
-    _check(lib.dynb_timing_enable(1 if on else 0))
+def dynb_timing_enable(mode) -> None:
+    """0/False off, 1/True one event per launch group or stage, 2 one event pair around all launch groups."""
+    _check(lib.dynb_timing_enable(int(mode)))
 
 
 def dynb_timing_read():

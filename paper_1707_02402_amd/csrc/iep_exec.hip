@@ -612,8 +612,11 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
     a.w1 = w->w1; a.b1 = w->b1; a.w3a = w->w3a; a.b3a = w->b3a; a.w3b = w->w3b; a.b3b = w->b3b;
     a.C = s->C; a.H = s->H; a.W = s->W;
     const unsigned bx = unsigned((chw + 255) / 256);
-    const bool timed = dynb::timing_on();
+    const bool timed = dynb::timing_on(), coarse = dynb::timing_coarse();
+    if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
+    int32_t evals = 0;
     for (const dynb_launch& l : p->launches) {
+        evals += l.count;
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
         bool any_binary = false;
@@ -630,8 +633,9 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
             hipLaunchKernelGGL((k_gen_conv<T, false>), grid, dim3(256), 0, st, b);
             hipLaunchKernelGGL((k_gen_conv<T, true>), grid, dim3(256), 0, st, b);
         }
-        if (timed) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
+        if (timed && !coarse) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
+    if (coarse) dynb::timing_mark(st, 0, evals);
     HIP_TRY(hipGetLastError(), "dynbatch_execute(generic kernels)");
     return DYNB_OK;
 }
@@ -679,8 +683,11 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.w1 = pk1; a.b1 = w->b1;
     a.w3a = pk3a; a.b3a = w->b3a;
     a.w3b = pk3b; a.b3b = w->b3b;
-    const bool timed = dynb::timing_on();
+    const bool timed = dynb::timing_on(), coarse = dynb::timing_coarse();
+    if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
+    int32_t evals = 0;
     for (const dynb_launch& l : p->launches) {
+        evals += l.count;
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
         a.any_binary = 0;
@@ -699,8 +706,9 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
             hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else
             hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
-        if (timed) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
+        if (timed && !coarse) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
+    if (coarse) dynb::timing_mark(st, 0, evals);
     HIP_TRY(hipGetLastError(), "dynbatch_execute(mfma kernels)");
     return DYNB_OK;
 }

@@ -17,6 +17,7 @@ struct Mark {
 
 struct State {
     bool on = false;
+    bool coarse = false;
     std::vector<hipEvent_t> pool;   // events are created once and reused
     std::vector<Mark> marks;        // marks[0] opens the call
     size_t used = 0;
@@ -37,6 +38,7 @@ thread_local State g;
 }  // namespace
 
 bool timing_on() { return g.on; }
+bool timing_coarse() { return g.on && g.coarse; }
 
 void timing_begin(hipStream_t st)
 {
@@ -57,7 +59,9 @@ void timing_mark(hipStream_t st, int32_t tag, int32_t units)
 
 extern "C" int dynb_timing_enable(int on)
 {
+    if (on < 0 || on > 2) return dynb::fail(DYNB_E_INVAL, "dynb_timing_enable: mode must be 0, 1 or 2");
     dynb::g.on = (on != 0);
+    dynb::g.coarse = (on == 2);
     return DYNB_OK;
 }
 

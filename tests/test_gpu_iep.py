@@ -147,3 +147,33 @@ def test_execute_error_paths(dyn, util):
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_plan_upload(plan, torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.name == "DYNB_E_WORKSPACE"
+
+
+def test_stage_timing_modes(dyn, util):
+    """Mode 1: set-up stage, then one stage per launch group; mode 2: set-up stage, then one stage for all groups."""
+    import torch
+    w = iep.small_mixed(seed=77, B=9, C=128, H=14, W=14, dtype="bf16", min_len=3, max_len=9)
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity)
+    view = dyn.dynbatch_plan_view(plan)
+    dyn.dynbatch_plan_upload(plan)
+    weights = util.iep_weights_dev(w)
+    feats = util.to_dev(w.feats, "bf16")
+    out = torch.empty_like(feats)
+    ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, 1), dtype=torch.uint8, device="cuda")
+    try:
+        dyn.dynb_timing_enable(1)
+        dyn.dynbatch_execute(plan, weights, feats, out, ws)
+        st = dyn.dynb_timing_read()
+        assert [t for t, _, _ in st] == [-2] + list(range(view.n_launches))
+        assert sum(u for t, u, _ in st if t >= 0) == view.n_compute_nodes
+        assert all(ms >= 0 for _, _, ms in st)
+        dyn.dynb_timing_enable(2)
+        dyn.dynbatch_execute(plan, weights, feats, out, ws)
+        st2 = dyn.dynb_timing_read()
+        assert [(t, u) for t, u, _ in st2] == [(-2, 0), (0, view.n_compute_nodes)]
+        with pytest.raises(dyn.DynbError):
+            dyn.dynb_timing_enable(3)
+    finally:
+        dyn.dynb_timing_enable(0)
+    dyn.dynbatch_execute(plan, weights, feats, out, ws)      # untimed again: the marks of the last timed call stay readable
+    assert [(t, u) for t, u, _ in dyn.dynb_timing_read()] == [(-2, 0), (0, view.n_compute_nodes)]
