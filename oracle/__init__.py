@@ -62,7 +62,8 @@ class MalformedProgram(ValueError):
 
 
 def plan(prog, prog_off, arity, mode: int = 0) -> SimpleNamespace:
-    """Plan of a batch of prefix programs. mode 0: root-distance labels, 1: post-order position labels."""
+    """Plan of a batch of prefix programs. mode 0: root-distance labels, 1: post-order position labels,
+    2: dependency-depth labels (0 for leaves, pools run in ascending order)."""
     prog, prog_off = _i32(prog), _i32(prog_off)
     arity = np.ascontiguousarray(arity, dtype=np.uint8)
     B = len(prog_off) - 1

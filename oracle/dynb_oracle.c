@@ -99,9 +99,27 @@ static int32_t build(tree_ctx* c, int32_t pos, int32_t lvl)
     return next;
 }
 
+/* Dependency depth of a node (Discussion: batching "by dependency depth" as TensorFlow Fold
+ * does): a node without arguments has depth 0, any other node is one deeper than its deepest
+ * argument.  Plain recursion from the definition, recomputed for every node. */
+static int32_t dependency_depth(const int32_t* child0, const int32_t* child1, int32_t id)
+{
+    int32_t d = 0;
+    if (child0[id] >= 0) {
+        int32_t a = dependency_depth(child0, child1, child0[id]) + 1;
+        if (a > d) d = a;
+    }
+    if (child1[id] >= 0) {
+        int32_t b = dependency_depth(child0, child1, child1[id]) + 1;
+        if (b > d) d = b;
+    }
+    return d;
+}
+
 /* mode 0: label = distance from the root, pools run deepest label first (improved sort).
  * mode 1: label = position in the example's post-order queue, pools (grid columns) run in
  *         ascending order (standard sort).
+ * mode 2: label = dependency depth (0 for argument-free nodes), pools run in ascending order.
  * Within a label, one pool per function id, ascending; members ascending by node id.
  * Returns ORC_OK, or ORC_E_MALFORMED with *bad_example set.
  * Caller provides: level/type/child0/child1/members/in0/in1/out [N], root [B],
@@ -113,7 +131,7 @@ int oracle_plan(const int32_t* prog, const int32_t* prog_off, int32_t B, const u
                 int32_t* bucket_start, int32_t* bucket_count, int32_t* members, int32_t* in0,
                 int32_t* in1, int32_t* out, int32_t* bad_example)
 {
-    if (!prog || !prog_off || B <= 0 || !arity || n_types <= 0) return ORC_E_INVAL;
+    if (!prog || !prog_off || B <= 0 || !arity || n_types <= 0 || mode < 0 || mode > 2) return ORC_E_INVAL;
     int32_t N = prog_off[B];
     int32_t* rootdist = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
     int32_t* post = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
@@ -145,6 +163,8 @@ int oracle_plan(const int32_t* prog, const int32_t* prog_off, int32_t B, const u
         }
         if (mode == 1)
             for (int32_t j = 0; j < c.n_post; ++j) level[post[prog_off[i] + j]] = j;
+        if (mode == 2)
+            for (int32_t j = 0; j < c.len; ++j) level[c.base + j] = dependency_depth(child0, child1, c.base + j);
         for (int32_t j = 0; j < c.len; ++j)
             if (level[c.base + j] + 1 > D) D = level[c.base + j] + 1;   /* max over the minibatch */
     }

@@ -63,6 +63,20 @@ def postorder_positions(kids):
     return pos
 
 
+def peel_heights(kids):
+    """Dependency depth by peeling: round r removes the nodes whose arguments were all removed before round r."""
+    h = [-1] * len(kids)
+    left, r = len(kids), 0
+    while left:
+        now = [n for n in range(len(kids)) if h[n] < 0 and all(0 <= h[c] < r for c in kids[n])]
+        assert now
+        for n in now:
+            h[n] = r
+        left -= len(now)
+        r += 1
+    return h
+
+
 def expected_buckets(labels, types, descending):
     keys = sorted(range(len(labels)), key=lambda i: ((-labels[i] if descending else labels[i]), types[i], i))
     buckets = []
@@ -80,7 +94,7 @@ def check_against_independent(o, progs, arity, mode):
     for i, p in enumerate(progs):
         kids = parse_iterative(list(p), arity)
         assert kids is not None
-        lab = bfs_levels(kids) if mode == 0 else postorder_positions(kids)
+        lab = bfs_levels(kids) if mode == 0 else postorder_positions(kids) if mode == 1 else peel_heights(kids)
         labels += lab
         types += list(p)
         base = int(off[i])
@@ -113,7 +127,7 @@ def all_sequences(max_len):
             yield list(seq)
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 2])
 def test_brute_force_all_programs_up_to_length_7(oracle, mode):
     """Every sequence over {leaf, unary, binary} up to length 7: accepted iff well formed, labels as BFS."""
     good, bad = [], 0
@@ -156,6 +170,12 @@ def test_golden_hand_labelled_tree(oracle):
            for b in range(pl.n_buckets)]
     assert got == pools
     assert list(oracle.plan(prog, off, arity, mode=1).node_level) == rows["postorder"]
+    dd = oracle.plan(prog, off, arity, mode=2)
+    assert list(dd.node_level) == rows["depdepth"]
+    # ascending labels, then function id: SCENE leaves first, the root last and alone
+    assert (int(dd.bucket_level[0]), int(dd.bucket_type[0])) == (0, 0)
+    assert list(dd.members[:3]) == [3, 5, 8]
+    assert (int(dd.bucket_level[-1]), int(dd.bucket_type[-1]), int(dd.bucket_count[-1])) == (4, 3, 1)
 
 
 @pytest.mark.parametrize("n", [1, 2, 7, 30])
@@ -167,6 +187,30 @@ def test_chain_has_one_node_per_level(oracle, n):
     assert list(pl.node_level) == list(range(n))
     assert pl.n_buckets == n                       # one pool per (level, type)
     assert int(pl.bucket_count.sum()) == n
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 30])
+def test_chain_dependency_depth_counts_up_from_the_leaf(oracle, n):
+    arity = np.array([0, 1], np.uint8)
+    prog = np.array([1] * (n - 1) + [0], np.int32)
+    pl = oracle.plan(prog, np.array([0, n], np.int32), arity, mode=2)
+    assert pl.n_levels == n
+    assert list(pl.node_level) == list(range(n - 1, -1, -1))
+    assert list(pl.members) == list(range(n - 1, -1, -1))          # the leaf runs first, the root last
+
+
+@pytest.mark.parametrize("m", [0, 1, 3, 5])
+def test_balanced_tree_dependency_depth_mirrors_root_distance(oracle, m):
+    """In a full binary tree every leaf is equally deep, so depth-from-leaves = m - distance-from-root."""
+    g = np.random.default_rng(100 + m)
+    arity = np.array([0] + [2] * 8, np.uint8)
+    progs = [iep.balanced_program(g, m + 1, list(range(1, 9))) for _ in range(3)]
+    dd = check_against_independent(oracle, progs, arity, 2)
+    rd = check_against_independent(oracle, progs, arity, 0)
+    assert dd.n_levels == m + 1
+    assert (dd.node_level == m - rd.node_level).all()
+    for h in range(m + 1):
+        assert int((dd.node_level == h).sum()) == 3 * 2 ** (m - h)
 
 
 @pytest.mark.parametrize("m", [0, 1, 2, 4, 6])
@@ -193,7 +237,7 @@ def test_config1_is_the_stated_balanced_case(oracle):
     assert (pl.bucket_type != 0).sum() <= 4 * 8
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 2])
 def test_invariants_on_iep_shaped_batch(oracle, mode):
     w = iep.config2()
     pl = oracle.plan(w.prog, w.prog_off, w.arity, mode=mode)
@@ -213,11 +257,32 @@ def test_invariants_on_iep_shaped_batch(oracle, mode):
     # call-count bounds of the paper: O(p d) for the improved sort, O(p s) for the standard one
     compute = pl.bucket_type != 0
     s_max = int(np.diff(w.prog_off).max())
-    assert compute.sum() <= p * (pl.n_levels if mode == 0 else s_max)
+    assert compute.sum() <= p * (s_max if mode == 1 else pl.n_levels)
     assert pl.n_levels <= s_max
     # arity of a node = number of children
     ar = w.arity[pl.node_type]
     assert ((pl.child0 >= 0).astype(int) + (pl.child1 >= 0).astype(int) == ar).all()
+
+
+def test_dependency_depth_is_the_earliest_and_root_distance_the_latest_step(oracle):
+    """Both labellings are schedules with the same number of steps; a node can never be ready before its
+    dependency depth, and its root-distance label is the last step that still lets its consumers run in time."""
+    w = iep.config2()
+    rd = oracle.plan(w.prog, w.prog_off, w.arity, mode=0)
+    dd = oracle.plan(w.prog, w.prog_off, w.arity, mode=2)
+    assert dd.n_levels == rd.n_levels
+    D = rd.n_levels
+    assert (dd.node_level <= D - 1 - rd.node_level).all()
+    ar = w.arity[dd.node_type]
+    assert (dd.node_level[ar == 0] == 0).all() and (dd.node_level[ar > 0] >= 1).all()
+    # label = 1 + the larger of the arguments' labels
+    l0 = np.where(dd.child0 >= 0, dd.node_level[np.maximum(dd.child0, 0)], -1)
+    l1 = np.where(dd.child1 >= 0, dd.node_level[np.maximum(dd.child1, 0)], -1)
+    assert (dd.node_level == np.maximum(l0, l1) + 1).all()
+    # each example's root carries that example's depth; the deepest one defines D
+    assert int(dd.node_level[dd.root].max()) == D - 1
+    assert (dd.node_level[dd.root] == np.array(
+        [rd.node_level[w.prog_off[i]:w.prog_off[i + 1]].max() for i in range(w.B)])).all()
 
 
 def test_permuting_examples_keeps_pool_sizes(oracle):
