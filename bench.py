@@ -72,8 +72,10 @@ def main():
     plan_flags = dyn.DYNB_SCHED_IMPROVED | (0 if args.no_balance else dyn.DYNB_PLAN_BALANCE)
     plan0 = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, plan_flags)
     view = dyn.dynbatch_plan_view(plan0)
+    SCHEDULES = {"improved": dyn.DYNB_SCHED_IMPROVED, "improved+balance": dyn.DYNB_SCHED_IMPROVED | dyn.DYNB_PLAN_BALANCE,
+                 "standard": dyn.DYNB_SCHED_STANDARD, "dependency_depth": dyn.DYNB_SCHED_DEPTH}
     ws_bytes = max(dyn.dynbatch_workspace_bytes(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, f), w.C, w.H, w.W,
-                                                dyn.DYNB_BF16) for f in (plan_flags, dyn.DYNB_SCHED_NAIVE))
+                                                dyn.DYNB_BF16) for f in [dyn.DYNB_SCHED_NAIVE, *SCHEDULES.values()])
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     devbuf = torch.empty(dyn.dynbatch_plan_device_bytes(plan0) + 4096, dtype=torch.uint8, device="cuda")
     n_evals = view.n_compute_nodes
@@ -124,6 +126,23 @@ def main():
     kern_ms_step = float(np.mean(launch_ms))          # all module-kernel launches of one step
     avg_launch_us = kern_ms_step * 1e3 / launch_n
     achieved_tflops = flops_step / (kern_ms_step * 1e-3) / 1e12
+
+    # the paper's schedules side by side (execute only, plan reused): launch groups, widest group, time
+    sched_cmp = {}
+    for name, fl in SCHEDULES.items():
+        pl = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, fl)
+        dyn.dynbatch_plan_upload(pl, devbuf)
+        v_ = dyn.dynbatch_plan_view(pl)
+        for _ in range(3):
+            dyn.dynbatch_execute(pl, weights, feats, out, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            dyn.dynbatch_execute(pl, weights, feats, out, ws)
+        torch.cuda.synchronize()
+        sched_cmp[name] = {"launch_groups": int(v_.n_launches), "max_group": int(v_.max_launch_nodes),
+                           "pools": int((w.arity[v_.bucket_type] > 0).sum()),
+                           "execute_ms": round((time.perf_counter() - t0) * 1e3 / K, 4)}
 
     naive = None
     if not args.skip_naive:
@@ -269,7 +288,7 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic, "launches_per_step": launch_n, "avg_launch_us": round(avg_launch_us, 2),
                      "flops_per_step": flops_step},
-        "rooflines_other": moe_roof, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
+        "rooflines_other": moe_roof, "schedules": sched_cmp, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
         "paper_context": "paper reports ratios only: >14x cell execution (IEP, GTX 1080 Ti), up to 1000x (MoE, 11 GB card)",
     }
     print(json.dumps(res))

@@ -57,6 +57,11 @@ enum {
     /* Results / IEP, the unbatched original: an explicit loop over examples, one module per
      * call.  Same kernels, one launch per node; the comparison row for the speed-up.           */
     DYNB_SCHED_NAIVE = 2,
+    /* Discussion / batching "by dependency depth" (the TensorFlow Fold scheme the paper compares
+     * with): label = 0 for argument-free nodes, else one more than the deepest argument; equal
+     * labels are pooled over the minibatch and pools run in ascending label order.  Same number
+     * of labels as DYNB_SCHED_IMPROVED; every node runs as early as its arguments allow.        */
+    DYNB_SCHED_DEPTH = 3,
     DYNB_SCHED_MASK = 3,
     /* Optional, with DYNB_SCHED_IMPROVED only (ignored otherwise): balance the launch groups.  The
      * label of a node is the latest group it can run in; nodes whose arguments are ready earlier are
@@ -77,7 +82,8 @@ typedef struct dynb_plan dynb_plan;
 /* Logical plan, independent of how the executor lays out memory.  Node id = prog_off[example] +
  * position in that example's prefix sequence.  Pools ("buckets") are listed in execution order:
  * IMPROVED — label descending, then function id ascending; STANDARD — column ascending, then
- * function id ascending; NAIVE — one bucket per node, example by example in queue order.
+ * function id ascending; DEPTH — label ascending, then function id ascending; NAIVE — one bucket
+ * per node, example by example in queue order.
  * Members of a bucket are ascending node ids.  in0/in1 are the node ids of the members'
  * arguments (-1 if absent), out is the member itself.  SCENE buckets (arity 0) are listed but
  * cost no network call.  All arrays are owned by the plan and valid until dynbatch_plan_free. */

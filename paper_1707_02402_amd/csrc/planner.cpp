@@ -3,7 +3,8 @@
 // Paper: Background / Visual Reasoning Programs (a function sequence plus fixed arities gives a
 // unique tree, assembled depth first); Methods / Improved topological sort (label = distance from
 // the root, pool equal labels, at most p calls per pool) and Standard topological sort (queue per
-// program, b x s grid run column by column).  Results / IEP asks for exactly this code to be
+// program, b x s grid run column by column); Discussion (batching by dependency depth, as
+// TensorFlow Fold does: label = one more than the deepest argument).  Results / IEP asks for exactly this code to be
 // multithreaded native code because in the authors' Python it took over half of the run time.
 //
 // No GPU call in this file: it can be built and tested on a machine without a GPU.
@@ -35,10 +36,10 @@ struct Frame {
     uint8_t arity;
 };
 
-// Parses example `ex`; fills level (root distance), children, queue position and example id.
+// Parses example `ex`; fills root distance, dependency depth, children and queue position.
 // Returns false if the sequence is not exactly one complete tree.
 bool parse_example(const int32_t* prog, int32_t base, int32_t len, const uint8_t* arity,
-                   int32_t n_types, int32_t* rootdist, int32_t* child0, int32_t* child1,
+                   int32_t n_types, int32_t* rootdist, int32_t* depdepth, int32_t* child0, int32_t* child1,
                    int32_t* queue_pos, std::vector<Frame>& stack)
 {
     if (len <= 0) return false;
@@ -61,9 +62,15 @@ bool parse_example(const int32_t* prog, int32_t base, int32_t len, const uint8_t
         }
         if (arity[t] == 0) {
             queue_pos[id] = done++;
-            // every enclosing function whose last argument just closed enters the queue too
+            depdepth[id] = 0;
+            // every enclosing function whose last argument just closed enters the queue too;
+            // its arguments' depths are final by then
             while (!stack.empty() && stack.back().filled == stack.back().arity) {
-                queue_pos[base + stack.back().node] = done++;
+                const int32_t fid = base + stack.back().node;
+                queue_pos[fid] = done++;
+                int32_t deepest = depdepth[child0[fid]];
+                if (child1[fid] >= 0) deepest = std::max(deepest, depdepth[child1[fid]]);
+                depdepth[fid] = deepest + 1;
                 stack.pop_back();
             }
         } else {
@@ -89,7 +96,6 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
     const bool balance = (flags & DYNB_PLAN_BALANCE) != 0;
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
-    if (mode > DYNB_SCHED_NAIVE) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown scheduling mode");
     for (int32_t t = 0; t < n_types; ++t)
         if (arity[t] > 2)
             return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: function " + std::to_string(t) + " has arity > 2");
@@ -105,7 +111,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(prog, prog + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);
-        std::vector<int32_t> rootdist(N), queue_pos(N), example(N);
+        std::vector<int32_t> rootdist(N), depdepth(N), queue_pos(N), example(N);
 
         // ---- trees: examples are independent, so large batches are parsed by several threads
         std::atomic<int32_t> first_bad(B);
@@ -114,7 +120,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
             stack.reserve(64);
             for (int32_t i = lo; i < hi; ++i) {
                 const int32_t base = prog_off[i], len = prog_off[i + 1] - base;
-                bool ok = dynb::parse_example(prog, base, len, arity, n_types, rootdist.data(),
+                bool ok = dynb::parse_example(prog, base, len, arity, n_types, rootdist.data(), depdepth.data(),
                                               p->child0.data(), p->child1.data(), queue_pos.data(), stack);
                 if (!ok) {
                     int32_t cur = first_bad.load();
@@ -144,10 +150,10 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         }
 
         // ---- labels
-        const bool improved = (mode == DYNB_SCHED_IMPROVED);
+        const bool improved = (mode == DYNB_SCHED_IMPROVED), by_depth = (mode == DYNB_SCHED_DEPTH);
         int32_t D = 0;
         for (int32_t n = 0; n < N; ++n) {
-            p->level[n] = improved ? rootdist[n] : queue_pos[n];
+            p->level[n] = improved ? rootdist[n] : by_depth ? depdepth[n] : queue_pos[n];
             D = std::max(D, p->level[n] + 1);
         }
         p->D = D;
@@ -307,7 +313,11 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         // 3. slots and items
         std::vector<int32_t> slot(N, -1);
         {
+            // Root-distance labels put every argument exactly one label below its consumer, so two
+            // alternating halves suffice.  Balanced and dependency-depth plans keep a result for several
+            // groups: they recycle slots through a free list once the consuming group has been issued.
             const bool pingpong = improved && !balance;
+            const bool recycle = (improved && balance) || by_depth;
             int32_t maxw = 0, running = 0;
             std::vector<int32_t> rank_in_level(D, 0);
             if (pingpong) {
@@ -331,13 +341,13 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
                     // arguments of a label-l node all sit at label l+1: two alternating halves suffice
                     slot[n] = (p->level[n] & 1) * maxw + rank_in_level[p->level[n]]++;
                 } else if (!is_root) {
-                    if (improved && !free_slots.empty()) { slot[n] = free_slots.back(); free_slots.pop_back(); }
+                    if (recycle && !free_slots.empty()) { slot[n] = free_slots.back(); free_slots.pop_back(); }
                     else slot[n] = running++;
                 }
                 auto src = [&](int32_t c) -> int32_t {
                     if (c < 0) return 0;
                     if (!is_compute(c)) return -1 - example[c];
-                    if (improved && !pingpong) release.push_back(slot[c]);
+                    if (recycle) release.push_back(slot[c]);
                     return slot[c];
                 };
                 dynb_item it;

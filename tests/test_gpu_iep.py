@@ -27,7 +27,7 @@ def util():
     return gpu_util
 
 
-@pytest.mark.parametrize("flags", [0, 1, 2])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_config0_fp32_all_schedules(dyn, util, oracle, flags):
     w = iep.config0()
     ref = oracle.iep_forward_workload(w)
@@ -47,7 +47,7 @@ def test_generic_kernels_on_ragged_shapes(dyn, util, oracle, dtype, C, H, W):
             assert (got[i] == w.feats[i]).all()
 
 
-@pytest.mark.parametrize("flags", [0, 1, 2])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_mfma_path_small_batch_every_element(dyn, util, oracle, flags):
     """bf16, C=128, 14x14: 13 pixel tiles with a ragged last tile, unary and binary functions,
     single-SCENE programs, odd batch so the two-node workgroups get a lone node."""
@@ -177,3 +177,12 @@ def test_stage_timing_modes(dyn, util):
         dyn.dynb_timing_enable(0)
     dyn.dynbatch_execute(plan, weights, feats, out, ws)      # untimed again: the marks of the last timed call stay readable
     assert [(t, u) for t, u, _ in dyn.dynb_timing_read()] == [(-2, 0), (0, view.n_compute_nodes)]
+
+
+def test_dependency_depth_schedule_on_config2_equals_improved_bitwise(dyn, util):
+    """Discussion / batching by dependency depth: another valid order of the same module calls, so the same bits;
+    its slot recycling (results live until their consumer's label) is exercised at full size."""
+    w = iep.config2()
+    a = util.iep_run(dyn, w, dyn.DYNB_SCHED_IMPROVED)
+    b = util.iep_run(dyn, w, dyn.DYNB_SCHED_DEPTH)
+    assert (a == b).all()

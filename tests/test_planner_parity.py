@@ -26,24 +26,33 @@ def assert_same_plan(v, o):
         assert a.dtype == np.int32 and a.shape == b.shape and (a == b).all(), f
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+# (library scheduling mode, oracle labelling mode): improved, standard, dependency depth
+MODES = [(0, 0), (1, 1), (3, 2)]
+
+
+@pytest.mark.parametrize("mode,omode", MODES)
 @pytest.mark.parametrize("cfg", ["config0", "config1", "config2"])
-def test_plan_is_bit_exact_on_the_configs(dyn, oracle, cfg, mode):
+def test_plan_is_bit_exact_on_the_configs(dyn, oracle, cfg, mode, omode):
     w = getattr(iep, cfg)()
     plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, mode)
     v = dyn.dynbatch_plan_view(plan)
-    assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=mode))
+    assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=omode))
     assert v.n_compute_nodes == w.n_module_evals
     if mode == 0:
         assert v.n_launches == v.n_levels - 1          # deepest label of these configs holds only SCENE leaves
+    if mode == 3:
+        assert v.n_launches == v.n_levels - 1          # label 0 holds exactly the SCENE leaves
+        compute = w.arity[v.node_type] > 0
+        assert (v.node_launch[compute] == v.node_level[compute] - 1).all()
+        assert v.n_slots <= v.n_compute_nodes
 
 
 def test_plan_is_bit_exact_on_many_random_batches(dyn, oracle):
     for seed in range(40):
         w = iep.small_mixed(seed=seed, B=1 + seed % 9, C=1, H=1, W=1, dtype="f32", min_len=1, max_len=3 + seed)
-        for mode in (0, 1):
+        for mode, omode in MODES:
             v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, mode))
-            assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=mode))
+            assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=omode))
 
 
 def test_threaded_parse_of_a_large_batch(dyn, oracle):
