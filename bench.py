@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--no-balance", action="store_true", help="plain improved sort, no pull-forward of nodes")
     ap.add_argument("--skip-moe", action="store_true")
     ap.add_argument("--skip-naive", action="store_true")
+    ap.add_argument("--skip-schedules", action="store_true", help="skip the side-by-side timing of the four schedules")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--moe-config", choices=["config3", "config4"], default="config4")
     args = ap.parse_args()
@@ -129,7 +130,7 @@ def main():
 
     # the paper's schedules side by side (execute only, plan reused): launch groups, widest group, time
     sched_cmp = {}
-    for name, fl in SCHEDULES.items():
+    for name, fl in ([] if args.skip_schedules else SCHEDULES.items()):
         pl = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, fl)
         dyn.dynbatch_plan_upload(pl, devbuf)
         v_ = dyn.dynbatch_plan_view(pl)

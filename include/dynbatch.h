@@ -66,7 +66,8 @@ enum {
     /* Optional, with DYNB_SCHED_IMPROVED only (ignored otherwise): balance the launch groups.  The
      * label of a node is the latest group it can run in; nodes whose arguments are ready earlier are
      * pulled forward out of groups wider than the chip's 256 CUs into earlier groups with idle CUs
-     * (Discussion: "optimize the order of dependency execution").  The logical plan (labels, pools)
+     * (the Discussion notes that the order of dependency execution could be optimised and does
+     * not pursue it).  The logical plan (labels, pools)
      * is unchanged; only node_launch and the executor's work lists differ.                       */
     DYNB_PLAN_BALANCE = 4
 };
@@ -226,8 +227,8 @@ int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const voi
                 const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* The unbatched comparison row of Results / Sparsely Gated Mixture of Experts ("the naive
- * implementation loops over and executes the kb experts independently"): gate, top-k, grouping and
+/* The unbatched comparison row of Results / Sparsely Gated Mixture of Experts (the naive version
+ * there runs each of the k*b expert uses on its own, in a loop): gate, top-k, grouping and
  * permute as in moe_forward, then one expert call (both layers, same kernels, one row) per use,
  * issued from a host loop, then combine.  Synchronises the stream once to read the group sizes.
  *   use_stride  >= 1; 1 executes every use and gives the same `out` as moe_forward; a larger

@@ -1,5 +1,5 @@
 // GPU executor of a plan: gather -> batched residual conv module -> scatter, one launch group
-// per label (paper: Methods, "each pool is executed at once"; Results / IEP, "data stacking").
+// per label (paper: Methods / Improved topological sort, a pool is executed as one batch; Results / IEP, data stacking).
 //
 // Two kernel families with the same semantics:
 //   * k_module_mfma  — bf16, C = 128, 14 x 14: one fused kernel per launch group.  A workgroup

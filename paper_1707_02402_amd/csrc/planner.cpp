@@ -219,7 +219,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         // node may run in; a node whose arguments finish early can run earlier.  Launch groups with
         // more nodes than the chip has CUs (256) cost a second round, so nodes are pulled forward out
         // of such groups into earlier groups that have idle CUs (earliest deadline first).  The paper
-        // mentions this freedom ("optimize the order of dependency execution") and leaves it aside.
+        // mentions in its Discussion that the execution order could be optimised and leaves it aside.
         if (improved && balance && n_launch > 1) {
             const int32_t S = n_launch;
             constexpr int32_t CUS = 256, HALF_CUS = 128;
