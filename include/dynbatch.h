@@ -161,7 +161,25 @@ typedef struct {
     const float* b3a;         /* device [n_types][C]            fp32;  NULL = no bias            */
     const void* w3b;          /* device [n_types][C][3][3][C]   dtype                            */
     const float* b3b;         /* device [n_types][C]            fp32;  NULL = no bias            */
+    const void* packed;       /* device, optional: the three weight tensors in the fast path's
+                                 MFMA fragment order, written by dynbatch_pack_weights for the same
+                                 n_types and shape.  NULL: dynbatch_execute repacks w1, w3a, w3b into
+                                 its workspace on every call (about 20 us for 41 functions).
+                                 Ignored by shapes without a fast path.  The caller keeps it in
+                                 step with the weights: repack after they change.               */
 } dynb_module_weights;
+
+/* Bytes of the packed copy for n_types functions (0 if the shape has no fast path or on bad input). */
+size_t dynbatch_packed_weights_bytes(const dynb_shape* shape, int32_t n_types);
+
+/* One-time preparation of constant weights (the paper's modules are fixed at inference time):
+ * writes w->w1 (if not NULL), w->w3a and w->w3b in fragment order into `packed`, asynchronously on
+ * `stream`.  Biases are not part of the packed copy.
+ *   packed   device, >= dynbatch_packed_weights_bytes, 256-byte aligned, caller-owned
+ * Errors: DYNB_E_INVAL (NULL, n_types <= 0, misaligned), DYNB_E_UNSUPPORTED (shape without a fast
+ * path), DYNB_E_WORKSPACE (too small), DYNB_E_HIP.                                              */
+int dynbatch_pack_weights(const dynb_shape* shape, int32_t n_types, const dynb_module_weights* w,
+                          void* packed, size_t packed_bytes, void* stream);
 
 /* Bytes of device workspace dynbatch_execute needs for this plan and shape (0 on bad input).   */
 size_t dynbatch_workspace_bytes(const dynb_plan* plan, const dynb_shape* shape);

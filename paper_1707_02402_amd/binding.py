@@ -23,6 +23,7 @@ ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "D
 
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
+           "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
            "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_naive", "dynb_timing_enable",
            "dynb_timing_read"]
 
@@ -50,7 +51,7 @@ class _Shape(ct.Structure):
 
 
 class _Weights(ct.Structure):
-    _fields_ = [(n, ct.c_void_p) for n in ("w1", "b1", "w3a", "b3a", "w3b", "b3b")]
+    _fields_ = [(n, ct.c_void_p) for n in ("w1", "b1", "w3a", "b3a", "w3b", "b3b", "packed")]
 
 
 class _MoeShape(ct.Structure):
@@ -82,6 +83,10 @@ def _load():
     L.dynbatch_workspace_bytes.restype = ct.c_size_t
     L.dynbatch_execute.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p,
                                    ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynbatch_packed_weights_bytes.argtypes = [ct.POINTER(_Shape), ct.c_int32]
+    L.dynbatch_packed_weights_bytes.restype = ct.c_size_t
+    L.dynbatch_pack_weights.argtypes = [ct.POINTER(_Shape), ct.c_int32, ct.POINTER(_Weights), ct.c_void_p, ct.c_size_t,
+                                        ct.c_void_p]
     L.moe_workspace_bytes.argtypes = [ct.POINTER(_MoeShape)]
     L.moe_workspace_bytes.restype = ct.c_size_t
     L.moe_forward.argtypes = [ct.POINTER(_MoeShape), ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p,
@@ -188,8 +193,32 @@ def dynbatch_workspace_bytes(plan: Plan, C: int, H: int, W: int, dtype: int) -> 
     return int(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(_Shape(C, H, W, dtype))))
 
 
+def _weights_struct(weights: dict) -> _Weights:
+    return _Weights(*[(t.data_ptr() if t is not None else None) for t in
+                      (weights.get(k) for k in ("w1", "b1", "w3a", "b3a", "w3b", "b3b", "packed"))])
+
+
+def dynbatch_packed_weights_bytes(C: int, H: int, W: int, dtype: int, n_types: int) -> int:
+    return int(lib.dynbatch_packed_weights_bytes(ct.byref(_Shape(C, H, W, dtype)), n_types))
+
+
+def dynbatch_pack_weights(weights: dict, C: int, H: int, W: int, dtype: int, packed=None, stream=None):
+    """One-time preparation: returns a device buffer to pass as weights["packed"]."""
+    import torch
+    n_types = int(weights["w3a"].shape[0])
+    shape = _Shape(C, H, W, dtype)
+    if packed is None:
+        packed = torch.empty(max(int(lib.dynbatch_packed_weights_bytes(ct.byref(shape), n_types)), 256),
+                             dtype=torch.uint8, device=weights["w3a"].device)
+    w = _weights_struct({**weights, "packed": None})
+    _check(lib.dynbatch_pack_weights(ct.byref(shape), n_types, ct.byref(w), _ptr(packed),
+                                     packed.numel() * packed.element_size(), _stream(stream)))
+    return packed
+
+
 def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None, stream=None):
-    """weights: dict with device tensors w1,b1,w3a,b3a,w3b,b3b (biases float32 or None; w1 may be None).
+    """weights: dict with device tensors w1,b1,w3a,b3a,w3b,b3b (biases float32 or None; w1 may be None)
+    and optionally packed (from dynbatch_pack_weights).
     feats: device [B,H,W,C] float32 or bfloat16, contiguous.  Returns out [B,H,W,C]."""
     import torch
     assert feats.is_cuda and feats.is_contiguous() and feats.shape[0] == plan.B
@@ -206,8 +235,7 @@ def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None,
     if workspace is None:
         workspace = torch.empty(int(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(shape))), dtype=torch.uint8,
                                 device=feats.device)
-    w = _Weights(*[(t.data_ptr() if t is not None else None) for t in
-                   (weights.get(k) for k in ("w1", "b1", "w3a", "b3a", "w3b", "b3b"))])
+    w = _weights_struct(weights)
     _check(lib.dynbatch_execute(plan.handle, ct.byref(shape), ct.byref(w), _ptr(feats), _ptr(out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
     return out

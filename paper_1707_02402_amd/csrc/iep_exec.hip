@@ -640,6 +640,20 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
     return DYNB_OK;
 }
 
+// w1 (2 halves), w3a, w3b (9 taps each) -> fragment order at pk: [w3a | w3b | w1]
+static void launch_pack(const dynb_module_weights* w, int n_types, char* pk, hipStream_t st)
+{
+    const size_t tap_bytes = size_t(n_types) * 128 * 128 * 2;
+    const unsigned g9 = unsigned(std::min<size_t>((size_t(n_types) * 4 * 9 * 512 + 255) / 256, 4096));
+    hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3a),
+                       reinterpret_cast<u32x4*>(pk), n_types, 9);
+    hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3b),
+                       reinterpret_cast<u32x4*>(pk + 9 * tap_bytes), n_types, 9);
+    if (w->w1)
+        hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w1),
+                           reinterpret_cast<u32x4*>(pk + 18 * tap_bytes), n_types, 2);
+}
+
 static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void* feats, void* out, char* ws,
                     hipStream_t st)
 {
@@ -664,22 +678,15 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.feats = static_cast<const bf16_t*>(feats);
     a.out = static_cast<bf16_t*>(out);
     a.slots = reinterpret_cast<bf16_t*>(ws);
-    // repack the weights into fragment order behind the slots (about 0.6 MB per function)
+    // weights in fragment order: the caller's prepared copy, or a fresh one behind the slots
+    // (about 0.6 MB per function)
     const size_t tap_bytes = size_t(p->n_types) * 128 * 128 * 2;
-    char* pk = ws + align256(size_t(p->n_slots) * mf::P * mf::C * 2);
+    char* pk = w->packed ? static_cast<char*>(const_cast<void*>(w->packed))
+                         : ws + align256(size_t(p->n_slots) * mf::P * mf::C * 2);
     bf16_t* pk3a = reinterpret_cast<bf16_t*>(pk);
     bf16_t* pk3b = reinterpret_cast<bf16_t*>(pk + 9 * tap_bytes);
     bf16_t* pk1 = reinterpret_cast<bf16_t*>(pk + 18 * tap_bytes);
-    {
-        const unsigned g9 = unsigned(std::min<size_t>((size_t(p->n_types) * 4 * 9 * 512 + 255) / 256, 4096));
-        hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3a),
-                           reinterpret_cast<u32x4*>(pk3a), p->n_types, 9);
-        hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w3b),
-                           reinterpret_cast<u32x4*>(pk3b), p->n_types, 9);
-        if (w->w1)
-            hipLaunchKernelGGL(k_pack_weights, dim3(g9), dim3(256), 0, st, static_cast<const u32x4*>(w->w1),
-                               reinterpret_cast<u32x4*>(pk1), p->n_types, 2);
-    }
+    if (!w->packed) launch_pack(w, p->n_types, pk, st);
     a.w1 = pk1; a.b1 = w->b1;
     a.w3a = pk3a; a.b3a = w->b3a;
     a.w3b = pk3b; a.b3b = w->b3b;
@@ -710,6 +717,26 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     }
     if (coarse) dynb::timing_mark(st, 0, evals);
     HIP_TRY(hipGetLastError(), "dynbatch_execute(mfma kernels)");
+    return DYNB_OK;
+}
+
+extern "C" size_t dynbatch_packed_weights_bytes(const dynb_shape* s, int32_t n_types)
+{
+    if (!s || n_types <= 0 || !fast_shape(s)) return 0;
+    return align256(packed_weight_bytes(n_types));
+}
+
+extern "C" int dynbatch_pack_weights(const dynb_shape* s, int32_t n_types, const dynb_module_weights* w, void* packed,
+                                     size_t packed_bytes, void* stream)
+{
+    if (!s || !w || !packed || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_pack_weights: NULL argument or n_types <= 0");
+    if (!fast_shape(s)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_pack_weights: this shape has no packed layout");
+    if (!w->w3a || !w->w3b) return fail(DYNB_E_INVAL, "dynbatch_pack_weights: conv3x3 weights missing");
+    if (reinterpret_cast<uintptr_t>(packed) & 255) return fail(DYNB_E_INVAL, "dynbatch_pack_weights: buffer not 256-byte aligned");
+    if (packed_bytes < dynbatch_packed_weights_bytes(s, n_types))
+        return fail(DYNB_E_WORKSPACE, "dynbatch_pack_weights: buffer too small");
+    launch_pack(w, n_types, static_cast<char*>(packed), static_cast<hipStream_t>(stream));
+    HIP_TRY(hipGetLastError(), "dynbatch_pack_weights");
     return DYNB_OK;
 }
 

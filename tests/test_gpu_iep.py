@@ -186,3 +186,31 @@ def test_dependency_depth_schedule_on_config2_equals_improved_bitwise(dyn, util)
     a = util.iep_run(dyn, w, dyn.DYNB_SCHED_IMPROVED)
     b = util.iep_run(dyn, w, dyn.DYNB_SCHED_DEPTH)
     assert (a == b).all()
+
+
+def test_prepared_weights_give_the_same_bits(dyn, util):
+    """dynbatch_pack_weights once, then execute with weights.packed: same kernels on the same fragments."""
+    import torch
+    w = iep.small_mixed(seed=31, B=13, C=128, H=14, W=14, dtype="bf16", min_len=2, max_len=9)
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity)
+    dyn.dynbatch_plan_upload(plan)
+    weights = util.iep_weights_dev(w)
+    feats = util.to_dev(w.feats, "bf16")
+    a = dyn.dynbatch_execute(plan, weights, feats)
+    nbytes = dyn.dynbatch_packed_weights_bytes(w.C, w.H, w.W, dyn.DYNB_BF16, w.n_types)
+    assert nbytes == w.n_types * 20 * 128 * 128 * 2
+    packed = dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16)
+    assert packed.numel() == nbytes
+    prepared = dict(weights, packed=packed)
+    b = dyn.dynbatch_execute(plan, prepared, feats)
+    c = dyn.dynbatch_execute(plan, prepared, feats)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(b, c)
+    # shapes without a fast path have no packed layout
+    assert dyn.dynbatch_packed_weights_bytes(16, 8, 8, dyn.DYNB_F32, 5) == 0
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_pack_weights(weights, 16, 8, 8, dyn.DYNB_F32)
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16, packed=packed[:4096])
+    assert e.value.name == "DYNB_E_WORKSPACE"
