@@ -214,3 +214,32 @@ def test_prepared_weights_give_the_same_bits(dyn, util):
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16, packed=packed[:4096])
     assert e.value.name == "DYNB_E_WORKSPACE"
+
+
+@pytest.mark.parametrize("dtype,C,H,W", [("bf16", 128, 14, 14), ("f32", 4, 3, 3)])
+def test_batches_without_any_module_call(dyn, util, dtype, C, H, W):
+    """Every program is a lone SCENE token: no launch group, the output is the input, bit for bit."""
+    w = iep.small_mixed(seed=2, B=5, C=C, H=H, W=W, dtype=dtype, min_len=1, max_len=1)
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
+    assert v.n_compute_nodes == 0 and v.n_launches == 0 and v.n_levels == 1
+    got = util.iep_run(dyn, w)
+    assert (got == w.feats).all()
+
+
+@pytest.mark.parametrize("dtype,C,H,W", [("bf16", 128, 14, 14), ("f32", 3, 2, 5)])
+def test_single_example_single_module(dyn, util, oracle, dtype, C, H, W):
+    w = iep.small_mixed(seed=4, B=1, C=C, H=H, W=W, dtype=dtype, min_len=2, max_len=2)
+    assert w.n_module_evals == 1
+    got = util.iep_run(dyn, w)
+    assert util.normwise(got, oracle.iep_forward_workload(w)) < TOL[dtype]
+
+
+def test_generic_path_launch_group_wider_than_one_grid(dyn, util, oracle):
+    """33000 one-module programs: the generic kernels split a launch group at 32768 nodes (grid.y limit)."""
+    w = iep.small_mixed(seed=6, B=33000, C=2, H=2, W=3, dtype="f32", min_len=2, max_len=2)
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
+    assert v.max_launch_nodes == 33000
+    got = util.iep_run(dyn, w)
+    ref = oracle.iep_forward_workload(w)
+    assert util.normwise(got, ref) < TOL["f32"]
+    assert util.normwise(got[32760:32780], ref[32760:32780]) < TOL["f32"]      # around the split

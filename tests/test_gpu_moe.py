@@ -153,3 +153,28 @@ def test_moe_error_paths(dyn, util):
     with pytest.raises(dyn.DynbError) as e:
         dyn.moe_forward(dev["x"], dev["Wg"], None, dev["noise"], dev["W1"], dev["W2"], 2)
     assert e.value.name == "DYNB_E_INVAL"
+
+
+def test_zero_tokens_is_a_successful_no_op(dyn):
+    import torch
+    d, h, E, k = 32, 32, 4, 2
+    z = lambda *shape, dt=torch.bfloat16: torch.zeros(shape, dtype=dt, device="cuda")
+    out = dyn.moe_forward(z(0, d), z(E, d), z(E, d), z(0, E, dt=torch.float32), z(E, h, d), z(E, d, h), k)
+    assert out.shape == (0, d)
+
+
+def test_every_token_to_one_expert_with_a_one_row_tail_tile(dyn, util, oracle):
+    """k = 1 and one dominant gate column: a single group of 64*9 + 1 rows, every other group empty."""
+    m = moe.small(seed=40, T=577, d=64, h=96, E=6, k=1)
+    Wg = np.zeros_like(m.Wg)
+    Wg[:, 4] = 0.0
+    noise = np.full_like(m.noise, -8.0)
+    noise[:, 4] = 8.0                                   # softplus(0) = ln 2: logit +-5.5, expert 4 always wins
+    from dataclasses import replace
+    m = replace(m, Wg=Wg, Wn=np.zeros_like(m.Wn), noise=noise)
+    W1, W2 = stack(m)
+    out, aux = util.moe_run(dyn, m, W1, W2)
+    assert (aux["topk_idx"] == 4).all() and aux["counts"].tolist() == [0, 0, 0, 0, 577, 0]
+    assert (aux["perm"] == np.arange(577)).all() and np.allclose(aux["topk_w"], 1.0)
+    ref = oracle.moe_experts(m.x, aux["topk_idx"], aux["topk_w"], W1, W2)
+    assert util.normwise(out, ref) < OUT_TOL
