@@ -34,10 +34,12 @@ PEAK_HBM_GBS = 8000.0
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--iep-config", choices=["config1", "config2"], default="config2")
     ap.add_argument("--no-balance", action="store_true", help="plain improved sort, no pull-forward of nodes")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="program-tree batches in flight: step i runs on HIP stream i %% streams with its own workspace")
     ap.add_argument("--skip-moe", action="store_true")
     ap.add_argument("--skip-naive", action="store_true")
     ap.add_argument("--no-prepare", action="store_true", help="repack the module weights inside every dynbatch_execute")
@@ -90,28 +92,45 @@ def main():
         f"launches={view.n_launches} buckets={view.n_buckets}")
 
     keep = []
+    # Independent batches may be in flight together: every lane is a HIP stream (default priority) with its
+    # own plan buffer, workspace and output, all resident in HBM.  Lane 0 is the current stream.
+    S = max(1, args.streams)
+    lanes = [dict(stream=None, devbuf=devbuf, ws=ws, out=out)]
+    for _ in range(S - 1):
+        lanes.append(dict(stream=torch.cuda.Stream(), devbuf=torch.empty_like(devbuf), ws=torch.empty_like(ws),
+                          out=torch.empty_like(out)))
 
-    def iep_step(flags=plan_flags, host_ms=None):
+    def iep_step(flags=plan_flags, host_ms=None, lane=None):
+        ln = lane if lane is not None else lanes[0]
         t0 = time.perf_counter()
         plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
         t1 = time.perf_counter()
-        dyn.dynbatch_plan_upload(plan, devbuf)
-        dyn.dynbatch_execute(plan, weights, feats, out, ws)
+        dyn.dynbatch_plan_upload(plan, ln["devbuf"], stream=ln["stream"])
+        dyn.dynbatch_execute(plan, weights, feats, ln["out"], ln["ws"], stream=ln["stream"])
         if host_ms is not None:
             host_ms.append((t1 - t0) * 1e3)
         keep.append(plan)
 
-    for _ in range(Wm):
-        iep_step()
-    torch.cuda.synchronize()
-    keep.clear()
-    plan_ms = []
-    t0 = time.perf_counter()
-    for _ in range(K):
-        iep_step(host_ms=plan_ms)
-    torch.cuda.synchronize()
-    iep_ms = (time.perf_counter() - t0) * 1e3 / K
-    keep.clear()
+    def timed_steps(n_lanes, flags):
+        for i in range(Wm):
+            iep_step(flags, lane=lanes[i % n_lanes])
+        torch.cuda.synchronize()
+        keep.clear()
+        host = []
+        t0 = time.perf_counter()
+        for i in range(K):
+            iep_step(flags, host_ms=host, lane=lanes[i % n_lanes])
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / K
+        keep.clear()
+        return ms, host
+
+    one_ms, plan_ms = timed_steps(1, plan_flags)      # one batch at a time: the latency of a step
+    iep_ms = one_ms
+    if S > 1:                                         # S batches in flight: the throughput figure
+        iep_ms, plan_ms = timed_steps(S, plan_flags | dyn.DYNB_PLAN_THROUGHPUT)
+        for ln in lanes[1:]:
+            assert torch.equal(ln["out"], lanes[0]["out"])
 
     # execute only (plan reused), and per-launch-group GPU times from HIP events on the same stream
     dyn.dynbatch_plan_upload(plan0, devbuf)
@@ -159,7 +178,7 @@ def main():
         naive_ms = (time.perf_counter() - t0) * 1e3
         keep.clear()
         naive = {"kind": "same kernels, one launch per node, example by example", "ms_per_step": round(naive_ms, 3),
-                 "module_evals_per_sec": round(n_evals / naive_ms * 1e3, 1), "speedup_batched": round(naive_ms / iep_ms, 2)}
+                 "module_evals_per_sec": round(n_evals / naive_ms * 1e3, 1), "speedup_batched": round(naive_ms / one_ms, 2), "speedup_note": "against one batched step at a time on one stream"}
 
     # ------------------------------------------------------------------ mixture of experts
     moe_res, moe_roof = None, []
@@ -286,7 +305,11 @@ def main():
         "config": {"workload": w.name, "batch": w.B, "nodes": int(view.n_nodes), "module_evals": int(n_evals),
                    "levels": int(view.n_levels), "launch_groups": int(view.n_launches), "C": w.C, "H": w.H, "W": w.W,
                    "step": "dynbatch_plan + dynbatch_plan_upload + dynbatch_execute",
+                   "batches_in_flight": S, "kernel_layout": "throughput (DYNB_PLAN_THROUGHPUT)" if S > 1 else "latency",
+                   "weights": "repacked per call" if args.no_prepare else "fragment order prepared once (dynbatch_pack_weights)",
                    "schedule": "improved topological sort" + ("" if args.no_balance else " + balanced launch groups")},
+        "single_stream": {"ms_per_step": round(one_ms, 4), "module_evals_per_sec": round(n_evals / one_ms * 1e3, 1)},
+        "chip_mfma_frac_of_step": round(flops_step / (iep_ms * 1e-3) / 1e12 / 2500.0, 4),
         "plan_host_ms": round(float(np.mean(plan_ms)), 4), "execute_only_ms": round(exec_ms, 4),
         "execute_only_module_evals_per_sec": round(n_evals / exec_ms * 1e3, 1),
         "roofline": {"kernel": "k_module_mfma", "bound": "mfma", "achieved": round(achieved_tflops, 2),

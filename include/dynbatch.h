@@ -69,7 +69,13 @@ enum {
      * (the Discussion notes that the order of dependency execution could be optimised and does
      * not pursue it).  The logical plan (labels, pools)
      * is unchanged; only node_launch and the executor's work lists differ.                       */
-    DYNB_PLAN_BALANCE = 4
+    DYNB_PLAN_BALANCE = 4,
+    /* Optional, any scheduling mode: the caller keeps several independent batches in flight (one
+     * HIP stream and workspace each) and wants chip throughput rather than the latency of one
+     * batch.  dynbatch_execute then always uses its kernel layout with the most work per CU (two
+     * nodes per workgroup) instead of spreading narrow launch groups over idle CUs; kernels of the
+     * batches in flight fill the chip together.  Results are bit-identical either way.          */
+    DYNB_PLAN_THROUGHPUT = 8
 };
 
 const char* dynb_last_error(void);
@@ -119,7 +125,7 @@ typedef struct {
  *   prog_off  host  [B+1], prog_off[0] = 0, example i owns prog[prog_off[i] .. prog_off[i+1])
  *   arity     host  [n_types] values 0, 1 or 2; any id with arity 0 is a SCENE-like leaf that
  *                   outputs the example's feature map
- *   flags     one DYNB_SCHED_* value, optionally | DYNB_PLAN_BALANCE
+ *   flags     one DYNB_SCHED_* value, optionally | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT
  *   out       receives a library-owned plan; release with dynbatch_plan_free
  * Errors: DYNB_E_INVAL (NULL, B <= 0, n_types <= 0, offsets not increasing from 0),
  * DYNB_E_UNSUPPORTED (arity > 2, unknown flag), DYNB_E_MALFORMED (function id out of range, a

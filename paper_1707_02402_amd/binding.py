@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdynbatch.so")
 
 DYNB_F32, DYNB_BF16 = 0, 1
 DYNB_SCHED_IMPROVED, DYNB_SCHED_STANDARD, DYNB_SCHED_NAIVE, DYNB_SCHED_DEPTH = 0, 1, 2, 3
+DYNB_PLAN_THROUGHPUT = 8
 DYNB_PLAN_BALANCE = 4
 ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
           -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}

@@ -701,7 +701,8 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         for (int i = 0; i < l.count; ++i) a.any_binary |= (p->arity[p->items[l.start + i].type] == 2);
         // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
         // workgroup up to 256 nodes, two nodes per workgroup (highest throughput per CU) beyond that
-        int wm = (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
+        // (with several batches in flight the narrow groups of different batches share the chip instead)
+        int wm = p->throughput ? 1 : (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
 #ifdef DYNB_PHASE_CLOCKS
         if (const char* f = getenv("DYNB_FORCE_WM")) wm = atoi(f);
 #endif

@@ -34,6 +34,7 @@ struct dynb_plan {
     std::vector<int32_t> leaf_roots;     // examples whose whole program is one SCENE token
     int32_t n_slots = 0, max_launch = 0;
     bool has_binary = false;
+    bool throughput = false;             // DYNB_PLAN_THROUGHPUT: most work per CU instead of lowest latency
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };

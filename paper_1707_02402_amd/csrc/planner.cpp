@@ -93,7 +93,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     if (out) *out = nullptr;
     if (!prog || !prog_off || !arity || !out) return fail(DYNB_E_INVAL, "dynbatch_plan: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
     const bool balance = (flags & DYNB_PLAN_BALANCE) != 0;
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
     for (int32_t t = 0; t < n_types; ++t)
@@ -108,6 +108,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     try {
         const int32_t N = prog_off[B];
         p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
+        p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(prog, prog + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);

@@ -243,3 +243,30 @@ def test_generic_path_launch_group_wider_than_one_grid(dyn, util, oracle):
     ref = oracle.iep_forward_workload(w)
     assert util.normwise(got, ref) < TOL["f32"]
     assert util.normwise(got[32760:32780], ref[32760:32780]) < TOL["f32"]      # around the split
+
+
+def test_throughput_mode_and_batches_in_flight_on_three_streams(dyn, util):
+    """DYNB_PLAN_THROUGHPUT only changes the kernel layout; batches that run concurrently on their own
+    streams and workspaces must not disturb each other: every output equals the latency-mode result bit for bit."""
+    import torch
+    w = iep.config2(B=96)
+    ref = util.iep_run(dyn, w, dyn.DYNB_PLAN_BALANCE, return_dev=True)
+    weights = util.iep_weights_dev(w)
+    weights["packed"] = dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16)
+    feats = util.to_dev(w.feats, "bf16")
+    flags = dyn.DYNB_PLAN_BALANCE | dyn.DYNB_PLAN_THROUGHPUT
+    torch.cuda.synchronize()
+    lanes = []
+    for _ in range(3):
+        plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
+        lanes.append(dict(stream=torch.cuda.Stream(), plan=plan, out=torch.empty_like(feats),
+                          ws=torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16),
+                                         dtype=torch.uint8, device="cuda")))
+    for rep in range(4):
+        for ln in lanes:
+            if rep == 0:
+                dyn.dynbatch_plan_upload(ln["plan"], stream=ln["stream"])
+            dyn.dynbatch_execute(ln["plan"], weights, feats, ln["out"], ln["ws"], stream=ln["stream"])
+    torch.cuda.synchronize()
+    for ln in lanes:
+        assert torch.equal(ln["out"], ref)

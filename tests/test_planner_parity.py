@@ -111,6 +111,7 @@ def test_error_codes(dyn):
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), np.array([0, 3], np.uint8))
     assert e.value.name == "DYNB_E_UNSUPPORTED"
+    dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=dyn.DYNB_PLAN_THROUGHPUT | dyn.DYNB_PLAN_BALANCE)
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=16)
     assert e.value.name == "DYNB_E_UNSUPPORTED"
