@@ -72,9 +72,10 @@ enum {
     DYNB_PLAN_BALANCE = 4,
     /* Optional, any scheduling mode: the caller keeps several independent batches in flight (one
      * HIP stream and workspace each) and wants chip throughput rather than the latency of one
-     * batch.  dynbatch_execute then always uses its kernel layout with the most work per CU (two
-     * nodes per workgroup) instead of spreading narrow launch groups over idle CUs; kernels of the
-     * batches in flight fill the chip together.  Results are bit-identical either way.          */
+     * batch.  dynbatch_execute then always uses the kernel layout with the most work per CU (one
+     * node per workgroup, two workgroups sharing a CU) instead of spreading narrow launch groups
+     * over idle CUs; kernels of the batches in flight fill the chip together.  Results are
+     * bit-identical either way.                                                                 */
     DYNB_PLAN_THROUGHPUT = 8
 };
 

@@ -231,14 +231,15 @@ __global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict_
 // fragments of all 8 steps
 // of a tap sit in registers: each is re-fetched from global memory one step after its last use,
 // i.e. 7 steps (> 1800 clocks) ahead of its next use.  Scheduler fences keep that order.
-template <int MTW, bool CENTER_ONLY>
+template <int MTW, bool CENTER_ONLY, int RW = 8>
 __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t (&xaddr)[MTW], int mcount,
                                            const bf16_t* (&wrow)[2])
 {
     // wrow[nt] points at this lane's 8 values of the first fragment of channel tile nt in the packed
     // weights; fragment (tap, j) follows at (tap*8 + j) * 512 elements
     constexpr int NTAP = CENTER_ONLY ? 1 : 9;
-    bf16x8 x[4][MTW], wf[8][2];
+    static_assert(RW == 8 || RW == 4, "weight ring of 4 or 8 steps");
+    bf16x8 x[4][MTW], wf[RW][2];
     auto tap_off = [](int tap) -> uint32_t {
         return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t((tap / 3) * mf::ROW_BYTES + (tap % 3) * mf::PIX_BYTES);
     };
@@ -271,7 +272,7 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
     // the wait counts the compiler derives for the loop entry and for the back edge agree and stay
     // as loose as the ring allows.  Slot 7 is filled by the first step of the loop.
 #pragma unroll
-    for (int j = 0; j < 7; ++j) {
+    for (int j = 0; j < RW - 1; ++j) {
         load_w(wf[j], j * mf::FRAG);
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -289,8 +290,8 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
         const int wo = tap * 8 * mf::FRAG, nwo = ntap * 8 * mf::FRAG;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            step(x[j & 3], x[(j + 2) & 3], j + 2 < 8 ? xo + (j + 2) * 16 : nxo + (j + 2 - 8) * 16, wf[j],
-                 wf[(j + 7) & 7], j == 0 ? wo + 7 * mf::FRAG : nwo + (j - 1) * mf::FRAG);
+            step(x[j & 3], x[(j + 2) & 3], j + 2 < 8 ? xo + (j + 2) * 16 : nxo + (j + 2 - 8) * 16, wf[j % RW],
+                 wf[(j + RW - 1) % RW], j + RW - 1 < 8 ? wo + (j + RW - 1) * mf::FRAG : nwo + (j + RW - 1 - 8) * mf::FRAG);
     }
 }
 
@@ -302,10 +303,14 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
 //           window (rows 0..7 or 6..13: the second conv needs one row of the first conv's output
 //           beyond its own rows), i.e. 112 pixels = 4 pixel tiles, 2 per wave.  Two CUs share a node,
 //           which halves the latency of narrow launch groups at the price of 8/7 of the MFMA work.
-template <int WM>
-__global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
+//   WM = 4: the layout of WM = 2 inside at most 256 registers (weight ring of 4 steps), so that two
+//           workgroups share a CU and one's staging, swap and epilogue run under the other's MFMAs.
+template <int WMODE>
+__global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs a)
 {
     using namespace mf;
+    constexpr int WM = (WMODE == 4) ? 2 : WMODE;
+    constexpr int RW = (WMODE == 4) ? 4 : 8;   // weight ring depth in K-steps
     constexpr int NPW = (WM == 1) ? 2 : 1;    // nodes per workgroup
     constexpr int WPN = 4 / NPW;              // waves per node
     constexpr int MTW = (WM == 1) ? 7 : (WM == 2 ? 4 : 2);    // pixel tiles per wave (upper bound)
@@ -439,7 +444,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
             w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
         if (binary) {
             init_bias(a.b1);
-            kloop_mfma<MTW, true>(acc, uaddr, mcount, w1row);
+            kloop_mfma<MTW, true, RW>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
@@ -447,7 +452,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         if (binary) {
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) w1row[nt] += 8 * FRAG;
-            kloop_mfma<MTW, true>(acc, uaddr, mcount, w1row);
+            kloop_mfma<MTW, true, RW>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) {                                     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
@@ -473,7 +478,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
         for (int nt = 0; nt < 2; ++nt)
             wrow[nt] = a.w3a + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
         init_bias(a.b3a);
-        kloop_mfma<MTW, false>(acc, xaddr, mcount, wrow);
+        kloop_mfma<MTW, false, RW>(acc, xaddr, mcount, wrow);
     }
     PHASE(4);
     __syncthreads();
@@ -515,7 +520,7 @@ __global__ __launch_bounds__(256) void k_module_mfma(MfArgs a)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
             wrow[nt] = a.w3b + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
-        kloop_mfma<MTW, false>(acc, xaddr, mcount, wrow);
+        kloop_mfma<MTW, false, RW>(acc, xaddr, mcount, wrow);
         PHASE(8);
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
@@ -667,6 +672,9 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<3>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<3>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<4>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<4>)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<1>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<1>)");
@@ -701,14 +709,17 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         for (int i = 0; i < l.count; ++i) a.any_binary |= (p->arity[p->items[l.start + i].type] == 2);
         // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
         // workgroup up to 256 nodes, two nodes per workgroup (highest throughput per CU) beyond that
-        // (with several batches in flight the narrow groups of different batches share the chip instead)
-        int wm = p->throughput ? 1 : (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
+        // (with several batches in flight the narrow groups of different batches share the chip instead:
+        // one node per workgroup in the 256-register variant, two workgroups per CU)
+        int wm = p->throughput ? 4 : (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
 #ifdef DYNB_PHASE_CLOCKS
         if (const char* f = getenv("DYNB_FORCE_WM")) wm = atoi(f);
 #endif
-        const int nwg = (wm == 1) ? (l.count + 1) / 2 : (wm == 2) ? l.count : 2 * l.count;
+        const int nwg = (wm == 1) ? (l.count + 1) / 2 : (wm == 3) ? 2 * l.count : l.count;
         const unsigned grid = unsigned((nwg + 7) / 8 * 8);
-        if (wm == 3)
+        if (wm == 4)
+            hipLaunchKernelGGL((k_module_mfma<4>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        else if (wm == 3)
             hipLaunchKernelGGL((k_module_mfma<3>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else if (wm == 2)
             hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
