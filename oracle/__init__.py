@@ -94,6 +94,59 @@ def plan(prog, prog_off, arity, mode: int = 0) -> SimpleNamespace:
         members=a["members"][:N], in0=a["in0"][:N], in1=a["in1"][:N], out=a["out"][:N])
 
 
+def plan_dag(node_type, arg0, arg1, node_off, root, arity, mode: int = 0) -> SimpleNamespace:
+    """Plan of a batch of dependency graphs (explicit argument indices, local to each example).
+    mode 0: maximum-root-distance labels (deepest first), 2: dependency-depth labels (ascending)."""
+    node_type, arg0, arg1, node_off, root = map(_i32, (node_type, arg0, arg1, node_off, root))
+    arity = np.ascontiguousarray(arity, dtype=np.uint8)
+    B = len(node_off) - 1
+    N = int(node_off[-1])
+    n = max(N, 1)
+    a = {k: np.full(n, -7, np.int32) for k in
+         ("level", "type", "child0", "child1", "bucket_level", "bucket_type", "bucket_start",
+          "bucket_count", "members", "in0", "in1", "out")}
+    groot = np.full(max(B, 1), -7, np.int32)
+    n_levels, n_buckets, bad = ct.c_int32(0), ct.c_int32(0), ct.c_int32(-1)
+    I = ct.c_int32
+    rc = lib().oracle_plan_dag(_p(node_type, I), _p(arg0, I), _p(arg1, I), _p(node_off, I), _p(root, I), I(B),
+                               _p(arity, ct.c_uint8), I(len(arity)), I(mode),
+                               _p(a["level"], I), _p(a["type"], I), _p(a["child0"], I), _p(a["child1"], I),
+                               _p(groot, I), ct.byref(n_levels), ct.byref(n_buckets), _p(a["bucket_level"], I),
+                               _p(a["bucket_type"], I), _p(a["bucket_start"], I), _p(a["bucket_count"], I),
+                               _p(a["members"], I), _p(a["in0"], I), _p(a["in1"], I), _p(a["out"], I),
+                               ct.byref(bad))
+    if rc == -2:
+        raise MalformedProgram(bad.value)
+    if rc != 0:
+        raise ValueError(f"oracle_plan_dag: invalid arguments (rc={rc})")
+    nb = n_buckets.value
+    return SimpleNamespace(
+        n_nodes=N, n_levels=n_levels.value, n_buckets=nb,
+        node_level=a["level"][:N], node_type=a["type"][:N], child0=a["child0"][:N], child1=a["child1"][:N],
+        root=groot[:B], bucket_level=a["bucket_level"][:nb], bucket_type=a["bucket_type"][:nb],
+        bucket_start=a["bucket_start"][:nb], bucket_count=a["bucket_count"][:nb],
+        members=a["members"][:N], in0=a["in0"][:N], in1=a["in1"][:N], out=a["out"][:N])
+
+
+def iep_forward_dag(node_type, arg0, arg1, node_off, root, arity, feats, w1, b1, w3a, b3a, w3b, b3b) -> np.ndarray:
+    """Root output of every example, float64 [B,H,W,C]; every node of a graph is evaluated once."""
+    node_type, arg0, arg1, node_off, root = map(_i32, (node_type, arg0, arg1, node_off, root))
+    arity = np.ascontiguousarray(arity, dtype=np.uint8)
+    plan_dag(node_type, arg0, arg1, node_off, root, arity)      # raises on malformed graphs
+    feats = _f32(feats)
+    B, H, W, C = feats.shape
+    assert B == len(node_off) - 1
+    w1, b1, w3a, b3a, w3b, b3b = map(_f32, (w1, b1, w3a, b3a, w3b, b3b))
+    out = np.empty((B, H, W, C), np.float64)
+    I, F = ct.c_int32, ct.c_float
+    rc = lib().oracle_iep_forward_dag(_p(node_type, I), _p(arg0, I), _p(arg1, I), _p(node_off, I), _p(root, I), I(B),
+                                      _p(arity, ct.c_uint8), I(len(arity)), I(C), I(H), I(W), _p(feats, F),
+                                      _p(w1, F), _p(b1, F), _p(w3a, F), _p(b3a, F), _p(w3b, F), _p(b3b, F),
+                                      _p(out, ct.c_double))
+    assert rc == 0, rc
+    return out
+
+
 def iep_forward(prog, prog_off, arity, feats, w1, b1, w3a, b3a, w3b, b3b) -> np.ndarray:
     """Root output of every example, float64 [B,H,W,C]; per-example tree recursion."""
     prog, prog_off = _i32(prog), _i32(prog_off)

@@ -19,6 +19,9 @@
  *     time; the batched version builds the same network, so outputs must agree.
  *   - Results / Sparsely Gated Mixture of Experts: n experts, k active per example; the
  *     naive version runs the k*b expert uses one by one.
+ *   - Discussion: batching by dependency depth (labels counted up from the argument-free nodes),
+ *     and architectures given as a general dependency graph in which a node may have several
+ *     consumers (there the label is the MAXIMUM distance from the root, as Methods words it).
  * The module (residual conv block), the noisy top-k gate and all sizes are fixed by the
  * benchmark configurations, not by the paper.
  *
@@ -303,6 +306,187 @@ int oracle_iep_forward(const int32_t* prog, const int32_t* prog_off, int32_t B, 
         double* y = eval_node(&m, prog + prog_off[i], &pos, feats + (size_t)i * n);
         memcpy(out + (size_t)i * n, y, n * sizeof(double));
         free(y);
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * General dependency graphs (Discussion: the method applies to any architecture whose dependency
+ * graph is known before execution; Methods / Improved topological sort labels a node with its
+ * MAXIMUM distance from the root, which only differs from the plain distance when a node has
+ * several consumers).  An example is a list of nodes with explicit argument indices (local to the
+ * example, -1 = none) and one root; a node may feed several consumers and is evaluated once.
+ * ---------------------------------------------------------------------------------------- */
+
+typedef struct {
+    const int32_t *type, *arg0, *arg1;   /* this example's nodes */
+    int32_t n, root;
+    int32_t* memo;                       /* -2 unknown, -3 being computed (a cycle if met again) */
+    int bad;
+} dag_ctx;
+
+/* Longest path from the root down to node id: 0 for the root, else one more than the largest
+ * value among the nodes that take id as an argument; -1 if no chain of consumers reaches the root. */
+static int32_t max_root_distance(dag_ctx* c, int32_t id)
+{
+    if (c->memo[id] == -3) { c->bad = 1; return -1; }
+    if (c->memo[id] != -2) return c->memo[id];
+    if (id == c->root) { c->memo[id] = 0; return 0; }
+    c->memo[id] = -3;
+    int32_t best = -1;
+    for (int32_t q = 0; q < c->n && !c->bad; ++q)
+        if (c->arg0[q] == id || c->arg1[q] == id) {
+            int32_t dq = max_root_distance(c, q);
+            if (dq >= 0 && dq + 1 > best) best = dq + 1;
+        }
+    c->memo[id] = best;
+    return best;
+}
+
+/* Dependency depth with a cycle guard: 0 without arguments, else one more than the deepest argument. */
+static int32_t dag_dependency_depth(dag_ctx* c, int32_t id)
+{
+    if (c->memo[id] == -3) { c->bad = 1; return 0; }
+    if (c->memo[id] != -2) return c->memo[id];
+    c->memo[id] = -3;
+    int32_t d = 0;
+    if (c->arg0[id] >= 0) { int32_t a = dag_dependency_depth(c, c->arg0[id]) + 1; if (a > d) d = a; }
+    if (c->arg1[id] >= 0 && !c->bad) { int32_t b = dag_dependency_depth(c, c->arg1[id]) + 1; if (b > d) d = b; }
+    c->memo[id] = d;
+    return d;
+}
+
+/* mode 0: label = maximum distance from the root, pools deepest label first.
+ * mode 2: label = dependency depth, pools in ascending order.
+ * An example is malformed if a function id or argument index is out of range, the number of
+ * arguments differs from the function's arity, the graph has a cycle, the root is out of range,
+ * or some node does not contribute to the root.  Outputs as oracle_plan (child0/child1 = global
+ * ids of the arguments, root = global id).                                                    */
+int oracle_plan_dag(const int32_t* type_in, const int32_t* arg0, const int32_t* arg1, const int32_t* node_off,
+                    const int32_t* root_local, int32_t B, const uint8_t* arity, int32_t n_types, int32_t mode,
+                    int32_t* level, int32_t* type, int32_t* child0, int32_t* child1, int32_t* root,
+                    int32_t* n_levels, int32_t* n_buckets, int32_t* bucket_level, int32_t* bucket_type,
+                    int32_t* bucket_start, int32_t* bucket_count, int32_t* members, int32_t* in0,
+                    int32_t* in1, int32_t* out, int32_t* bad_example)
+{
+    if (!type_in || !arg0 || !arg1 || !node_off || !root_local || B <= 0 || !arity || n_types <= 0 ||
+        (mode != 0 && mode != 2))
+        return ORC_E_INVAL;
+    int32_t N = node_off[B], D = 0;
+    int32_t* memo = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    for (int32_t i = 0; i < B; ++i) {
+        int32_t base = node_off[i], n = node_off[i + 1] - base;
+        int bad = (n <= 0 || root_local[i] < 0 || root_local[i] >= n);
+        for (int32_t j = 0; j < n && !bad; ++j) {
+            int32_t t = type_in[base + j], a = arg0[base + j], b = arg1[base + j];
+            if (t < 0 || t >= n_types || arity[t] > 2 || a < -1 || a >= n || b < -1 || b >= n) { bad = 1; break; }
+            int given = (a >= 0) + (b >= 0);
+            if (given != arity[t] || (b >= 0 && a < 0)) bad = 1;
+        }
+        dag_ctx c = { type_in + base, arg0 + base, arg1 + base, n, bad ? 0 : root_local[i], memo + base, 0 };
+        if (!bad) {
+            /* a cycle anywhere makes the example malformed: walk the argument edges first */
+            for (int32_t j = 0; j < n; ++j) c.memo[j] = -2;
+            for (int32_t j = 0; j < n && !c.bad; ++j) dag_dependency_depth(&c, j);
+            bad = c.bad;
+        }
+        if (!bad && mode == 0) {
+            for (int32_t j = 0; j < n; ++j) c.memo[j] = -2;
+            for (int32_t j = 0; j < n; ++j) level[base + j] = max_root_distance(&c, j);
+        } else if (!bad) {
+            for (int32_t j = 0; j < n; ++j) level[base + j] = c.memo[j];
+            /* reachability is judged on root distances in both modes */
+            int32_t* dist = (int32_t*)malloc(sizeof(int32_t) * (size_t)n);
+            dag_ctx r = { c.type, c.arg0, c.arg1, n, c.root, dist, 0 };
+            for (int32_t j = 0; j < n; ++j) dist[j] = -2;
+            for (int32_t j = 0; j < n; ++j) if (max_root_distance(&r, j) < 0) bad = 1;
+            free(dist);
+        }
+        for (int32_t j = 0; j < n && !bad; ++j) if (level[base + j] < 0) bad = 1;   /* feeds nothing */
+        if (bad) {
+            if (bad_example) *bad_example = i;
+            free(memo);
+            return ORC_E_MALFORMED;
+        }
+        root[i] = base + root_local[i];
+        for (int32_t j = 0; j < n; ++j) {
+            type[base + j] = type_in[base + j];
+            child0[base + j] = arg0[base + j] >= 0 ? base + arg0[base + j] : -1;
+            child1[base + j] = arg1[base + j] >= 0 ? base + arg1[base + j] : -1;
+            if (level[base + j] + 1 > D) D = level[base + j] + 1;
+        }
+    }
+    free(memo);
+    *n_levels = D;
+    int32_t nb = 0, filled = 0;
+    for (int32_t step = 0; step < D; ++step) {
+        int32_t lvl = (mode == 0) ? D - 1 - step : step;
+        for (int32_t t = 0; t < n_types; ++t) {
+            int32_t start = filled;
+            for (int32_t id = 0; id < N; ++id)
+                if (level[id] == lvl && type[id] == t) {
+                    members[filled] = id;
+                    in0[filled] = child0[id];
+                    in1[filled] = child1[id];
+                    out[filled] = id;
+                    ++filled;
+                }
+            if (filled > start) {
+                bucket_level[nb] = lvl;
+                bucket_type[nb] = t;
+                bucket_start[nb] = start;
+                bucket_count[nb] = filled - start;
+                ++nb;
+            }
+        }
+    }
+    *n_buckets = nb;
+    return ORC_OK;
+}
+
+/* Value of node id of one example; every node is computed once and kept in val[] (NULL = not yet). */
+static const double* eval_dag_node(const modules* m, const int32_t* type, const int32_t* arg0, const int32_t* arg1,
+                                   int32_t id, const float* feat, double** val)
+{
+    if (val[id]) return val[id];
+    size_t n = (size_t)m->H * m->W * m->C;
+    int t = type[id];
+    double* y = (double*)malloc(n * sizeof(double));
+    if (m->arity[t] == 0) {
+        for (size_t i = 0; i < n; ++i) y[i] = (double)feat[i];
+    } else if (m->arity[t] == 1) {
+        residual_block(m, t, eval_dag_node(m, type, arg0, arg1, arg0[id], feat, val), y);
+    } else {
+        const double* a = eval_dag_node(m, type, arg0, arg1, arg0[id], feat, val);
+        const double* b = eval_dag_node(m, type, arg0, arg1, arg1[id], feat, val);
+        double* u = (double*)malloc(n * sizeof(double));
+        join1x1(m, t, a, b, u);
+        residual_block(m, t, u, y);
+        free(u);
+    }
+    val[id] = y;
+    return y;
+}
+
+/* Graphs must be well formed (check with oracle_plan_dag first). out: double [B,H,W,C]. */
+int oracle_iep_forward_dag(const int32_t* type, const int32_t* arg0, const int32_t* arg1, const int32_t* node_off,
+                           const int32_t* root_local, int32_t B, const uint8_t* arity, int32_t n_types,
+                           int32_t C, int32_t H, int32_t W, const float* feats, const float* w1, const float* b1,
+                           const float* w3a, const float* b3a, const float* w3b, const float* b3b, double* out)
+{
+    if (!type || !arg0 || !arg1 || !node_off || !root_local || B <= 0 || !feats || !out || !w3a || !w3b)
+        return ORC_E_INVAL;
+    modules m = { C, H, W, n_types, arity, w1, b1, w3a, b3a, w3b, b3b };
+    size_t n = (size_t)H * W * C;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < B; ++i) {
+        int32_t base = node_off[i], cnt = node_off[i + 1] - base;
+        double** val = (double**)calloc((size_t)cnt, sizeof(double*));
+        const double* y = eval_dag_node(&m, type + base, arg0 + base, arg1 + base, root_local[i],
+                                        feats + (size_t)i * n, val);
+        memcpy(out + (size_t)i * n, y, n * sizeof(double));
+        for (int32_t j = 0; j < cnt; ++j) free(val[j]);
+        free(val);
     }
     return ORC_OK;
 }

@@ -225,3 +225,115 @@ def small_mixed(seed: int, B: int, C: int, H: int, W: int, dtype: str, n_unary: 
         length = int(g.integers(min_len, max_len + 1))
         progs.append(chain_like_program(g, length, unary, binary, p_binary=0.3))
     return _assemble(f"mixed-{dtype}-B{B}-C{C}-{H}x{W}", seed, dtype, arity, progs, C, H, W)
+
+
+# --------------------------------------------------------------------------- dependency graphs
+@dataclass
+class DagWorkload:
+    """A batch of dependency graphs: explicit argument indices (local to the example), nodes in arbitrary
+    order, one root per example; a node may feed several consumers."""
+    name: str
+    dtype: str
+    arity: np.ndarray
+    node_type: np.ndarray       # int32 [N]
+    arg0: np.ndarray            # int32 [N] local index of the first argument or -1
+    arg1: np.ndarray            # int32 [N] local index of the second argument or -1
+    node_off: np.ndarray        # int32 [B+1]
+    root: np.ndarray            # int32 [B] local index of the output node
+    C: int
+    H: int
+    W: int
+    feats: np.ndarray
+    w1: np.ndarray
+    b1: np.ndarray
+    w3a: np.ndarray
+    b3a: np.ndarray
+    w3b: np.ndarray
+    b3b: np.ndarray
+
+    @property
+    def B(self) -> int:
+        return len(self.node_off) - 1
+
+    @property
+    def n_types(self) -> int:
+        return len(self.arity)
+
+    @property
+    def n_module_evals(self) -> int:
+        return int((self.arity[self.node_type] > 0).sum())
+
+    def expanded(self) -> IepWorkload:
+        """The same computation as prefix programs: every shared sub-graph is written out once per use."""
+        progs = []
+        for i in range(self.B):
+            b = int(self.node_off[i])
+            seq = []
+
+            def emit(j):
+                seq.append(int(self.node_type[b + j]))
+                for a in (self.arg0[b + j], self.arg1[b + j]):
+                    if a >= 0:
+                        emit(int(a))
+
+            emit(int(self.root[i]))
+            progs.append(np.array(seq, np.int32))
+        prog, off = _pack(progs)
+        return IepWorkload(self.name + "-expanded", self.dtype, self.arity, prog, off, self.C, self.H, self.W,
+                           self.feats, self.w1, self.b1, self.w3a, self.b3a, self.w3b, self.b3b)
+
+
+def random_dag(g: np.random.Generator, n_nodes: int, unary, binary, window: int = 4, p_binary: float = 0.4):
+    """Random graph built bottom up (a node's arguments are earlier nodes, so no cycle can arise), cut down to
+    what the last node depends on, then renumbered in random order.  Returns (type, arg0, arg1, root)."""
+    types, a0, a1 = [SCENE], [-1], [-1]
+    for i in range(1, n_nodes):
+        lo = max(0, i - window)
+        if i >= 2 and g.random() < p_binary:
+            types.append(int(g.choice(binary)))
+            a0.append(int(g.integers(lo, i)))
+            a1.append(int(g.integers(lo, i)))
+        elif g.random() < 0.1:
+            types.append(SCENE)
+            a0.append(-1)
+            a1.append(-1)
+        else:
+            types.append(int(g.choice(unary)))
+            a0.append(int(g.integers(lo, i)))
+            a1.append(-1)
+    keep, stack = set(), [n_nodes - 1]
+    while stack:
+        j = stack.pop()
+        if j in keep:
+            continue
+        keep.add(j)
+        stack += [a for a in (a0[j], a1[j]) if a >= 0]
+    old = sorted(keep)
+    order = g.permutation(len(old))                      # new index of old[k] is order[k]
+    new_of = {o: int(order[k]) for k, o in enumerate(old)}
+    n = len(old)
+    t2, b0, b1 = np.zeros(n, np.int32), np.full(n, -1, np.int32), np.full(n, -1, np.int32)
+    for o in old:
+        q = new_of[o]
+        t2[q] = types[o]
+        b0[q] = new_of[a0[o]] if a0[o] >= 0 else -1
+        b1[q] = new_of[a1[o]] if a1[o] >= 0 else -1
+    return t2, b0, b1, new_of[n_nodes - 1]
+
+
+def dag_batch(seed: int, B: int, C: int, H: int, W: int, dtype: str, n_unary: int = 3, n_binary: int = 2,
+              min_nodes: int = 2, max_nodes: int = 12, window: int = 4) -> DagWorkload:
+    arity = np.array([0] + [1] * n_unary + [2] * n_binary, np.uint8)
+    unary = list(range(1, n_unary + 1))
+    binary = list(range(n_unary + 1, n_unary + n_binary + 1))
+    g = stream(seed, _S_TREE)
+    parts = [random_dag(g, int(g.integers(min_nodes, max_nodes + 1)), unary, binary, window) for _ in range(B)]
+    off = np.zeros(B + 1, np.int32)
+    off[1:] = np.cumsum([len(p[0]) for p in parts])
+    feats = make_feats(seed, B, H, W, C, dtype)
+    w = make_weights(seed, arity, C, dtype)
+    return DagWorkload(f"dag-{dtype}-B{B}-C{C}-{H}x{W}", dtype, arity,
+                       np.concatenate([p[0] for p in parts]).astype(np.int32),
+                       np.concatenate([p[1] for p in parts]).astype(np.int32),
+                       np.concatenate([p[2] for p in parts]).astype(np.int32), off,
+                       np.array([p[3] for p in parts], np.int32), C, H, W, feats, *w)
