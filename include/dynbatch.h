@@ -135,6 +135,26 @@ typedef struct {
 int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
                   int32_t n_types, uint32_t flags, dynb_plan** out);
 
+/* The same for architectures given as general dependency graphs (Discussion: any architecture
+ * whose dependencies are known before execution; a node may have several consumers and is
+ * evaluated once).  Example i owns nodes [node_off[i], node_off[i+1]) in any order.
+ *   type      host  [N]   function id of every node
+ *   arg0/1    host  [N]   index INSIDE the example of the node that produces the first / second
+ *                         argument, -1 if the function takes none; arg1 >= 0 requires arg0 >= 0
+ *   node_off  host  [B+1] node_off[0] = 0
+ *   root      host  [B]   index inside the example of the node whose map is the example's output
+ *   flags     DYNB_SCHED_IMPROVED (label = MAXIMUM distance from the root, Methods / Improved
+ *             topological sort) or DYNB_SCHED_DEPTH, optionally | DYNB_PLAN_THROUGHPUT;
+ *             DYNB_PLAN_BALANCE is accepted and ignored
+ * The plan behaves like one from dynbatch_plan (view, upload, execute, free); in its view node id
+ * = node_off[example] + index and child0/child1 are the arguments' node ids.
+ * Errors as dynbatch_plan; DYNB_E_MALFORMED also for an argument index out of range, an argument
+ * count that differs from the arity, a cycle, a root out of range, or a node that the root does
+ * not depend on; DYNB_E_UNSUPPORTED for the standard and naive schedules.                       */
+int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const int32_t* arg1,
+                      const int32_t* node_off, const int32_t* root, int32_t B, const uint8_t* arity,
+                      int32_t n_types, uint32_t flags, dynb_plan** out);
+
 int dynbatch_plan_view(const dynb_plan* plan, dynb_plan_view* view);
 
 void dynbatch_plan_free(dynb_plan* plan);

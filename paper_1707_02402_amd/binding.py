@@ -22,7 +22,7 @@ DYNB_PLAN_BALANCE = 4
 ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
           -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}
 
-EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_view", "dynbatch_plan_free",
+EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
            "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_naive", "dynb_timing_enable",
@@ -74,6 +74,8 @@ def _load():
     L.dynb_last_error.restype = ct.c_char_p
     L.dynbatch_plan.argtypes = [I32P, I32P, ct.c_int32, ct.POINTER(ct.c_uint8), ct.c_int32, ct.c_uint32,
                                 ct.POINTER(ct.c_void_p)]
+    L.dynbatch_plan_dag.argtypes = [I32P, I32P, I32P, I32P, I32P, ct.c_int32, ct.POINTER(ct.c_uint8), ct.c_int32, ct.c_uint32,
+                                    ct.POINTER(ct.c_void_p)]
     L.dynbatch_plan_view.argtypes = [ct.c_void_p, ct.POINTER(_PlanView)]
     L.dynbatch_plan_free.argtypes = [ct.c_void_p]
     L.dynbatch_plan_free.restype = None
@@ -143,6 +145,22 @@ def dynbatch_plan(prog, prog_off, arity, flags: int = DYNB_SCHED_IMPROVED) -> Pl
     _check(lib.dynbatch_plan(prog.ctypes.data_as(I32P), prog_off.ctypes.data_as(I32P), len(prog_off) - 1,
                              arity.ctypes.data_as(ct.POINTER(ct.c_uint8)), len(arity), flags, ct.byref(h)))
     return Plan(h, len(prog_off) - 1)
+
+
+def dynbatch_plan_dag(node_type, arg0, arg1, node_off, root, arity, flags: int = DYNB_SCHED_IMPROVED) -> Plan:
+    """Plan of a batch of dependency graphs (argument indices local to each example, -1 = none)."""
+    a = [np.ascontiguousarray(v, dtype=np.int32) for v in (node_type, arg0, arg1, node_off, root)]
+    arity = np.ascontiguousarray(arity, dtype=np.uint8)
+    for i in range(3):
+        if len(a[i]) == 0:
+            a[i] = np.zeros(1, np.int32)  # keep the pointers non-NULL; lengths come from node_off
+    h = ct.c_void_p()
+    B = len(a[3]) - 1
+    if len(a[4]) != B:
+        raise ValueError("root must have one entry per example")
+    _check(lib.dynbatch_plan_dag(*[v.ctypes.data_as(I32P) for v in a], B,
+                                 arity.ctypes.data_as(ct.POINTER(ct.c_uint8)), len(arity), flags, ct.byref(h)))
+    return Plan(h, B)
 
 
 def dynbatch_plan_view(plan: Plan) -> SimpleNamespace:

@@ -85,6 +85,234 @@ bool parse_example(const int32_t* prog, int32_t base, int32_t len, const uint8_t
 
 using dynb::fail;
 
+namespace {
+
+// Pools and executor work lists from labels, arguments and roots (p->level, type, child0, child1,
+// root).  `example` maps a node to its example, `queue_pos` is the per-example post-order position
+// (only read by the naive schedule), `shared` says that a node may have several consumers.
+void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, const std::vector<int32_t>& example,
+                 const std::vector<int32_t>& queue_pos, bool balance, bool shared)
+{
+    const int32_t B = p->B, N = p->N, D = p->D, n_types = p->n_types, mode = p->mode;
+    const bool improved = (mode == DYNB_SCHED_IMPROVED), by_depth = (mode == DYNB_SCHED_DEPTH);
+    if (shared) balance = false;                     // the pull-forward pass assumes one consumer per node
+    // ---- pools: stable counting sort of node ids by (execution step, function id)
+    p->members.resize(N); p->in0.resize(N); p->in1.resize(N); p->out.resize(N);
+    if (mode == DYNB_SCHED_NAIVE) {
+        // one pool per node, example by example in queue order
+        for (int32_t i = 0; i < B; ++i) {
+            const int32_t base = prog_off[i], len = prog_off[i + 1] - base;
+            for (int32_t j = 0; j < len; ++j) p->members[base + queue_pos[base + j]] = base + j;
+        }
+        p->b_level.resize(N); p->b_type.resize(N); p->b_start.resize(N); p->b_count.assign(N, 1);
+        for (int32_t s = 0; s < N; ++s) {
+            const int32_t n = p->members[s];
+            p->b_level[s] = p->level[n]; p->b_type[s] = p->type[n]; p->b_start[s] = s;
+        }
+    } else {
+        const size_t n_keys = size_t(D) * size_t(n_types);
+        std::vector<int32_t> hist(n_keys + 1, 0);
+        auto key = [&](int32_t n) {
+            const int32_t step = improved ? D - 1 - p->level[n] : p->level[n];
+            return size_t(step) * n_types + size_t(p->type[n]);
+        };
+        for (int32_t n = 0; n < N; ++n) ++hist[key(n) + 1];
+        for (size_t q = 0; q < n_keys; ++q) {
+            if (hist[q + 1] > 0) {
+                const int32_t step = int32_t(q / n_types);
+                p->b_level.push_back(improved ? D - 1 - step : step);
+                p->b_type.push_back(int32_t(q % n_types));
+                p->b_start.push_back(hist[q]);
+                p->b_count.push_back(hist[q + 1]);
+            }
+            hist[q + 1] += hist[q];
+        }
+        for (int32_t n = 0; n < N; ++n) p->members[hist[key(n)]++] = n;   // ascending ids inside a pool
+    }
+    for (int32_t s = 0; s < N; ++s) {
+        const int32_t n = p->members[s];
+        p->in0[s] = p->child0[n]; p->in1[s] = p->child1[n]; p->out[s] = n;
+    }
+
+    // ---- executor work lists: items in execution order, launch groups, slots
+    // 1. launch group of every compute node, in the logical order of the pools
+    p->node_launch.assign(N, -1);
+    std::vector<int32_t> order;                       // compute nodes in execution order
+    int32_t n_launch = 0;
+    {
+        int32_t cur_label = -1;
+        for (int32_t s = 0; s < N; ++s) {
+            const int32_t n = p->members[s];
+            if (arity[p->type[n]] == 0) continue;
+            if (arity[p->type[n]] == 2) p->has_binary = true;
+            if (mode == DYNB_SCHED_NAIVE || p->level[n] != cur_label) { ++n_launch; cur_label = p->level[n]; }
+            p->node_launch[n] = n_launch - 1;
+            order.push_back(n);
+        }
+    }
+    const int32_t n_compute = int32_t(order.size());
+    auto is_compute = [&](int32_t c) { return c >= 0 && arity[p->type[c]] > 0; };
+
+    // 2. optional balancing of the improved sort.  A label only fixes the LATEST launch group a
+    // node may run in; a node whose arguments finish early can run earlier.  Launch groups with
+    // more nodes than the chip has CUs (256) cost a second round, so nodes are pulled forward out
+    // of such groups into earlier groups that have idle CUs (earliest deadline first).  The paper
+    // mentions in its Discussion that the execution order could be optimised and leaves it aside.
+    if (improved && balance && n_launch > 1) {
+        const int32_t S = n_launch;
+        constexpr int32_t CUS = 256, HALF_CUS = 128;
+        std::vector<int32_t> remaining(S, 0), pending(N, 0), ready_at(N, 0), assigned(N, -1), parent(N, -1);
+        for (int32_t n : order) {
+            ++remaining[p->node_launch[n]];
+            for (int32_t c : {p->child0[n], p->child1[n]})
+                if (is_compute(c)) { ++pending[n]; parent[c] = n; }
+        }
+        // `order` is grouped by deadline already.  Size classes of the executor: up to 128 nodes a
+        // group runs with two CUs per node, up to 256 with one, beyond that in two rounds.
+        std::vector<int32_t> first_of(S + 1, 0);
+        for (int32_t n : order) ++first_of[p->node_launch[n] + 1];
+        for (int32_t L = 0; L < S; ++L) first_of[L + 1] += first_of[L];
+        std::vector<int32_t> size_at(S, 0);             // nodes currently scheduled in a group
+        std::vector<char> gives(S, 0);                  // groups above the smallest size class
+        std::vector<int32_t> givers;
+        for (int32_t L = 0; L < S; ++L)
+            if (remaining[L] > HALF_CUS) { gives[L] = 1; givers.push_back(L); }
+        std::vector<std::vector<int32_t>> ready(S);
+        for (int32_t L : givers) ready[L].reserve(remaining[L]);
+        for (int32_t n : order)
+            if (pending[n] == 0 && gives[p->node_launch[n]]) ready[p->node_launch[n]].push_back(n);
+        auto assign = [&](int32_t n, int32_t s) {
+            assigned[n] = s;
+            ++size_at[s];
+            --remaining[p->node_launch[n]];
+            const int32_t q = parent[n];
+            if (q >= 0) {
+                ready_at[q] = std::max(ready_at[q], s + 1);
+                if (--pending[q] == 0 && gives[p->node_launch[q]]) ready[p->node_launch[q]].push_back(q);
+            }
+        };
+        // pass 0: every node at its deadline unless it is pulled forward out of a group wider than
+        // the chip (those come down to 256); earlier groups are filled up to their size class
+        for (int32_t s = 0; s < S; ++s) {
+            for (int32_t i = first_of[s]; i < first_of[s + 1]; ++i)
+                if (assigned[order[i]] < 0) assign(order[i], s);
+            const int32_t here = size_at[s];
+            const int32_t cap = here <= HALF_CUS ? HALF_CUS : (here <= CUS ? CUS : here);
+            for (int32_t L : givers) {
+                if (size_at[s] >= cap) break;
+                if (L <= s || remaining[L] <= CUS) continue;
+                auto& pool = ready[L];
+                size_t keep = 0;
+                for (size_t i = 0; i < pool.size(); ++i) {
+                    const int32_t n = pool[i];
+                    if (size_at[s] < cap && remaining[L] > CUS && ready_at[n] <= s) assign(n, s);
+                    else pool[keep++] = n;
+                }
+                pool.resize(keep);
+            }
+        }
+        // pass 1: with the room that is left below 128, bring groups of 129..256 nodes down to 128,
+        // earliest deadline first (ready_at is a safe upper bound: arguments only ever move earlier)
+        std::vector<std::vector<int32_t>> at(S);
+        for (int32_t L : givers)
+            if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].reserve(size_at[L]);
+        for (int32_t n : order) {
+            const int32_t L = assigned[n];
+            if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].push_back(n);
+        }
+        for (int32_t s = 0; s < S; ++s) {
+            if (size_at[s] >= HALF_CUS) continue;
+            for (int32_t L : givers) {
+                if (size_at[s] >= HALF_CUS) break;
+                if (L <= s || size_at[L] <= HALF_CUS || size_at[L] > CUS) continue;
+                auto& pool = at[L];
+                size_t keep = 0;
+                for (size_t i = 0; i < pool.size(); ++i) {
+                    const int32_t n = pool[i];
+                    if (size_at[s] < HALF_CUS && size_at[L] > HALF_CUS && ready_at[n] <= s) {
+                        assigned[n] = s; ++size_at[s]; --size_at[L];
+                    } else pool[keep++] = n;
+                }
+                pool.resize(keep);
+            }
+        }
+        for (int32_t n : order) p->node_launch[n] = assigned[n];
+        // execution order: launch group, then function id (weights stay hot), then node id
+        std::vector<int32_t> start(size_t(S) * n_types + 1, 0);
+        auto key = [&](int32_t n) { return size_t(p->node_launch[n]) * n_types + size_t(p->type[n]); };
+        for (int32_t n : order) ++start[key(n) + 1];
+        for (size_t q = 0; q + 1 < start.size(); ++q) start[q + 1] += start[q];
+        std::vector<int32_t> sorted(order.size());
+        for (int32_t n = 0; n < N; ++n)                       // ascending node id inside a (group, function) run
+            if (p->node_launch[n] >= 0) sorted[start[key(n)]++] = n;
+        order.swap(sorted);
+    }
+
+    // 3. slots and items
+    std::vector<int32_t> slot(N, -1);
+    {
+        // Root-distance labels put every argument exactly one label below its consumer, so two
+        // alternating halves suffice.  Balanced and dependency-depth plans keep a result for several
+        // groups: they recycle slots through a free list once the consuming group has been issued.
+        // A shared node lives until its last consumer has been issued (use counts).
+        const bool pingpong = improved && !balance && !shared;
+        const bool recycle = (improved && balance) || by_depth || shared;
+        std::vector<int32_t> uses;
+        if (recycle) {
+            uses.assign(N, 0);
+            for (int32_t n : order)
+                for (int32_t c : {p->child0[n], p->child1[n]})
+                    if (c >= 0) ++uses[c];
+        }
+        int32_t maxw = 0, running = 0;
+        std::vector<int32_t> rank_in_level(D, 0);
+        if (pingpong) {
+            std::vector<int32_t> width(D, 0);
+            for (int32_t n : order) ++width[p->level[n]];
+            for (int32_t l = 0; l < D; ++l) maxw = std::max(maxw, width[l]);
+        }
+        std::vector<int32_t> free_slots, release;     // balanced plans recycle slots through a free list
+        p->items.reserve(n_compute);
+        int32_t cur = -1;
+        for (int32_t n : order) {
+            if (p->node_launch[n] != cur) {
+                // slots of arguments consumed by the previous group may be reused from here on
+                free_slots.insert(free_slots.end(), release.begin(), release.end());
+                release.clear();
+                p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0});
+                cur = p->node_launch[n];
+            }
+            const bool is_root = (n == p->root[example[n]]);
+            if (pingpong) {
+                // arguments of a label-l node all sit at label l+1: two alternating halves suffice
+                slot[n] = (p->level[n] & 1) * maxw + rank_in_level[p->level[n]]++;
+            } else if (!is_root) {
+                if (recycle && !free_slots.empty()) { slot[n] = free_slots.back(); free_slots.pop_back(); }
+                else slot[n] = running++;
+            }
+            auto src = [&](int32_t c) -> int32_t {
+                if (c < 0) return 0;
+                if (!is_compute(c)) return -1 - example[c];
+                if (recycle && --uses[c] == 0) release.push_back(slot[c]);
+                return slot[c];
+            };
+            dynb_item it;
+            it.src0 = src(p->child0[n]);
+            it.src1 = src(p->child1[n]);
+            it.dst = is_root ? -1 - example[n] : slot[n];
+            it.type = p->type[n];
+            ++p->launches.back().count;
+            p->items.push_back(it);
+        }
+        p->n_slots = pingpong ? 2 * maxw : running;
+        for (const auto& l : p->launches) p->max_launch = std::max(p->max_launch, l.count);
+    }
+    for (int32_t i = 0; i < B; ++i)
+        if (arity[p->type[p->root[i]]] == 0) p->leaf_roots.push_back(i);
+}
+
+}  // namespace
+
 extern "C" const char* dynb_last_error(void) { return dynb::g_error.c_str(); }
 
 extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32_t B,
@@ -159,214 +387,124 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         }
         p->D = D;
 
-        // ---- pools: stable counting sort of node ids by (execution step, function id)
-        p->members.resize(N); p->in0.resize(N); p->in1.resize(N); p->out.resize(N);
-        if (mode == DYNB_SCHED_NAIVE) {
-            // one pool per node, example by example in queue order
-            for (int32_t i = 0; i < B; ++i) {
-                const int32_t base = prog_off[i], len = prog_off[i + 1] - base;
-                for (int32_t j = 0; j < len; ++j) p->members[base + queue_pos[base + j]] = base + j;
-            }
-            p->b_level.resize(N); p->b_type.resize(N); p->b_start.resize(N); p->b_count.assign(N, 1);
-            for (int32_t s = 0; s < N; ++s) {
-                const int32_t n = p->members[s];
-                p->b_level[s] = p->level[n]; p->b_type[s] = p->type[n]; p->b_start[s] = s;
-            }
-        } else {
-            const size_t n_keys = size_t(D) * size_t(n_types);
-            std::vector<int32_t> hist(n_keys + 1, 0);
-            auto key = [&](int32_t n) {
-                const int32_t step = improved ? D - 1 - p->level[n] : p->level[n];
-                return size_t(step) * n_types + size_t(p->type[n]);
-            };
-            for (int32_t n = 0; n < N; ++n) ++hist[key(n) + 1];
-            for (size_t q = 0; q < n_keys; ++q) {
-                if (hist[q + 1] > 0) {
-                    const int32_t step = int32_t(q / n_types);
-                    p->b_level.push_back(improved ? D - 1 - step : step);
-                    p->b_type.push_back(int32_t(q % n_types));
-                    p->b_start.push_back(hist[q]);
-                    p->b_count.push_back(hist[q + 1]);
-                }
-                hist[q + 1] += hist[q];
-            }
-            for (int32_t n = 0; n < N; ++n) p->members[hist[key(n)]++] = n;   // ascending ids inside a pool
-        }
-        for (int32_t s = 0; s < N; ++s) {
-            const int32_t n = p->members[s];
-            p->in0[s] = p->child0[n]; p->in1[s] = p->child1[n]; p->out[s] = n;
-        }
-
-        // ---- executor work lists: items in execution order, launch groups, slots
-        // 1. launch group of every compute node, in the logical order of the pools
-        p->node_launch.assign(N, -1);
-        std::vector<int32_t> order;                       // compute nodes in execution order
-        int32_t n_launch = 0;
-        {
-            int32_t cur_label = -1;
-            for (int32_t s = 0; s < N; ++s) {
-                const int32_t n = p->members[s];
-                if (arity[p->type[n]] == 0) continue;
-                if (arity[p->type[n]] == 2) p->has_binary = true;
-                if (mode == DYNB_SCHED_NAIVE || p->level[n] != cur_label) { ++n_launch; cur_label = p->level[n]; }
-                p->node_launch[n] = n_launch - 1;
-                order.push_back(n);
-            }
-        }
-        const int32_t n_compute = int32_t(order.size());
-        auto is_compute = [&](int32_t c) { return c >= 0 && arity[p->type[c]] > 0; };
-
-        // 2. optional balancing of the improved sort.  A label only fixes the LATEST launch group a
-        // node may run in; a node whose arguments finish early can run earlier.  Launch groups with
-        // more nodes than the chip has CUs (256) cost a second round, so nodes are pulled forward out
-        // of such groups into earlier groups that have idle CUs (earliest deadline first).  The paper
-        // mentions in its Discussion that the execution order could be optimised and leaves it aside.
-        if (improved && balance && n_launch > 1) {
-            const int32_t S = n_launch;
-            constexpr int32_t CUS = 256, HALF_CUS = 128;
-            std::vector<int32_t> remaining(S, 0), pending(N, 0), ready_at(N, 0), assigned(N, -1), parent(N, -1);
-            for (int32_t n : order) {
-                ++remaining[p->node_launch[n]];
-                for (int32_t c : {p->child0[n], p->child1[n]})
-                    if (is_compute(c)) { ++pending[n]; parent[c] = n; }
-            }
-            // `order` is grouped by deadline already.  Size classes of the executor: up to 128 nodes a
-            // group runs with two CUs per node, up to 256 with one, beyond that in two rounds.
-            std::vector<int32_t> first_of(S + 1, 0);
-            for (int32_t n : order) ++first_of[p->node_launch[n] + 1];
-            for (int32_t L = 0; L < S; ++L) first_of[L + 1] += first_of[L];
-            std::vector<int32_t> size_at(S, 0);             // nodes currently scheduled in a group
-            std::vector<char> gives(S, 0);                  // groups above the smallest size class
-            std::vector<int32_t> givers;
-            for (int32_t L = 0; L < S; ++L)
-                if (remaining[L] > HALF_CUS) { gives[L] = 1; givers.push_back(L); }
-            std::vector<std::vector<int32_t>> ready(S);
-            for (int32_t L : givers) ready[L].reserve(remaining[L]);
-            for (int32_t n : order)
-                if (pending[n] == 0 && gives[p->node_launch[n]]) ready[p->node_launch[n]].push_back(n);
-            auto assign = [&](int32_t n, int32_t s) {
-                assigned[n] = s;
-                ++size_at[s];
-                --remaining[p->node_launch[n]];
-                const int32_t q = parent[n];
-                if (q >= 0) {
-                    ready_at[q] = std::max(ready_at[q], s + 1);
-                    if (--pending[q] == 0 && gives[p->node_launch[q]]) ready[p->node_launch[q]].push_back(q);
-                }
-            };
-            // pass 0: every node at its deadline unless it is pulled forward out of a group wider than
-            // the chip (those come down to 256); earlier groups are filled up to their size class
-            for (int32_t s = 0; s < S; ++s) {
-                for (int32_t i = first_of[s]; i < first_of[s + 1]; ++i)
-                    if (assigned[order[i]] < 0) assign(order[i], s);
-                const int32_t here = size_at[s];
-                const int32_t cap = here <= HALF_CUS ? HALF_CUS : (here <= CUS ? CUS : here);
-                for (int32_t L : givers) {
-                    if (size_at[s] >= cap) break;
-                    if (L <= s || remaining[L] <= CUS) continue;
-                    auto& pool = ready[L];
-                    size_t keep = 0;
-                    for (size_t i = 0; i < pool.size(); ++i) {
-                        const int32_t n = pool[i];
-                        if (size_at[s] < cap && remaining[L] > CUS && ready_at[n] <= s) assign(n, s);
-                        else pool[keep++] = n;
-                    }
-                    pool.resize(keep);
-                }
-            }
-            // pass 1: with the room that is left below 128, bring groups of 129..256 nodes down to 128,
-            // earliest deadline first (ready_at is a safe upper bound: arguments only ever move earlier)
-            std::vector<std::vector<int32_t>> at(S);
-            for (int32_t L : givers)
-                if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].reserve(size_at[L]);
-            for (int32_t n : order) {
-                const int32_t L = assigned[n];
-                if (size_at[L] > HALF_CUS && size_at[L] <= CUS) at[L].push_back(n);
-            }
-            for (int32_t s = 0; s < S; ++s) {
-                if (size_at[s] >= HALF_CUS) continue;
-                for (int32_t L : givers) {
-                    if (size_at[s] >= HALF_CUS) break;
-                    if (L <= s || size_at[L] <= HALF_CUS || size_at[L] > CUS) continue;
-                    auto& pool = at[L];
-                    size_t keep = 0;
-                    for (size_t i = 0; i < pool.size(); ++i) {
-                        const int32_t n = pool[i];
-                        if (size_at[s] < HALF_CUS && size_at[L] > HALF_CUS && ready_at[n] <= s) {
-                            assigned[n] = s; ++size_at[s]; --size_at[L];
-                        } else pool[keep++] = n;
-                    }
-                    pool.resize(keep);
-                }
-            }
-            for (int32_t n : order) p->node_launch[n] = assigned[n];
-            // execution order: launch group, then function id (weights stay hot), then node id
-            std::vector<int32_t> start(size_t(S) * n_types + 1, 0);
-            auto key = [&](int32_t n) { return size_t(p->node_launch[n]) * n_types + size_t(p->type[n]); };
-            for (int32_t n : order) ++start[key(n) + 1];
-            for (size_t q = 0; q + 1 < start.size(); ++q) start[q + 1] += start[q];
-            std::vector<int32_t> sorted(order.size());
-            for (int32_t n = 0; n < N; ++n)                       // ascending node id inside a (group, function) run
-                if (p->node_launch[n] >= 0) sorted[start[key(n)]++] = n;
-            order.swap(sorted);
-        }
-
-        // 3. slots and items
-        std::vector<int32_t> slot(N, -1);
-        {
-            // Root-distance labels put every argument exactly one label below its consumer, so two
-            // alternating halves suffice.  Balanced and dependency-depth plans keep a result for several
-            // groups: they recycle slots through a free list once the consuming group has been issued.
-            const bool pingpong = improved && !balance;
-            const bool recycle = (improved && balance) || by_depth;
-            int32_t maxw = 0, running = 0;
-            std::vector<int32_t> rank_in_level(D, 0);
-            if (pingpong) {
-                std::vector<int32_t> width(D, 0);
-                for (int32_t n : order) ++width[p->level[n]];
-                for (int32_t l = 0; l < D; ++l) maxw = std::max(maxw, width[l]);
-            }
-            std::vector<int32_t> free_slots, release;     // balanced plans recycle slots through a free list
-            p->items.reserve(n_compute);
-            int32_t cur = -1;
-            for (int32_t n : order) {
-                if (p->node_launch[n] != cur) {
-                    // slots of arguments consumed by the previous group may be reused from here on
-                    free_slots.insert(free_slots.end(), release.begin(), release.end());
-                    release.clear();
-                    p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0});
-                    cur = p->node_launch[n];
-                }
-                const bool is_root = (n == p->root[example[n]]);
-                if (pingpong) {
-                    // arguments of a label-l node all sit at label l+1: two alternating halves suffice
-                    slot[n] = (p->level[n] & 1) * maxw + rank_in_level[p->level[n]]++;
-                } else if (!is_root) {
-                    if (recycle && !free_slots.empty()) { slot[n] = free_slots.back(); free_slots.pop_back(); }
-                    else slot[n] = running++;
-                }
-                auto src = [&](int32_t c) -> int32_t {
-                    if (c < 0) return 0;
-                    if (!is_compute(c)) return -1 - example[c];
-                    if (recycle) release.push_back(slot[c]);
-                    return slot[c];
-                };
-                dynb_item it;
-                it.src0 = src(p->child0[n]);
-                it.src1 = src(p->child1[n]);
-                it.dst = is_root ? -1 - example[n] : slot[n];
-                it.type = p->type[n];
-                ++p->launches.back().count;
-                p->items.push_back(it);
-            }
-            p->n_slots = pingpong ? 2 * maxw : running;
-            for (const auto& l : p->launches) p->max_launch = std::max(p->max_launch, l.count);
-        }
-        for (int32_t i = 0; i < B; ++i)
-            if (arity[p->type[p->root[i]]] == 0) p->leaf_roots.push_back(i);
+        build_lists(p, arity, prog_off, example, queue_pos, balance, false);
     } catch (const std::bad_alloc&) {
         delete p;
         return fail(DYNB_E_NOMEM, "dynbatch_plan: out of host memory");
+    }
+    *out = p;
+    return DYNB_OK;
+}
+
+namespace {
+
+// Labels of one dependency graph (nodes [base, base + n), argument indices local to the example).
+// Returns false if it is malformed: a function id or argument index out of range, an argument
+// count that differs from the arity, a cycle, or a node the root does not depend on.
+bool label_graph(const int32_t* type, const int32_t* arg0, const int32_t* arg1, int32_t base, int32_t n,
+                 int32_t root, const uint8_t* arity, int32_t n_types, int32_t* rootdist, int32_t* depdepth,
+                 int32_t* queue_pos, std::vector<int32_t>& post, std::vector<int32_t>& stack, std::vector<uint8_t>& state)
+{
+    if (n <= 0 || root < 0 || root >= n) return false;
+    for (int32_t j = 0; j < n; ++j) {
+        const int32_t t = type[base + j], a = arg0[base + j], b = arg1[base + j];
+        if (t < 0 || t >= n_types || a < -1 || a >= n || b < -1 || b >= n) return false;
+        if ((a >= 0) + (b >= 0) != arity[t] || (b >= 0 && a < 0)) return false;
+    }
+    // depth-first from the root with an explicit stack: state 0 unseen, 1 open (on the path), 2 closed;
+    // a node enters `post` when all its arguments are closed
+    post.clear(); stack.clear(); state.assign(size_t(n), 0);
+    stack.push_back(root);
+    while (!stack.empty()) {
+        const int32_t j = stack.back();
+        if (state[j] == 2) { stack.pop_back(); continue; }
+        if (state[j] == 0) {
+            state[j] = 1;
+            for (int32_t a : {arg1[base + j], arg0[base + j]}) {
+                if (a < 0) continue;
+                if (state[a] == 1) return false;                  // back edge: a cycle
+                if (state[a] == 0) stack.push_back(a);
+            }
+        } else {                                                  // arguments done
+            state[j] = 2;
+            queue_pos[base + j] = int32_t(post.size());
+            post.push_back(j);
+            stack.pop_back();
+        }
+    }
+    if (int32_t(post.size()) != n) return false;                  // some node does not feed the root
+    for (int32_t j : post) {                                      // arguments before consumers
+        int32_t d = 0;
+        for (int32_t a : {arg0[base + j], arg1[base + j]})
+            if (a >= 0) d = std::max(d, depdepth[base + a] + 1);
+        depdepth[base + j] = d;
+    }
+    for (int32_t j = 0; j < n; ++j) rootdist[base + j] = -1;
+    rootdist[base + root] = 0;
+    for (auto it = post.rbegin(); it != post.rend(); ++it)        // consumers before arguments: longest path
+        for (int32_t a : {arg0[base + *it], arg1[base + *it]})
+            if (a >= 0) rootdist[base + a] = std::max(rootdist[base + a], rootdist[base + *it] + 1);
+    return true;
+}
+
+}  // namespace
+
+extern "C" int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const int32_t* arg1, const int32_t* node_off,
+                                 const int32_t* root, int32_t B, const uint8_t* arity, int32_t n_types,
+                                 uint32_t flags, dynb_plan** out)
+{
+    if (out) *out = nullptr;
+    if (!type || !arg0 || !arg1 || !node_off || !root || !arity || !out)
+        return fail(DYNB_E_INVAL, "dynbatch_plan_dag: NULL argument");
+    if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan_dag: B and n_types must be positive");
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT))
+        return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan_dag: unknown flag bits");
+    const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
+    if (mode != DYNB_SCHED_IMPROVED && mode != DYNB_SCHED_DEPTH)
+        return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan_dag: graphs are scheduled by root distance or dependency depth only");
+    for (int32_t t = 0; t < n_types; ++t)
+        if (arity[t] > 2)
+            return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan_dag: function " + std::to_string(t) + " has arity > 2");
+    if (node_off[0] != 0) return fail(DYNB_E_INVAL, "dynbatch_plan_dag: node_off[0] must be 0");
+    for (int32_t i = 0; i < B; ++i)
+        if (node_off[i + 1] < node_off[i]) return fail(DYNB_E_INVAL, "dynbatch_plan_dag: node_off must not decrease");
+
+    dynb_plan* p = new (std::nothrow) dynb_plan;
+    if (!p) return fail(DYNB_E_NOMEM, "dynbatch_plan_dag: out of host memory");
+    try {
+        const int32_t N = node_off[B];
+        p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
+        p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
+        p->arity.assign(arity, arity + n_types);
+        p->level.resize(N); p->type.assign(type, type + N);
+        p->child0.resize(N); p->child1.resize(N); p->root.resize(B);
+        std::vector<int32_t> rootdist(N), depdepth(N), queue_pos(N), example(N), post, stack;
+        std::vector<uint8_t> state;
+        for (int32_t i = 0; i < B; ++i) {
+            const int32_t base = node_off[i], n = node_off[i + 1] - base;
+            if (!label_graph(type, arg0, arg1, base, n, root[i], arity, n_types, rootdist.data(), depdepth.data(),
+                             queue_pos.data(), post, stack, state)) {
+                delete p;
+                return fail(DYNB_E_MALFORMED, "dynbatch_plan_dag: example " + std::to_string(i) +
+                                                  " is not a well-formed dependency graph");
+            }
+            p->root[i] = base + root[i];
+            for (int32_t j = 0; j < n; ++j) {
+                example[base + j] = i;
+                p->child0[base + j] = arg0[base + j] >= 0 ? base + arg0[base + j] : -1;
+                p->child1[base + j] = arg1[base + j] >= 0 ? base + arg1[base + j] : -1;
+            }
+        }
+        int32_t D = 0;
+        for (int32_t n = 0; n < N; ++n) {
+            p->level[n] = mode == DYNB_SCHED_IMPROVED ? rootdist[n] : depdepth[n];
+            D = std::max(D, p->level[n] + 1);
+        }
+        p->D = D;
+        build_lists(p, arity, node_off, example, queue_pos, false, true);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        return fail(DYNB_E_NOMEM, "dynbatch_plan_dag: out of host memory");
     }
     *out = p;
     return DYNB_OK;

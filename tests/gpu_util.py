@@ -51,6 +51,17 @@ def iep_run(dyn, w, flags: int = 0, weights=None, feats=None, return_dev: bool =
     return out if return_dev else to_host(out)
 
 
+def dag_run(dyn, d, flags: int = 0, weights=None, feats=None):
+    """dependency graphs: plan -> upload -> execute; returns root maps as float32 host array [B,H,W,C]."""
+    plan = dyn.dynbatch_plan_dag(d.node_type, d.arg0, d.arg1, d.node_off, d.root, d.arity, flags)
+    dyn.dynbatch_plan_upload(plan)
+    weights = weights if weights is not None else iep_weights_dev(d)
+    feats = feats if feats is not None else to_dev(d.feats, d.dtype)
+    out = dyn.dynbatch_execute(plan, weights, feats)
+    torch.cuda.synchronize()
+    return to_host(out)
+
+
 def moe_inputs_dev(m, W1: np.ndarray, W2: np.ndarray):
     """Device tensors in the library's layouts (gate matrices transposed to [E,d])."""
     return dict(x=to_dev(m.x, "bf16"), Wg=to_dev(np.ascontiguousarray(m.Wg.T), "bf16"),

@@ -55,6 +55,46 @@ def test_plan_is_bit_exact_on_many_random_batches(dyn, oracle):
             assert_same_plan(v, oracle.plan(w.prog, w.prog_off, w.arity, mode=omode))
 
 
+@pytest.mark.parametrize("mode,omode", [(0, 0), (3, 2)])
+def test_graph_plan_is_bit_exact(dyn, oracle, mode, omode):
+    for seed in range(12):
+        d = iep.dag_batch(seed=seed, B=1 + 7 * seed, C=1, H=1, W=1, dtype="f32", max_nodes=4 + 2 * seed)
+        v = dyn.dynbatch_plan_view(dyn.dynbatch_plan_dag(d.node_type, d.arg0, d.arg1, d.node_off, d.root, d.arity, mode))
+        assert_same_plan(v, oracle.plan_dag(d.node_type, d.arg0, d.arg1, d.node_off, d.root, d.arity, mode=omode))
+        assert v.n_compute_nodes == d.n_module_evals and v.n_slots <= max(v.n_compute_nodes, 1)
+
+
+def test_graph_plan_of_a_tree_equals_the_tree_plan(dyn):
+    w = iep.config2(B=50)
+    n = len(w.prog)
+    a0, a1 = np.full(n, -1, np.int32), np.full(n, -1, np.int32)
+    tree = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
+    for i in range(w.B):                               # arguments as indices inside the example
+        b, e = w.prog_off[i], w.prog_off[i + 1]
+        a0[b:e] = np.where(tree.child0[b:e] >= 0, tree.child0[b:e] - b, -1)
+        a1[b:e] = np.where(tree.child1[b:e] >= 0, tree.child1[b:e] - b, -1)
+    g = dyn.dynbatch_plan_view(dyn.dynbatch_plan_dag(w.prog, a0, a1, w.prog_off, np.zeros(w.B, np.int32), w.arity))
+    for f in FIELDS + ("node_launch",):
+        assert (getattr(g, f) == getattr(tree, f)).all(), f
+
+
+def test_graph_plan_errors(dyn):
+    ar = np.array([0, 1, 2], np.uint8)
+    good = dict(node_type=[1, 0], arg0=[1, -1], arg1=[-1, -1])
+    off = np.array([0, 2, 4], np.int32)
+    for t, a0, a1, r in [([1, 1], [1, 0], [-1, -1], 0), ([1, 0, 0][:2], [0, -1], [-1, -1], 0), ([2, 0], [1, -1], [-1, -1], 0),
+                         ([1, 0], [1, -1], [-1, -1], 2), ([1, 0], [3, -1], [-1, -1], 0)]:
+        with pytest.raises(dyn.DynbError) as e:
+            dyn.dynbatch_plan_dag(good["node_type"] + t, good["arg0"] + a0, good["arg1"] + a1, off, [0, r], ar)
+        assert e.value.name == "DYNB_E_MALFORMED" and "example 1" in str(e.value)
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.dynbatch_plan_dag(good["node_type"], good["arg0"], good["arg1"], off[:2], [0], ar, flags=dyn.DYNB_SCHED_STANDARD)
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+    with pytest.raises(dyn.DynbError) as e:                # a node that the root does not depend on
+        dyn.dynbatch_plan_dag([1, 0, 0], [1, -1, -1], [-1, -1, -1], np.array([0, 3], np.int32), [0], ar)
+    assert e.value.name == "DYNB_E_MALFORMED"
+
+
 def test_threaded_parse_of_a_large_batch(dyn, oracle):
     w = iep.config2(B=2500)                          # > 32768 nodes: the planner uses several threads
     assert len(w.prog) > (1 << 15)
