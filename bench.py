@@ -140,6 +140,18 @@ def main():
         dyn.dynbatch_execute(plan0, weights, feats, out, ws)
     torch.cuda.synchronize()
     exec_ms = (time.perf_counter() - t0) * 1e3 / K
+    # the same launches replayed from a HIP graph (the call enqueues kernels only, so it can be captured)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dyn.dynbatch_execute(plan0, weights, feats, out, ws)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) * 1e3 / K
+    del graph
     # one event pair around all module-kernel launches of a step (set-up work is a stage of its own)
     dyn.dynb_timing_enable(2)
     launch_ms, launch_n = [], int(view.n_launches)
@@ -310,7 +322,7 @@ def main():
                    "schedule": "improved topological sort" + ("" if args.no_balance else " + balanced launch groups")},
         "single_stream": {"ms_per_step": round(one_ms, 4), "module_evals_per_sec": round(n_evals / one_ms * 1e3, 1)},
         "chip_mfma_frac_of_step": round(flops_step / (iep_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "plan_host_ms": round(float(np.mean(plan_ms)), 4), "execute_only_ms": round(exec_ms, 4),
+        "plan_host_ms": round(float(np.mean(plan_ms)), 4), "execute_only_ms": round(exec_ms, 4), "execute_only_graph_replay_ms": round(graph_ms, 4),
         "execute_only_module_evals_per_sec": round(n_evals / exec_ms * 1e3, 1),
         "roofline": {"kernel": "k_module_mfma", "bound": "mfma", "achieved": round(achieved_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
