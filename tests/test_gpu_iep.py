@@ -128,6 +128,38 @@ def test_config2_iep_shaped_sampled(dyn, util, oracle):
     assert np.isfinite(got).all() and (got >= 0).all()
 
 
+def test_config2_in_the_benchmarks_launch_configuration(dyn, util, oracle):
+    """Full config 2 as bench.py times it: balanced + throughput plan, prepared weights, four batches in flight
+    on four streams; sampled examples of every lane against the oracle."""
+    import torch
+    w = iep.config2()
+    weights = util.iep_weights_dev(w)
+    weights["packed"] = dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16)
+    feats = util.to_dev(w.feats, "bf16")
+    flags = dyn.DYNB_SCHED_IMPROVED | dyn.DYNB_PLAN_BALANCE | dyn.DYNB_PLAN_THROUGHPUT
+    torch.cuda.synchronize()
+    lanes = []
+    for _ in range(4):
+        plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
+        lanes.append(dict(stream=torch.cuda.Stream(), plan=plan, out=torch.empty_like(feats),
+                          ws=torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16),
+                                         dtype=torch.uint8, device="cuda")))
+    for step in range(8):
+        ln = lanes[step % 4]
+        if step < 4:
+            dyn.dynbatch_plan_upload(ln["plan"], stream=ln["stream"])
+        dyn.dynbatch_execute(ln["plan"], weights, feats, ln["out"], ln["ws"], stream=ln["stream"])
+    torch.cuda.synchronize()
+    lens = np.diff(w.prog_off)
+    sample = [int(np.argmax(lens)), 3, 200]
+    ref = oracle.iep_forward_workload(w.subset(sample))
+    for ln in lanes:
+        got = util.to_host(ln["out"])
+        for j, i in enumerate(sample):
+            assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
+        assert torch.equal(ln["out"], lanes[0]["out"])
+
+
 def test_execute_error_paths(dyn, util):
     import torch
     w = iep.config0()
