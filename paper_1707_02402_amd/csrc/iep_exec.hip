@@ -231,7 +231,9 @@ __global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict_
 // fragments of all 8 steps
 // of a tap sit in registers: each is re-fetched from global memory one step after its last use,
 // i.e. 7 steps (> 1800 clocks) ahead of its next use.  Scheduler fences keep that order.
-template <int MTW, bool CENTER_ONLY, int RW = 8>
+// TAIL: the wave's last pixel-tile slot is shared by the four waves of a node; this wave multiplies
+// only its first channel tile (wrow[0]) of it, into acc[MTW-1][0].
+template <int MTW, bool CENTER_ONLY, int RW = 8, bool TAIL = false>
 __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t (&xaddr)[MTW], int mcount,
                                            const bf16_t* (&wrow)[2])
 {
@@ -257,9 +259,13 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
         for (int t = 0; t < MTW; ++t) {
             if (t < mcount) {
                 xn[t] = lds_read_frag(xaddr[t] + noff);
+                if (TAIL && t == MTW - 1) {
+                    acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[0], xc[t], acc[t][0], 0, 0, 0);
+                } else {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[nt], xc[t], acc[t][nt], 0, 0, 0);
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[nt], xc[t], acc[t][nt], 0, 0, 0);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             if (t == 0) {
@@ -298,7 +304,8 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
 // WM selects how a node is spread over waves and workgroups.
 //   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles
 //           each): best throughput per CU, used for the widest launch groups.
-//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 4 or 3 pixel tiles).
+//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 3 pixel tiles, plus 32 channels
+//           of the seventh pixel tile: 7 MFMA tiles per wave).
 //   WM = 3: half a node per workgroup: output rows 0..6 or 7..13.  The workgroup convolves an 8-row
 //           window (rows 0..7 or 6..13: the second conv needs one row of the first conv's output
 //           beyond its own rows), i.e. 112 pixels = 4 pixel tiles, 2 per wave.  Two CUs share a node,
@@ -340,8 +347,17 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     const uint32_t tile = uint32_t(node_local) * TILE_BYTES;
     const int r = lane & 31, h = lane >> 5;
     const int n0 = (wi & 1) * 64;             // first output channel of this wave
-    const int m0 = (wi >> 1) * MTW;           // first pixel tile of this wave
-    const int mcount = (WM == 2) ? (MT7 - m0 < MTW ? MT7 - m0 : MTW) : MTW;
+    // One node per workgroup: 7 pixel tiles x 4 channel tiles = 28 MFMA tiles for 4 waves.  Wave
+    // (pixel group pg, channel half) owns pixel tiles 3 pg .. 3 pg + 2 for its 64 channels and, in its
+    // fourth slot, one 32-channel quarter of pixel tile 6: 7 MFMA tiles per wave, the four SIMDs of
+    // the CU carry the same load.
+    constexpr bool TAIL = (WM == 2);
+    const int pg = wi >> 1;
+    const int m0 = TAIL ? pg * 3 : pg * MTW;  // first pixel tile of this wave
+    const int mcount = MTW;
+    auto tile_of = [&](int t) -> int { return (TAIL && t == MTW - 1) ? MT7 - 1 : m0 + t; };
+    // first channel of accumulator acc[t][nt], and whether this wave owns it
+    auto live = [&](int t, int nt) -> bool { return !(TAIL && t == MTW - 1 && nt == 1); };
 
     // ---- gather: zero border once, then the argument map into the centre of the halo tile;
     // all global loads of the map are issued before the first LDS write, so one memory latency is paid
@@ -388,27 +404,41 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     uint32_t xaddr[MTW];
 #pragma unroll
     for (int t = 0; t < MTW; ++t) {
-        const int p = wrow0 * S + min((m0 + t) * 32 + r, NPIX - 1);
+        const int p = wrow0 * S + min(tile_of(t) * 32 + r, NPIX - 1);
         xaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
     }
     // this lane's 16 accumulator elements of channel tile nt are channels n0 + nt*32 + 16*h + (0..15)
     // (the packed weights carry the matching row permutation)
     const int cbase = n0 + 16 * h;
+    // A wave's two channel tiles are numbered so that its quarter of the shared pixel tile is tile 0:
+    // waves of pixel group 1 take their channel tiles in swapped order.
+    const int ntswap = TAIL ? pg : 0;
+    auto chan = [&](int nt) -> int { return cbase + ((nt ^ ntswap) * 32); };
     f32x16 acc[MTW][2];
 
+    constexpr int NFULL = (WM == 2) ? MTW - 1 : MTW;          // slots that hold both channel tiles
     auto init_bias = [&](const float* bias) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + cbase + nt * 32 + b * 4);
+                if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan(nt) + b * 4);
 #pragma unroll
-                for (int t = 0; t < MTW; ++t) {
+                for (int t = 0; t < NFULL; ++t) {
                     acc[t][nt][4 * b + 0] = v.x; acc[t][nt][4 * b + 1] = v.y;
                     acc[t][nt][4 * b + 2] = v.z; acc[t][nt][4 * b + 3] = v.w;
                 }
             }
+        if (NFULL < MTW) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan(0) + b * 4);
+                acc[MTW - 1][0][4 * b + 0] = v.x; acc[MTW - 1][0][4 * b + 1] = v.y;
+                acc[MTW - 1][0][4 * b + 2] = v.z; acc[MTW - 1][0][4 * b + 3] = v.w;
+            }
+        }
     };
     // byte address of this lane's centre pixel of tile t (channel 0)
     auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
@@ -435,16 +465,16 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
         uint32_t uaddr[MTW];
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            const int p = urow0 * S + min((m0 + t) * 32 + r, UPIX - 1);
+            const int p = urow0 * S + min(tile_of(t) * 32 + r, UPIX - 1);
             uaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
         }
         const bf16_t* w1row[2];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
-            w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
+            w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 2 * 8) * FRAG + lane * 8;
         if (binary) {
             init_bias(a.b1);
-            kloop_mfma<MTW, true, RW>(acc, uaddr, mcount, w1row);
+            kloop_mfma<MTW, true, RW, TAIL>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
@@ -452,19 +482,20 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
         if (binary) {
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) w1row[nt] += 8 * FRAG;
-            kloop_mfma<MTW, true, RW>(acc, uaddr, mcount, w1row);
+            kloop_mfma<MTW, true, RW, TAIL>(acc, uaddr, mcount, w1row);
         }
         __syncthreads();
         if (binary) {                                     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
 #pragma unroll
             for (int t = 0; t < MTW; ++t)
-                if (t < mcount && (m0 + t) * 32 + r < UPIX) {
+                if (t < mcount && tile_of(t) * 32 + r < UPIX) {
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                         for (int q = 0; q < 2; ++q)
-                            *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
-                                                      uint32_t((cbase + nt * 32 + q * 8) * 2)) = packed(t, nt, q);
+                            if (live(t, nt))
+                                *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
+                                                          uint32_t((chan(nt) + q * 8) * 2)) = packed(t, nt, q);
                 }
         }
         __syncthreads();
@@ -476,40 +507,55 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     if (active) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
-            wrow[nt] = a.w3a + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
+            wrow[nt] = a.w3a + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 9 * 8) * FRAG + lane * 8;
         init_bias(a.b3a);
-        kloop_mfma<MTW, false, RW>(acc, xaddr, mcount, wrow);
+        kloop_mfma<MTW, false, RW, TAIL>(acc, xaddr, mcount, wrow);
     }
     PHASE(4);
     __syncthreads();
     PHASE(5);
     if (active) {
+        auto bias8 = [&](int ch, f32x4& lo, f32x4& hi) {
+            lo = f32x4{0.f, 0.f, 0.f, 0.f};
+            hi = lo;
+            if (a.b3b) {
+                const float* bp = a.b3b + size_t(it.type) * C + ch;
+                lo = *reinterpret_cast<const f32x4*>(bp);
+                hi = *reinterpret_cast<const f32x4*>(bp + 4);
+            }
+        };
+        // acc[t][nt][8q .. 8q+7]: ReLU'd bf16 into the tile, old centre values + bias back into acc
+        auto swap8 = [&](int t, int nt, int q, const f32x4& blo, const f32x4& bhi) {
+            const uint32_t addr = centre(t) + uint32_t((chan(nt) + q * 8) * 2);
+            const u32x4 res = *reinterpret_cast<const u32x4*>(lds_raw + addr);
+            *reinterpret_cast<u32x4*>(lds_raw + addr) = packed(t, nt, q);
+            acc[t][nt][8 * q + 0] = __uint_as_float(res.x << 16) + blo.x;
+            acc[t][nt][8 * q + 1] = __uint_as_float(res.x & 0xffff0000u) + blo.y;
+            acc[t][nt][8 * q + 2] = __uint_as_float(res.y << 16) + blo.z;
+            acc[t][nt][8 * q + 3] = __uint_as_float(res.y & 0xffff0000u) + blo.w;
+            acc[t][nt][8 * q + 4] = __uint_as_float(res.z << 16) + bhi.x;
+            acc[t][nt][8 * q + 5] = __uint_as_float(res.z & 0xffff0000u) + bhi.y;
+            acc[t][nt][8 * q + 6] = __uint_as_float(res.w << 16) + bhi.z;
+            acc[t][nt][8 * q + 7] = __uint_as_float(res.w & 0xffff0000u) + bhi.w;
+        };
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                f32x4 blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
-                if (a.b3b) {
-                    const float* bp = a.b3b + size_t(it.type) * C + cbase + nt * 32 + q * 8;
-                    blo = *reinterpret_cast<const f32x4*>(bp);
-                    bhi = *reinterpret_cast<const f32x4*>(bp + 4);
-                }
+                f32x4 blo, bhi;
+                bias8(chan(nt) + q * 8, blo, bhi);
 #pragma unroll
-                for (int t = 0; t < MTW; ++t)
-                    if (t < mcount && (m0 + t) * 32 + r < NPIX) {
-                        const uint32_t addr = centre(t) + uint32_t((cbase + nt * 32 + q * 8) * 2);
-                        const u32x4 res = *reinterpret_cast<const u32x4*>(lds_raw + addr);
-                        *reinterpret_cast<u32x4*>(lds_raw + addr) = packed(t, nt, q);
-                        acc[t][nt][8 * q + 0] = __uint_as_float(res.x << 16) + blo.x;
-                        acc[t][nt][8 * q + 1] = __uint_as_float(res.x & 0xffff0000u) + blo.y;
-                        acc[t][nt][8 * q + 2] = __uint_as_float(res.y << 16) + blo.z;
-                        acc[t][nt][8 * q + 3] = __uint_as_float(res.y & 0xffff0000u) + blo.w;
-                        acc[t][nt][8 * q + 4] = __uint_as_float(res.z << 16) + bhi.x;
-                        acc[t][nt][8 * q + 5] = __uint_as_float(res.z & 0xffff0000u) + bhi.y;
-                        acc[t][nt][8 * q + 6] = __uint_as_float(res.w << 16) + bhi.z;
-                        acc[t][nt][8 * q + 7] = __uint_as_float(res.w & 0xffff0000u) + bhi.w;
-                    }
+                for (int t = 0; t < NFULL; ++t)
+                    if (t < mcount && tile_of(t) * 32 + r < NPIX) swap8(t, nt, q, blo, bhi);
             }
+        if (TAIL && tile_of(MTW - 1) * 32 + r < NPIX) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                f32x4 blo, bhi;
+                bias8(chan(0) + q * 8, blo, bhi);
+                swap8(MTW - 1, 0, q, blo, bhi);
+            }
+        }
     }
     PHASE(6);
     __syncthreads();
@@ -519,20 +565,21 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     if (active) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
-            wrow[nt] = a.w3b + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8) * FRAG + lane * 8;
-        kloop_mfma<MTW, false, RW>(acc, xaddr, mcount, wrow);
+            wrow[nt] = a.w3b + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 9 * 8) * FRAG + lane * 8;
+        kloop_mfma<MTW, false, RW, TAIL>(acc, xaddr, mcount, wrow);
         PHASE(8);
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            const int pl = (m0 + t) * 32 + r;
+            const int pl = tile_of(t) * 32 + r;
             const int p = wrow0 * S + pl;
             if (t < mcount && pl < NPIX && p >= orow0 * S && p < orow1 * S) {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
-                        *reinterpret_cast<u32x4*>(dst + size_t(p) * C + cbase + nt * 32 + q * 8) = packed(t, nt, q);
+                        if (live(t, nt))
+                            *reinterpret_cast<u32x4*>(dst + size_t(p) * C + chan(nt) + q * 8) = packed(t, nt, q);
             }
         }
     }
