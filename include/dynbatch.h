@@ -217,7 +217,9 @@ size_t dynbatch_workspace_bytes(const dynb_plan* plan, const dynb_shape* shape);
  * function and parameter block.
  *   feats      device [B][H][W][C]  the SCENE output of each example
  *   out        device [B][H][W][C]  receives each example's root map
- *   workspace  device, >= dynbatch_workspace_bytes, 256-byte aligned; contents are scratch
+ *   workspace  device, >= dynbatch_workspace_bytes, 256-byte aligned; contents are scratch, and
+ *              nothing else may read or write it until the call's work on `stream` has finished
+ *              (calls in flight on different streams need a workspace each)
  * The fast path (bf16, C = 128, 14 x 14) runs fused MFMA kernels; every other shape runs generic
  * kernels with the same semantics.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (workspace too small
  * or plan not uploaded), DYNB_E_UNSUPPORTED (dtype; w1 NULL with binary functions), DYNB_E_HIP. */
@@ -265,7 +267,9 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *   W2     device [E][d][h]   bf16   (row c of W2_e produces output channel c)
  *   out    device [T][d]      bf16
  *   aux    host struct of device pointers, or NULL
- *   workspace device, >= moe_workspace_bytes, 256-byte aligned
+ *   workspace device, >= moe_workspace_bytes, 256-byte aligned; it holds the routing tables of the
+ *             call, so nothing else may write it until the call's work on `stream` has finished
+ *             (calls in flight on different streams need a workspace each)
  * T = 0 succeeds without work.  Errors: DYNB_E_INVAL (NULL, k > E, k > 8, sizes <= 0, d or h not
  * a multiple of 32), DYNB_E_WORKSPACE, DYNB_E_UNSUPPORTED (dtype), DYNB_E_HIP.                   */
 int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const void* Wn,

@@ -178,3 +178,24 @@ def test_every_token_to_one_expert_with_a_one_row_tail_tile(dyn, util, oracle):
     assert (aux["perm"] == np.arange(577)).all() and np.allclose(aux["topk_w"], 1.0)
     ref = oracle.moe_experts(m.x, aux["topk_idx"], aux["topk_w"], W1, W2)
     assert util.normwise(out, ref) < OUT_TOL
+
+
+def test_layers_in_flight_on_three_streams(dyn, util):
+    """Independent calls on their own streams, workspaces and outputs do not disturb each other.  The device is
+    drained after the buffers are allocated: a side stream must not meet memory the default stream still uses."""
+    import torch
+    m = moe.config3()
+    W1, W2 = stack(m)
+    dev = util.moe_inputs_dev(m, W1, W2)
+    args = (dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k)
+    ref = dyn.moe_forward(*args)
+    nb = dyn.moe_workspace_bytes(m.T, m.d, m.h, m.E, m.k)
+    lanes = [dict(s=torch.cuda.Stream(), ws=torch.empty(nb, dtype=torch.uint8, device="cuda"), out=torch.empty_like(ref))
+             for _ in range(3)]
+    torch.cuda.synchronize()
+    for i in range(9):
+        ln = lanes[i % 3]
+        dyn.moe_forward(*args, out=ln["out"], workspace=ln["ws"], stream=ln["s"])
+    torch.cuda.synchronize()
+    for ln in lanes:
+        assert torch.equal(ln["out"], ref)
