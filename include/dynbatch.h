@@ -7,6 +7,8 @@
  *   1. Program-tree execution engine (Background / Visual Reasoning Programs; Methods):
  *      dynbatch_plan()    host  — prefix programs + arities -> trees -> labels -> pools with
  *                                 gather/scatter index lists
+ *      dynbatch_plan_dag() host — the same for dependency graphs whose nodes may have several
+ *                                 consumers (Discussion)
  *      dynbatch_execute() GPU   — runs the pools: gather the arguments, one batched residual
  *                                 conv module per pool, scatter the results; root maps come back
  *   2. Sparsely gated mixture of experts (Results / Sparsely Gated Mixture of Experts):

@@ -119,6 +119,7 @@ __global__ void k_gen_conv(GenArgs a)
 __global__ void k_copy_leaf_roots(const int32_t* examples, int n, const uint32_t* feats, uint32_t* out,
                                   size_t words_per_map)
 {
+    if (int(blockIdx.y) >= n) return;
     const int ex = examples[blockIdx.y];
     for (size_t w = size_t(blockIdx.x) * blockDim.x + threadIdx.x; w < words_per_map;
          w += size_t(gridDim.x) * blockDim.x)
@@ -140,7 +141,6 @@ constexpr int PIX_BYTES = 272;           // 128 channels bf16 + 16 bytes pad: 17
 constexpr int ROW_BYTES = HALO * PIX_BYTES + 14 * 16;  // 4576
 constexpr int TILE_BYTES = HALO * ROW_BYTES;           // 73216
 constexpr int CENTER = ROW_BYTES + PIX_BYTES;           // (+1,+1) from the top-left tap
-constexpr int MAP_BYTES = P * C * 2;     // 50176
 }  // namespace mf
 
 // Development aid, compiled in only with -DDYNB_PHASE_CLOCKS: lane 0 of every wave stores the
