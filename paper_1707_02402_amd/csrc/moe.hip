@@ -34,7 +34,8 @@ namespace {
 
 constexpr int SORT_BLOCK = 256;   // uses ranked together by one workgroup
 constexpr int TM = 64;            // rows of one grouped-GEMM tile
-constexpr int TN = 128;           // output features of one grouped-GEMM tile
+constexpr int TN = 256;           // output features of one grouped-GEMM tile
+constexpr int NTW = TN / 64;      // 16-feature sub-tiles per wave (4 waves split the features)
 constexpr int MAX_K = 8;
 constexpr int MG = 8;             // row tiles of one expert that walk the feature tiles together
 constexpr int XCD_CHUNK = 128;    // consecutive grouped-GEMM tiles dealt to one XCD
@@ -348,15 +349,16 @@ __global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, c
 }
 
 // ------------------------------------------------------------------------------------------ grouped GEMM
-// Tile body: out[row0 .. row0+rows)[nb .. nb+128) = act(in[rows][K] . We[n][K]^T), ML = live 16-row tiles.
+// Tile body: out[row0 .. row0+rows)[nb .. nb+TN) = act(in[rows][K] . We[n][K]^T), ML = live 16-row tiles.
 //
 // Operands go through LDS in K-chunks of 64.  Loading MFMA fragments straight from global memory
 // makes every lane of a load touch its own 16 bytes of a different row, and the vector L1 then
 // retires about one lane per clock (measured: ~16 B/clk per CU, which capped this kernel at 2 ms
 // per layer).  Staged loads instead let 8 neighbouring lanes read one row's 128 contiguous bytes;
 // the fragments are then cut out of LDS with ds_read_b128 (row pitch 144 bytes, conflict free).
-// The next chunk is fetched into registers while the current one is multiplied, so with 4-5
-// workgroups per CU about 100 KB of weight reads stay in flight per CU.
+// The next chunk is fetched into registers while the current one is multiplied: 40 KB per
+// workgroup, two workgroups per CU.  (Tiles of 128 features with four workgroups per CU stream
+// the second layer's 4 KB-pitched weight rows 15 % slower and are no faster elsewhere.)
 constexpr int KC = 64;                 // K-chunk
 constexpr int LDP = KC + 8;            // LDS row pitch in elements (144 bytes)
 
@@ -388,11 +390,11 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
             if (i * RPP < ML * 16)                    // only rows of live 16-row sub-tiles
                 xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
     };
-    f32x4 acc[ML][2];
+    f32x4 acc[ML][NTW];
 #pragma unroll
     for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
+        for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
     const int nchunk = (K + KC - 1) / KC;
     fetch(0);
     for (int kc = 0; kc < nchunk; ++kc) {
@@ -406,29 +408,29 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
         if (kc + 1 < nchunk) fetch(kc + 1);
 #pragma unroll
         for (int kk = 0; kk < KC / 32; ++kk) {
-            bf16x8 wf[2], xf[ML];
+            bf16x8 wf[NTW], xf[ML];
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-                wf[nt] = *reinterpret_cast<const bf16x8*>(Ws + (wave * 32 + nt * 16 + r) * LDP + kk * 32 + g * 8);
+            for (int nt = 0; nt < NTW; ++nt)
+                wf[nt] = *reinterpret_cast<const bf16x8*>(Ws + (wave * (TN / 4) + nt * 16 + r) * LDP + kk * 32 + g * 8);
 #pragma unroll
             for (int mt = 0; mt < ML; ++mt)
                 xf[mt] = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * LDP + kk * 32 + g * 8);
 #pragma unroll
             for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NTW; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[mt], acc[mt][nt], 0, 0, 0);
         }
         __syncthreads();
     }
     // lane holds features n0 + nt*16 + g*4 .. +3 of row row0 + mt*16 + r
-    const int n0 = nb + wave * 32;
+    const int n0 = nb + wave * (TN / 4);
 #pragma unroll
     for (int mt = 0; mt < ML; ++mt) {
         const int lr = mt * 16 + r;
         if (lr >= rows) continue;
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NTW; ++nt) {
             const int n = n0 + nt * 16 + g * 4;
             if (n >= N) continue;
             const f32x4 v = acc[mt][nt];
@@ -442,9 +444,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
 }
 
 // out[row][n] = act( sum_k in[row][k] * W[e][n][k] ) for the rows of expert e.
-// One workgroup = one (row tile of <= 64 rows inside one group, 128 output features) pair; a group's
+// One workgroup = one (row tile of <= 64 rows inside one group, 256 output features) pair; a group's
 // tiles are found from tile_start (prefix sum of ceil(count/64)), so ragged and empty groups cost
-// nothing beyond their real rows.  4 waves split the 128 features; only the live 16-row sub-tiles
+// nothing beyond their real rows.  4 waves split the 256 features; only the live 16-row sub-tiles
 // are multiplied.  N must be a multiple of 4 (it is: d and h are multiples of 32).
 template <bool RELU>
 __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
