@@ -203,7 +203,6 @@ namespace mf {
 constexpr int FRAG = 512;   // elements of one packed weight fragment: 64 lanes x 8 bf16 = 1 KB
 }
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // dst[function][tile][tap][j][lane][i] = src[function][co = tile*32 + rho(lane%32)][tap][ci = (lane/32)*64 + j*8 + i]
 // one thread per 16-byte piece; ntap = 9 for a conv3x3, 2 for the two halves of the conv1x1 over 2C inputs.

@@ -390,56 +390,98 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
             if (i * RPP < ML * 16)                    // only rows of live 16-row sub-tiles
                 xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
     };
-    f32x4 acc[ML][NTW];
-#pragma unroll
-    for (int mt = 0; mt < ML; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
     const int nchunk = (K + KC - 1) / KC;
-    fetch(0);
-    for (int kc = 0; kc < nchunk; ++kc) {
+    // one K-chunk through LDS: registers -> LDS, barrier, prefetch of the next chunk, multiply, barrier
+    auto chunk_loop = [&](auto&& multiply) {
+        fetch(0);
+        for (int kc = 0; kc < nchunk; ++kc) {
 #pragma unroll
-        for (int i = 0; i < WPASS; ++i)
-            *reinterpret_cast<u32x4*>(Ws + (prow + i * RPP) * LDP + part * 8) = wreg[i];
+            for (int i = 0; i < WPASS; ++i)
+                *reinterpret_cast<u32x4*>(Ws + (prow + i * RPP) * LDP + part * 8) = wreg[i];
 #pragma unroll
-        for (int i = 0; i < XPASS; ++i)
-            if (i * RPP < ML * 16) *reinterpret_cast<u32x4*>(Xs + (prow + i * RPP) * LDP + part * 8) = xreg[i];
-        __syncthreads();
-        if (kc + 1 < nchunk) fetch(kc + 1);
+            for (int i = 0; i < XPASS; ++i)
+                if (i * RPP < ML * 16) *reinterpret_cast<u32x4*>(Xs + (prow + i * RPP) * LDP + part * 8) = xreg[i];
+            __syncthreads();
+            if (kc + 1 < nchunk) fetch(kc + 1);
+            multiply();
+            __syncthreads();
+        }
+    };
+    const int n0 = nb + wave * (TN / 4);          // first feature of this wave
+    auto store4 = [&](int lr, int n, float v0, float v1, float v2, float v3) {
+        if (lr >= rows || n >= N) return;
+        u32x2 pk;
+        pk.x = pack_bf16x2(v0, v1);
+        pk.y = pack_bf16x2(v2, v3);
+        if (RELU) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }
+        *reinterpret_cast<u32x2*>(out + size_t(row0 + lr) * N + n) = pk;
+    };
+    if constexpr (ML == 4) {
+        // all four 16-row sub-tiles live: 32x32x16 MFMAs (the faster bf16 shape), 2 x 2 tiles per wave
+        static_assert(TN == 256, "two 32-feature tiles per wave");
+        const int q = lane & 31, hk = lane >> 5;
+        f32x16 acc[2][2];
 #pragma unroll
-        for (int kk = 0; kk < KC / 32; ++kk) {
-            bf16x8 wf[NTW], xf[ML];
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int nt = 0; nt < NTW; ++nt)
-                wf[nt] = *reinterpret_cast<const bf16x8*>(Ws + (wave * (TN / 4) + nt * 16 + r) * LDP + kk * 32 + g * 8);
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int mt = 0; mt < ML; ++mt)
-                xf[mt] = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * LDP + kk * 32 + g * 8);
+                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+        chunk_loop([&] {
 #pragma unroll
-            for (int mt = 0; mt < ML; ++mt)
+            for (int ks = 0; ks < KC / 16; ++ks) {
+                bf16x8 wf[2], xf[2];
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    wf[a] = *reinterpret_cast<const bf16x8*>(Ws + (wave * 64 + a * 32 + q) * LDP + ks * 16 + hk * 8);
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    xf[b] = *reinterpret_cast<const bf16x8*>(Xs + (b * 32 + q) * LDP + ks * 16 + hk * 8);
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
+            }
+        });
+        // lane holds row b*32 + q, features n0 + a*32 + 8j + 4hk .. +3 in acc[a][b][4j .. 4j+3]
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    store4(b * 32 + q, n0 + a * 32 + 8 * j + 4 * hk, acc[a][b][4 * j], acc[a][b][4 * j + 1],
+                           acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+    } else {
+        f32x4 acc[ML][NTW];
+#pragma unroll
+        for (int mt = 0; mt < ML; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0, 0, 0, 0};
+        chunk_loop([&] {
+#pragma unroll
+            for (int kk = 0; kk < KC / 32; ++kk) {
+                bf16x8 wf[NTW], xf[ML];
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[mt], acc[mt][nt], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-    // lane holds features n0 + nt*16 + g*4 .. +3 of row row0 + mt*16 + r
-    const int n0 = nb + wave * (TN / 4);
+                    wf[nt] = *reinterpret_cast<const bf16x8*>(Ws + (wave * (TN / 4) + nt * 16 + r) * LDP + kk * 32 + g * 8);
 #pragma unroll
-    for (int mt = 0; mt < ML; ++mt) {
-        const int lr = mt * 16 + r;
-        if (lr >= rows) continue;
+                for (int mt = 0; mt < ML; ++mt)
+                    xf[mt] = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * LDP + kk * 32 + g * 8);
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const int n = n0 + nt * 16 + g * 4;
-            if (n >= N) continue;
-            const f32x4 v = acc[mt][nt];
-            u32x2 pk;
-            pk.x = pack_bf16x2(v.x, v.y);
-            pk.y = pack_bf16x2(v.z, v.w);
-            if (RELU) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }
-            *reinterpret_cast<u32x2*>(out + size_t(row0 + lr) * N + n) = pk;
-        }
+                for (int mt = 0; mt < ML; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[mt], acc[mt][nt], 0, 0, 0);
+            }
+        });
+        // lane holds features n0 + nt*16 + g*4 .. +3 of row mt*16 + r
+#pragma unroll
+        for (int mt = 0; mt < ML; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt)
+                store4(mt * 16 + r, n0 + nt * 16 + g * 4, acc[mt][nt].x, acc[mt][nt].y, acc[mt][nt].z, acc[mt][nt].w);
     }
 }
 
