@@ -45,8 +45,8 @@ __device__ __forceinline__ bf16x8 ldg_frag(const bf16_t* p) { return *reinterpre
 // ------------------------------------------------------------------------------------------ gate
 // Workgroup tile: 64 tokens x 64 experts, both gate matrices at once.  Operands are staged through
 // LDS in K-chunks of 64 with coalesced 128-byte row reads (see the grouped GEMM below for why), the
-// next chunk is prefetched into registers.  Wave w owns experts [16w, 16w+16) of the tile for all
-// 64 tokens: 4 token tiles x (clean, noise) accumulators.
+// next chunk is prefetched into registers.  A wave owns a 32-token x 32-expert quarter of the tile
+// for both matrices (clean and noise accumulators), multiplied with 32x32x16 MFMAs.
 constexpr int GKC = 64;                // K-chunk
 constexpr int GLDP = GKC + 8;          // LDS row pitch in elements (144 bytes, conflict free)
 
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
 {
     __shared__ __attribute__((aligned(16))) bf16_t Ws[128 * GLDP];   // rows 0..63 Wg, 64..127 Wn
     __shared__ __attribute__((aligned(16))) bf16_t Xs[64 * GLDP];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int t0 = blockIdx.y * 64, e0 = blockIdx.x * 64;
     const int part = tid & 7, srow = tid >> 3;          // staging: 32 rows x 8 pieces of 16 bytes per pass
     const bf16_t* wsrc[4];
@@ -78,9 +78,11 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
         for (int i = 0; i < 2; ++i)
             xreg[i] = inside ? *reinterpret_cast<const u32x4*>(xsrc[i] + kc * GKC) : u32x4{0u, 0u, 0u, 0u};
     };
-    f32x4 ag[4], an[4];
+    // 4 waves = 2 token halves x 2 expert halves; each wave one 32 x 32 tile per gate matrix (32x32x16 MFMAs)
+    const int q = lane & 31, hk = lane >> 5, th = wave & 1, eh = wave >> 1;
+    f32x16 ag, an;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) { ag[mt] = f32x4{0, 0, 0, 0}; an[mt] = f32x4{0, 0, 0, 0}; }
+    for (int i = 0; i < 16; ++i) { ag[i] = 0.f; an[i] = 0.f; }
     const int nchunk = (d + GKC - 1) / GKC;
     fetch(0);
     for (int kc = 0; kc < nchunk; ++kc) {
@@ -91,35 +93,32 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
         __syncthreads();
         if (kc + 1 < nchunk) fetch(kc + 1);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 gf = *reinterpret_cast<const bf16x8*>(Ws + (wave * 16 + r) * GLDP + kk * 32 + g * 8);
-            const bf16x8 nf = *reinterpret_cast<const bf16x8*>(Ws + (64 + wave * 16 + r) * GLDP + kk * 32 + g * 8);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + (mt * 16 + r) * GLDP + kk * 32 + g * 8);
-                ag[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, gf, ag[mt], 0, 0, 0);
-                if (noise) an[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, nf, an[mt], 0, 0, 0);
+        for (int ks = 0; ks < GKC / 16; ++ks) {
+            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + (th * 32 + q) * GLDP + ks * 16 + hk * 8);
+            const bf16x8 gf = *reinterpret_cast<const bf16x8*>(Ws + (eh * 32 + q) * GLDP + ks * 16 + hk * 8);
+            ag = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, gf, ag, 0, 0, 0);
+            if (noise) {
+                const bf16x8 nf = *reinterpret_cast<const bf16x8*>(Ws + (64 + eh * 32 + q) * GLDP + ks * 16 + hk * 8);
+                an = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, nf, an, 0, 0, 0);
             }
         }
         __syncthreads();
     }
-    // lane holds tokens t0 + mt*16 + g*4 + i, expert e0 + wave*16 + r
-    const int e = e0 + wave * 16 + r;
+    // lane holds expert e0 + eh*32 + q, tokens t0 + th*32 + 8*(i/4) + 4*hk + i%4 in element i
+    const int e = e0 + eh * 32 + q;
     if (e >= E) return;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int t = t0 + mt * 16 + g * 4 + i;
-            if (t >= T) continue;
-            float v = ag[mt][i];
-            if (noise) {
-                const float z = an[mt][i];
-                const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
-                v += noise[size_t(t) * E + e] * sp;
-            }
-            logits[size_t(t) * E + e] = v;
+    for (int i = 0; i < 16; ++i) {
+        const int t = t0 + th * 32 + 8 * (i / 4) + 4 * hk + (i % 4);
+        if (t >= T) continue;
+        float v = ag[i];
+        if (noise) {
+            const float z = an[i];
+            const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
+            v += noise[size_t(t) * E + e] * sp;
         }
+        logits[size_t(t) * E + e] = v;
+    }
 }
 
 // ------------------------------------------------------------------------------------------ top-k
