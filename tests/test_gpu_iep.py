@@ -302,3 +302,26 @@ def test_throughput_mode_and_batches_in_flight_on_three_streams(dyn, util):
     torch.cuda.synchronize()
     for ln in lanes:
         assert torch.equal(ln["out"], ref)
+
+
+def test_random_shapes_and_schedules(dyn, util, oracle):
+    """Seeded sweep: generic shapes in both dtypes and the fast shape, every schedule and flag combination."""
+    g = np.random.default_rng(7)
+    flag_sets = [0, 1, 2, 3, dyn.DYNB_PLAN_BALANCE, dyn.DYNB_PLAN_THROUGHPUT, 3 | dyn.DYNB_PLAN_THROUGHPUT,
+                 dyn.DYNB_PLAN_BALANCE | dyn.DYNB_PLAN_THROUGHPUT]
+    for case in range(10):
+        fast = case % 3 == 0
+        dtype = "bf16" if fast else str(g.choice(["f32", "bf16"]))
+        C, H, W = (128, 14, 14) if fast else (int(g.integers(1, 40)), int(g.integers(1, 9)), int(g.integers(1, 9)))
+        if dtype == "bf16" and (C * H * W) % 2:
+            C += 1                                     # bf16 maps are copied in 4-byte words
+        w = iep.small_mixed(seed=300 + case, B=int(g.integers(1, 14)), C=C, H=H, W=W, dtype=dtype, min_len=1,
+                            max_len=int(g.integers(1, 12)))
+        ref = oracle.iep_forward_workload(w)
+        base = None
+        for flags in flag_sets:
+            got = util.iep_run(dyn, w, flags)
+            assert util.normwise(got, ref) < TOL[dtype] or np.abs(ref).max() == 0, (case, flags, C, H, W, dtype)
+            if base is None:
+                base = got
+            assert (got == base).all(), (case, flags)   # every schedule gives the same bits

@@ -207,3 +207,22 @@ def test_layers_in_flight_on_three_streams(dyn, util):
     torch.cuda.synchronize()
     for ln in lanes:
         assert torch.equal(ln["out"], ref)
+
+
+def test_random_small_shapes(dyn, util, oracle):
+    """Seeded sweep over ragged shapes (d, h multiples of 32 only; E and T arbitrary; k up to min(E, 8))."""
+    g = np.random.default_rng(2024)
+    for case in range(10):
+        T = int(g.integers(1, 400))
+        d = int(g.choice([32, 64, 96, 160, 288]))
+        h = int(g.choice([32, 96, 224, 320]))
+        E = int(g.integers(2, 140))
+        k = int(g.integers(1, min(E, 8) + 1))
+        m = moe.small(seed=1000 + case, T=T, d=d, h=h, E=E, k=k, empty_frac=float(g.choice([0.0, 0.3])))
+        W1, W2 = stack(m)
+        out, aux = util.moe_run(dyn, m, W1, W2)
+        shape = (case, T, d, h, E, k)
+        assert util.normwise(aux["logits"], oracle.moe_logits(m.x, m.Wg, m.Wn, m.noise)) < LOGIT_TOL, shape
+        r = check_routing(oracle, m, aux)
+        ref = oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)
+        assert util.normwise(out, ref) < OUT_TOL, shape
