@@ -55,6 +55,8 @@ def main():
         sys.exit(2)
 
     import torch
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # loads the built library; compiles only if there is none
     import paper_1707_02402_amd as dyn
     from tests import gpu_util as U
     from workloads import iep, moe
