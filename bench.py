@@ -9,6 +9,12 @@ One step = one pass of the whole hot path over one batch of synthetic input:
 Inputs are resident in HBM before the timed region.  `value` is module evaluations per second of
 the program-tree part (the metric's first half); the MoE half is in the "moe" object.
 
+By default several independent batches are in flight: step i runs on HIP stream i % --streams (4) with
+its own plan buffer, workspace and output, MoE call i on stream i % --moe-streams (3); every timed step
+still plans, uploads and executes one whole batch, and all K steps end inside the timed region.
+"single_stream" holds the same measurement with one batch at a time; "roofline" describes that
+one-at-a-time configuration (per-launch durations are only meaningful without overlap).
+
 Prints ONE JSON line (see the keys at the bottom of main()).
 """
 from __future__ import annotations
