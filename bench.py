@@ -122,6 +122,10 @@ def main():
         keep.append(plan)
 
     def timed_steps(n_lanes, flags):
+        for i in range(n_lanes):                      # every lane's buffers and stream are touched once,
+            iep_step(flags, lane=lanes[i])            # whatever --warmup says
+        torch.cuda.synchronize()
+        keep.clear()
         for i in range(Wm):
             iep_step(flags, lane=lanes[i % n_lanes])
         torch.cuda.synchronize()
@@ -243,7 +247,7 @@ def main():
                 dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, out=ln["out"],
                                 workspace=ln["ws"], stream=ln["stream"])
 
-            for i in range(max(Wm, MS)):
+            for i in range(MS + Wm):                  # every lane once, then the warm-up steps
                 moe_lane_step(i)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
