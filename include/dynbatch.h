@@ -278,6 +278,22 @@ int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const voi
                 const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* moe_forward for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same layer, same kernels, same results, but no
+ * workspace argument.  The routing tables and the permuted / hidden / expert-output rows live in a
+ * device array of MOE_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the
+ * library runs on holds it until the process ends).  The call allocates nothing and frees nothing.
+ *   other arguments as moe_forward (aux pointers, if given, are still the caller's memory)
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or
+ * threads) race on it; issue them on one stream or serialise them.  Nothing is kept between calls.
+ * Errors as moe_forward; DYNB_E_WORKSPACE if moe_workspace_bytes(shape) exceeds
+ * MOE_STATIC_SCRATCH_BYTES (the 4096-token, 256-expert benchmark layer needs 38 MB and fits; the
+ * 16384-token, 1024-expert one needs 607 MB and does not: use moe_forward for it).               */
+#define MOE_STATIC_SCRATCH_BYTES (48u << 20)
+int moe_forward_static(const moe_shape* shape, const void* x, const void* Wg, const void* Wn,
+                       const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
+                       void* stream);
+
 /* The unbatched comparison row of Results / Sparsely Gated Mixture of Experts (the naive version
  * there runs each of the k*b expert uses on its own, in a loop): gate, top-k, grouping and
  * permute as in moe_forward, then one expert call (both layers, same kernels, one row) per use,

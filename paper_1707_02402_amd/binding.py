@@ -25,7 +25,8 @@ ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "D
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
-           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_naive", "dynb_timing_enable",
+           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
+           "dynb_timing_enable",
            "dynb_timing_read"]
 
 
@@ -95,6 +96,7 @@ def _load():
     L.moe_forward.argtypes = [ct.POINTER(_MoeShape), ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p, ct.c_void_p,
                               ct.c_void_p, ct.c_void_p, ct.POINTER(_MoeAux), ct.c_void_p, ct.c_size_t, ct.c_void_p]
     L.moe_forward_naive.argtypes = L.moe_forward.argtypes + [ct.c_int32]
+    L.moe_forward_static.argtypes = L.moe_forward.argtypes[:9] + [ct.c_void_p]
     L.dynb_timing_enable.argtypes = [ct.c_int]
     L.dynb_timing_read.argtypes = [ct.POINTER(_StageTime), ct.c_int32, ct.POINTER(ct.c_int32)]
     return L
@@ -263,6 +265,25 @@ def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None,
 # ------------------------------------------------------------------------------------------ MoE
 def moe_workspace_bytes(T: int, d: int, h: int, E: int, k: int, dtype: int = DYNB_BF16) -> int:
     return int(lib.moe_workspace_bytes(ct.byref(_MoeShape(T, d, h, E, k, dtype))))
+
+
+MOE_STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def moe_forward_static(x, Wg, Wn, noise, W1, W2, k: int, out, aux=None, stream=None):
+    """moe_forward without a workspace: the library's built-in device array holds the scratch data and the
+    call allocates nothing, so `out` (and the aux tensors, if wanted: a namespace like moe_forward returns)
+    must be given."""
+    T, d = x.shape
+    E, h = W1.shape[0], W1.shape[1]
+    shape = _MoeShape(T, d, h, E, k, DYNB_BF16)
+    aux_c = None
+    if aux is not None:
+        aux_c = _MoeAux(*[getattr(aux, n).data_ptr() for n in
+                          ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")])
+    _check(lib.moe_forward_static(ct.byref(shape), _ptr(x), _ptr(Wg), _ptr(Wn), _ptr(noise), _ptr(W1), _ptr(W2),
+                                  _ptr(out), ct.byref(aux_c) if aux_c is not None else None, _stream(stream)))
+    return out
 
 
 def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = False, workspace=None, stream=None,

@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -692,6 +693,51 @@ extern "C" int moe_forward(const moe_shape* s, const void* x, const void* Wg, co
                            size_t workspace_bytes, void* stream)
 {
     return moe_run(s, x, Wg, Wn, noise, W1, W2, out, aux, workspace, workspace_bytes, stream, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// Entry point for callers that cannot allocate device memory.  The routing tables and the
+// xs / hid / y buffers that moe_forward keeps in its caller-provided workspace live in a device
+// array that is part of the library's code object; every GPU holds its own copy at its own address.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current GPU.  In host code the array's name is only a
+// stand-in for the symbol, so the address is asked for once per device and kept.
+static int static_scratch_ptr(void** out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void* ptr_of[MAX_DEVICES] = {};
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev), "moe_forward_static(hipGetDevice)");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(DYNB_E_UNSUPPORTED, "moe_forward_static: device ordinal beyond 63");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "moe_forward_static(hipGetSymbolAddress)");
+        if (!p) return fail(DYNB_E_HIP, "moe_forward_static: no device address for the scratch array");
+        ptr_of[dev] = p;
+    }
+    *out = ptr_of[dev];
+    return DYNB_OK;
+}
+
+extern "C" int moe_forward_static(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
+                                  const void* W1, const void* W2, void* out, const moe_aux* aux, void* stream)
+{
+    int rc = check_shape(s, "moe_forward_static");
+    if (rc != DYNB_OK) return rc;
+    const size_t need = layout(s).total;
+    if (need > size_t(MOE_STATIC_SCRATCH_BYTES))
+        return fail(DYNB_E_WORKSPACE, "moe_forward_static: this shape needs " + std::to_string(need) +
+                                          " bytes of scratch memory, the built-in array holds " +
+                                          std::to_string(size_t(MOE_STATIC_SCRATCH_BYTES)) + "; use moe_forward");
+    void* ws = nullptr;
+    rc = static_scratch_ptr(&ws);
+    if (rc != DYNB_OK) return rc;
+    // every buffer of the layout is written before it is read, and the one table that must start
+    // at zero (blockcnt) is cleared by a fill kernel inside the layer: the previous call's contents do not matter
+    return moe_run(s, x, Wg, Wn, noise, W1, W2, out, aux, ws, size_t(MOE_STATIC_SCRATCH_BYTES), stream, 0);
 }
 
 extern "C" int moe_forward_naive(const moe_shape* s, const void* x, const void* Wg, const void* Wn, const float* noise,
