@@ -64,7 +64,7 @@ def main():
     import __graft_entry__
     __graft_entry__.ensure_built()          # loads the built library; compiles only if there is none
     import paper_1707_02402_amd as dyn
-    from tests import gpu_util as U
+    from workloads import device as U
     from workloads import iep, moe
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

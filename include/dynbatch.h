@@ -166,7 +166,9 @@ size_t dynbatch_plan_device_bytes(const dynb_plan* plan);
 
 /* Copies the index lists to `dev_buf` (device, >= dynbatch_plan_device_bytes, 16-byte aligned)
  * on `stream`, once per plan.  The plan remembers dev_buf; it must stay valid and unmodified
- * while the plan is executed.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small), DYNB_E_HIP.  */
+ * while the plan is executed.  The copies read the plan's own host arrays: do not free the plan
+ * before the work enqueued on `stream` up to this call has finished.
+ * Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small), DYNB_E_HIP.                               */
 int dynbatch_plan_upload(dynb_plan* plan, void* dev_buf, size_t bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------- */
@@ -238,7 +240,7 @@ typedef struct {
     int32_t d;                /* model width                                                    */
     int32_t h;                /* hidden units per expert                                        */
     int32_t E;                /* experts (the paper's n)                                        */
-    int32_t k;                /* experts per token, 1 <= k <= min(E, 8)                         */
+    int32_t k;                /* experts per token, 1 <= k <= E                                 */
     int32_t dtype;            /* DYNB_BF16 only                                                 */
 } moe_shape;
 
@@ -272,8 +274,9 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *   workspace device, >= moe_workspace_bytes, 256-byte aligned; it holds the routing tables of the
  *             call, so nothing else may write it until the call's work on `stream` has finished
  *             (calls in flight on different streams need a workspace each)
- * T = 0 succeeds without work.  Errors: DYNB_E_INVAL (NULL, k > E, k > 8, sizes <= 0, d or h not
- * a multiple of 32), DYNB_E_WORKSPACE, DYNB_E_UNSUPPORTED (dtype), DYNB_E_HIP.                   */
+ * T = 0 succeeds without work.  Errors: DYNB_E_INVAL (NULL, k > E, sizes <= 0), DYNB_E_WORKSPACE,
+ * DYNB_E_UNSUPPORTED (dtype; d or h not a multiple of 8: rows move in 16-byte pieces; more than
+ * 2^30 expert uses), DYNB_E_HIP.  All shape errors are reported before any work is enqueued.      */
 int moe_forward(const moe_shape* shape, const void* x, const void* Wg, const void* Wn,
                 const float* noise, const void* W1, const void* W2, void* out, const moe_aux* aux,
                 void* workspace, size_t workspace_bytes, void* stream);

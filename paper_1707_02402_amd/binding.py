@@ -120,6 +120,16 @@ def _ptr(t):
     return None if t is None else ct.c_void_p(t.data_ptr())
 
 
+def _scratch(nbytes: int, device, stream):
+    """Device buffer the binding allocates on the caller's behalf.  If the work runs on another stream than
+    the current one, the allocator is told so: it must not hand the block out again before that work is done."""
+    import torch
+    t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device=device)
+    if stream is not None and stream != torch.cuda.current_stream():
+        t.record_stream(stream)
+    return t
+
+
 # ------------------------------------------------------------------------------------------ planner
 class Plan:
     """Owner of a dynb_plan*; keeps the uploaded index-list buffer alive."""
@@ -128,13 +138,18 @@ class Plan:
         self.handle = handle
         self.B = B
         self.dev_buf = None
+        self._free = lib.dynbatch_plan_free      # kept here: module globals may be gone at interpreter shutdown
+
+    def free(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h:
+            self._free(h)
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib.dynbatch_plan_free(self.handle)
-            self.handle = None
-
-    free = __del__
+        try:
+            self.free()
+        except Exception:                        # nothing useful can be done in a finalizer
+            pass
 
 
 def dynbatch_plan(prog, prog_off, arity, flags: int = DYNB_SCHED_IMPROVED) -> Plan:
@@ -191,7 +206,7 @@ def dynbatch_plan_upload(plan: Plan, dev_buf=None, stream=None):
     import torch
     n = dynbatch_plan_device_bytes(plan)
     if dev_buf is None:
-        dev_buf = torch.empty(n, dtype=torch.uint8, device="cuda")
+        dev_buf = _scratch(n, "cuda", stream)
     _check(lib.dynbatch_plan_upload(plan.handle, _ptr(dev_buf), dev_buf.numel() * dev_buf.element_size(), _stream(stream)))
     plan.dev_buf = dev_buf
     return dev_buf
@@ -252,10 +267,11 @@ def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None,
         assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32), key
     if out is None:
         out = torch.empty_like(feats)
+        if stream is not None and stream != torch.cuda.current_stream():
+            out.record_stream(stream)
     assert out.is_cuda and out.is_contiguous() and out.shape == feats.shape and out.dtype == feats.dtype
     if workspace is None:
-        workspace = torch.empty(int(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(shape))), dtype=torch.uint8,
-                                device=feats.device)
+        workspace = _scratch(lib.dynbatch_workspace_bytes(plan.handle, ct.byref(shape)), feats.device, stream)
     w = _weights_struct(weights)
     _check(lib.dynbatch_execute(plan.handle, ct.byref(shape), ct.byref(w), _ptr(feats), _ptr(out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -301,13 +317,16 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
     assert noise is None or (noise.is_cuda and noise.is_contiguous() and noise.dtype == torch.float32
                              and noise.shape == (T, E))
     shape = _MoeShape(T, d, h, E, k, DYNB_BF16)
+    side = stream is not None and stream != torch.cuda.current_stream()
     if out is None:
         out = torch.empty_like(x)
+        if side:
+            out.record_stream(stream)
     if workspace is None:
         n = int(lib.moe_workspace_bytes(ct.byref(shape)))
         if n == 0:
             _check(lib.moe_forward(ct.byref(shape), None, None, None, None, None, None, None, None, None, 0, None))
-        workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
+        workspace = _scratch(n, x.device, stream)
     aux_t, aux_c = None, None
     if want_aux:
         dev = x.device
@@ -319,6 +338,9 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
             offsets=torch.empty(E + 1, dtype=torch.int32, device=dev),
             perm=torch.empty(T * k, dtype=torch.int32, device=dev),
             inv=torch.empty(T * k, dtype=torch.int32, device=dev))
+        if side:
+            for t_ in vars(aux_t).values():
+                t_.record_stream(stream)
         aux_c = _MoeAux(*[getattr(aux_t, n).data_ptr() for n in
                           ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv")])
     args = (ct.byref(shape), _ptr(x), _ptr(Wg), _ptr(Wn), _ptr(noise), _ptr(W1), _ptr(W2), _ptr(out),

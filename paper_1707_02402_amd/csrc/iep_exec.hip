@@ -670,8 +670,7 @@ static int run_generic(const dynb_plan* p, const dynb_shape* s, const dynb_modul
         evals += l.count;
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
-        bool any_binary = false;
-        for (int i = 0; i < l.count; ++i) any_binary |= (p->arity[p->items[l.start + i].type] == 2);
+        const bool any_binary = l.any_binary != 0;
         // grid.y is limited to 65535: split very wide launch groups
         for (int off = 0; off < l.count; off += 32768) {
             GenArgs b = a;
@@ -751,8 +750,7 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         evals += l.count;
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
         a.count = l.count;
-        a.any_binary = 0;
-        for (int i = 0; i < l.count; ++i) a.any_binary |= (p->arity[p->items[l.start + i].type] == 2);
+        a.any_binary = l.any_binary;
         // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
         // workgroup up to 256 nodes, two nodes per workgroup (highest throughput per CU) beyond that
         // (with several batches in flight the narrow groups of different batches share the chip instead:

@@ -37,7 +37,7 @@ constexpr int SORT_BLOCK = 256;   // uses ranked together by one workgroup
 constexpr int TM = 64;            // rows of one grouped-GEMM tile
 constexpr int TN = 256;           // output features of one grouped-GEMM tile
 constexpr int NTW = TN / 64;      // 16-feature sub-tiles per wave (4 waves split the features)
-constexpr int MAX_K = 8;
+constexpr int MAX_K = 8;          // uses of a token whose places are kept in registers (more are looked up)
 constexpr int MG = 8;             // row tiles of one expert that walk the feature tiles together
 constexpr int XCD_CHUNK = 128;    // consecutive grouped-GEMM tiles dealt to one XCD
 
@@ -126,7 +126,9 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
 // One wave per token. Selection compares fp32 logits exactly: larger first, equal -> lower id.
 // The row is read once into registers (lane l holds experts l, l+64, ...; up to NV*64 experts) and the
 // k selection rounds run on registers with a wave-wide argmax; NV = 0 re-reads the row every round
-// (any E).
+// (any E).  Selections come out in strictly descending (value, then ascending id) order, so "already
+// taken" is simply "not below the previous selection": no list of chosen ids is kept and k may be
+// anything up to E.  A NaN logit counts as -inf.
 template <int NV>
 __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, int32_t* __restrict__ topk_idx,
                                               float* __restrict__ topk_w, int T, int E, int k)
@@ -135,60 +137,48 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const float* row = logits + size_t(t) * E;
+    auto clean = [](float v) -> float { return v != v ? -INFINITY : v; };
     float reg[NV > 0 ? NV : 1];
-    uint32_t taken = 0;                      // bit i: this lane's i-th value was already selected
     if (NV > 0) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int e = lane + 64 * i;
-            reg[i] = e < E ? row[e] : 0.f;
+            reg[i] = e < E ? clean(row[e]) : 0.f;
         }
     }
-    int chosen[MAX_K];
-    float val[MAX_K];
+    constexpr int NONE = 0x7fffffff;
+    float last_v = INFINITY, v0 = 0.f, den = 0.f;
+    int last_e = -1;
+    int32_t* idx_t = topk_idx + size_t(t) * k;
+    float* w_t = topk_w + size_t(t) * k;
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY;
+        int bi = NONE;
+        auto offer = [&](float v, int e) {
+            const bool open = v < last_v || (v == last_v && e > last_e);       // below the previous selection
+            if (open && (v > bv || bi == NONE)) { bv = v; bi = e; }
+        };
+        if (NV > 0) {
 #pragma unroll
-    for (int j = 0; j < MAX_K; ++j) { chosen[j] = -1; val[j] = 0.f; }
-#pragma unroll
-    for (int j = 0; j < MAX_K; ++j) {
-        if (j < k) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;
-            if (NV > 0) {
-#pragma unroll
-                for (int i = 0; i < NV; ++i) {
-                    const int e = lane + 64 * i;
-                    const float v = reg[i];
-                    if (e < E && !((taken >> i) & 1u) && (v > bv || bi == 0x7fffffff)) { bv = v; bi = e; }
-                }
-            } else {
-                for (int e = lane; e < E; e += 64) {
-                    bool was = false;
-#pragma unroll
-                    for (int q = 0; q < MAX_K; ++q) was |= (q < j && chosen[q] == e);
-                    const float v = row[e];
-                    if (!was && (v > bv || bi == 0x7fffffff)) { bv = v; bi = e; }
-                }
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oi = __shfl_xor(bi, off);
-                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
-            }
-            chosen[j] = bi;
-            val[j] = bv;
-            if (NV > 0 && (bi & 63) == lane) taken |= 1u << (bi >> 6);
+            for (int i = 0; i < NV; ++i)
+                if (lane + 64 * i < E) offer(reg[i], lane + 64 * i);
+        } else {
+            for (int e = lane; e < E; e += 64) offer(clean(row[e]), e);
         }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            if (oi != NONE && (bi == NONE || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+        }
+        // k <= E: a candidate always exists.  The selection is uniform over the wave.
+        last_v = bv;
+        last_e = bi;
+        if (j == 0) v0 = bv;
+        den += expf(bv - v0);
+        if ((j & 63) == lane) { idx_t[j] = bi; w_t[j] = bv; }                  // raw logit until den is complete
     }
-    float den = 0.f;
-#pragma unroll
-    for (int j = 0; j < MAX_K; ++j) if (j < k) den += expf(val[j] - val[0]);
-#pragma unroll
-    for (int j = 0; j < MAX_K; ++j)
-        if (j < k && lane == j) {
-            topk_idx[size_t(t) * k + j] = chosen[j];
-            topk_w[size_t(t) * k + j] = expf(val[j] - val[0]) / den;
-        }
+    for (int j = lane; j < k; j += 64) w_t[j] = expf(w_t[j] - v0) / den;       // each lane revisits its own stores
 }
 
 // ------------------------------------------------------------------------------------------ grouping
@@ -282,15 +272,17 @@ __global__ __launch_bounds__(SORT_BLOCK) void k_place(const int32_t* __restrict_
 // xs[inv[t*k + j]] = x[t] for j < k: one wave per token reads the row once and scatters it to the
 // token's k places in the expert-sorted order (reading by sorted position instead would fetch every
 // token row k times, since a token's uses sit in k different groups).  d is a multiple of 8.
+// The first MAX_K places sit in registers; a token with more uses looks the others up as it goes.
 __global__ __launch_bounds__(256) void k_permute(const bf16_t* __restrict__ x, const int32_t* __restrict__ inv,
                                                  bf16_t* __restrict__ xs, int T, int d, int k)
 {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
+    const int32_t* inv_t = inv + size_t(t) * k;
     int pos[MAX_K];
 #pragma unroll
-    for (int j = 0; j < MAX_K; ++j) pos[j] = j < k ? inv[size_t(t) * k + j] : 0;
+    for (int j = 0; j < MAX_K; ++j) pos[j] = j < k ? inv_t[j] : 0;
     const u32x4* src = reinterpret_cast<const u32x4*>(x + size_t(t) * d);
     for (int c0 = 0; c0 < d / 8; c0 += 256) {
         u32x4 v[4];
@@ -299,16 +291,18 @@ __global__ __launch_bounds__(256) void k_permute(const bf16_t* __restrict__ x, c
             const int c = c0 + i * 64 + lane;
             if (c < d / 8) v[i] = src[c];
         }
+        auto put = [&](int p) {
+            u32x4* dst = reinterpret_cast<u32x4*>(xs + size_t(p) * d);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = c0 + i * 64 + lane;
+                if (c < d / 8) dst[c] = v[i];
+            }
+        };
 #pragma unroll
         for (int j = 0; j < MAX_K; ++j)
-            if (j < k) {
-                u32x4* dst = reinterpret_cast<u32x4*>(xs + size_t(pos[j]) * d);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int c = c0 + i * 64 + lane;
-                    if (c < d / 8) dst[c] = v[i];
-                }
-            }
+            if (j < k) put(pos[j]);
+        for (int j = MAX_K; j < k; ++j) put(inv_t[j]);
     }
 }
 
@@ -319,26 +313,30 @@ __global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, c
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
+    const int32_t* inv_t = inv + size_t(t) * k;
+    const float* w_t = topk_w + size_t(t) * k;
     int pos[MAX_K];
     float w[MAX_K];
 #pragma unroll
     for (int j = 0; j < MAX_K; ++j)
-        if (j < k) { pos[j] = inv[size_t(t) * k + j]; w[j] = topk_w[size_t(t) * k + j]; }
+        if (j < k) { pos[j] = inv_t[j]; w[j] = w_t[j]; }
     for (int c = lane; c < d / 8; c += 64) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        auto add = [&](int p, float wj) {                  // j ascending: the summation order is fixed
+            const u32x4 v = reinterpret_cast<const u32x4*>(y + size_t(p) * d)[c];
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[2 * i] += wj * __uint_as_float(u[i] << 16);
+                acc[2 * i + 1] += wj * __uint_as_float(u[i] & 0xffff0000u);
+            }
+        };
 #pragma unroll
         for (int j = 0; j < MAX_K; ++j)
-            if (j < k) {
-                const u32x4 v = reinterpret_cast<const u32x4*>(y + size_t(pos[j]) * d)[c];
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] += w[j] * __uint_as_float(u[i] << 16);
-                    acc[2 * i + 1] += w[j] * __uint_as_float(u[i] & 0xffff0000u);
-                }
-            }
+            if (j < k) add(pos[j], w[j]);
+        for (int j = MAX_K; j < k; ++j) add(inv_t[j], w_t[j]);
         u32x4 o;
         o.x = pack_bf16x2(acc[0], acc[1]);
         o.y = pack_bf16x2(acc[2], acc[3]);
@@ -381,7 +379,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
     for (int i = 0; i < XPASS; ++i) xsrc[i] = in + size_t(row0 + min(prow + i * RPP, rows - 1)) * K + part * 8;
     u32x4 wreg[WPASS], xreg[XPASS];
     auto fetch = [&](int kc) {
-        const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 32: the last chunk may be partly empty
+        const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 8: the last chunk may be partly empty
 #pragma unroll
         for (int i = 0; i < WPASS; ++i)
             wreg[i] = inside ? *reinterpret_cast<const u32x4*>(wsrc[i] + kc * KC) : u32x4{0u, 0u, 0u, 0u};
@@ -489,7 +487,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
 // One workgroup = one (row tile of <= 64 rows inside one group, 256 output features) pair; a group's
 // tiles are found from tile_start (prefix sum of ceil(count/64)), so ragged and empty groups cost
 // nothing beyond their real rows.  4 waves split the 256 features; only the live 16-row sub-tiles
-// are multiplied.  N must be a multiple of 4 (it is: d and h are multiples of 32).
+// are multiplied.  N must be a multiple of 4 (it is: d and h are multiples of 8).
 template <bool RELU>
 __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ offsets,
@@ -569,11 +567,15 @@ int check_shape(const moe_shape* s, const char* who)
     if (s->T < 0 || s->d <= 0 || s->h <= 0 || s->E <= 0 || s->k <= 0)
         return fail(DYNB_E_INVAL, std::string(who) + ": sizes must be positive");
     if (s->k > s->E) return fail(DYNB_E_INVAL, std::string(who) + ": k > E");
-    if (s->k > MAX_K) return fail(DYNB_E_INVAL, std::string(who) + ": k > 8");
-    if (s->d % 32 || s->h % 32) return fail(DYNB_E_INVAL, std::string(who) + ": d and h must be multiples of 32");
+    if (s->d % 8 || s->h % 8)
+        return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": d and h must be multiples of 8 (rows are moved in 16-byte pieces)");
     if (s->dtype != DYNB_BF16) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": only bf16");
     if (size_t(s->T) * size_t(s->k) >= (size_t(1) << 30) || size_t(s->T) * size_t(s->E) >= (size_t(1) << 40))
         return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": too many expert uses");
+    // the grouped expert layers launch one workgroup per (row tile, feature tile): at most ceil(A/TM) + E row tiles
+    const long long max_mtiles = ((long long)s->T * s->k + TM - 1) / TM + s->E;
+    const long long nt = (std::max(s->h, s->d) + TN - 1) / TN;
+    if (max_mtiles * nt + 8ll * XCD_CHUNK >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": grid too large");
     return DYNB_OK;
 }
 
@@ -653,7 +655,6 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
     const int nt1 = (h + TN - 1) / TN, nt2 = (d + TN - 1) / TN;
-    if (max_mtiles * std::max(nt1, nt2) + 8ll * XCD_CHUNK >= (1ll << 31)) return fail(DYNB_E_UNSUPPORTED, "moe_forward: grid too large");
     if (naive_stride <= 0) {
         const long long span = 8ll * XCD_CHUNK;
         hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles * nt1 + span - 1) / span * span)), dim3(256), 0, st,

@@ -19,8 +19,9 @@ struct dynb_item {
 };
 
 struct dynb_launch {
-    int32_t start;  // first item
+    int32_t start;       // first item
     int32_t count;
+    int32_t any_binary;  // some item of the group is a two-argument function (the kernels take the conv1x1 path)
 };
 
 struct dynb_plan {

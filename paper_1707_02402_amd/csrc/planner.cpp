@@ -279,7 +279,7 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
                 // slots of arguments consumed by the previous group may be reused from here on
                 free_slots.insert(free_slots.end(), release.begin(), release.end());
                 release.clear();
-                p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0});
+                p->launches.push_back(dynb_launch{int32_t(p->items.size()), 0, 0});
                 cur = p->node_launch[n];
             }
             const bool is_root = (n == p->root[example[n]]);
@@ -302,6 +302,7 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
             it.dst = is_root ? -1 - example[n] : slot[n];
             it.type = p->type[n];
             ++p->launches.back().count;
+            if (arity[it.type] == 2) p->launches.back().any_binary = 1;
             p->items.push_back(it);
         }
         p->n_slots = pingpong ? 2 * maxw : running;

@@ -19,3 +19,23 @@ def oracle():
     import oracle as o
     o.build()
     return o
+
+
+class _RefCache:
+    """Oracle results of the full-size program-tree configurations, computed once per session
+    (config 2 takes about 10 s on the 16 host cores of a GPU machine)."""
+
+    def __init__(self, oracle):
+        self.oracle = oracle
+        self.items = {}
+
+    def get(self, key, make):
+        if key not in self.items:
+            w = make()
+            self.items[key] = (w, self.oracle.iep_forward_workload(w))
+        return self.items[key]
+
+
+@pytest.fixture(scope="session")
+def full_refs(oracle):
+    return _RefCache(oracle)

@@ -60,7 +60,7 @@ def test_mfma_path_small_batch_every_element(dyn, util, oracle, flags):
 
 
 def test_mfma_path_wide_level_uses_two_nodes_per_workgroup(dyn, util, oracle):
-    """More than 512 nodes in one launch group selects the two-node kernel; sampled examples vs oracle."""
+    """More than 256 nodes in one launch group selects the two-node kernel; sampled examples vs oracle."""
     w = iep.small_mixed(seed=5, B=701, C=128, H=14, W=14, dtype="bf16", min_len=2, max_len=4)
     v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
     assert v.max_launch_nodes > 512 and v.max_launch_nodes % 2 == 1
@@ -96,28 +96,36 @@ def test_identity_kernels_are_exact_on_the_mfma_path(dyn, util):
         assert (got[i] == scale * f[i]).all(), i
 
 
-def test_config1_balanced_trees_sampled(dyn, util, oracle):
-    w = iep.config1()
+def lane_batch(lane: int):
+    """Batch of lane `lane` of the benchmark: config 2 itself for lane 0, further batches of the same recipe
+    (own programs and feature maps, the same 40 modules) for the others."""
+    base = iep.config2.__defaults__[0]
+    return iep.config2() if lane == 0 else iep.config2(seed=base + 1000 * lane, weight_seed=base)
+
+
+def assert_every_example(util, got, ref, tol, what=""):
+    errs = np.array([util.normwise(got[i], ref[i]) for i in range(len(ref))])
+    assert errs.max() < tol, (what, int(errs.argmax()), float(errs.max()))
+    return errs
+
+
+def test_config1_balanced_trees_every_example(dyn, util, full_refs):
+    w, ref = full_refs.get("config1", iep.config1)
     v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
     assert v.n_levels == 5 and v.n_launches == 4 and v.n_compute_nodes == 960
     got = util.iep_run(dyn, w)
-    sample = [0, 31, 63]
-    ref = oracle.iep_forward_workload(w.subset(sample))
-    for j, i in enumerate(sample):
-        assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
+    assert_every_example(util, got, ref, TOL["bf16"], "config1")                # all 64 examples
     again = util.iep_run(dyn, w)
     assert (again == got).all()                  # deterministic
     assert np.isfinite(got).all() and (got >= 0).all()
+    assert (util.iep_run(dyn, w, dyn.DYNB_PLAN_THROUGHPUT) == got).all()        # the other kernel layout: same bits
 
 
-def test_config2_iep_shaped_sampled(dyn, util, oracle):
-    w = iep.config2()
+def test_config2_iep_shaped_every_example(dyn, util, full_refs):
+    w, ref = full_refs.get("config2", iep.config2)
     got = util.iep_run(dyn, w)
-    lens = np.diff(w.prog_off)
-    sample = [int(np.argmax(lens)), int(np.argmin(lens)), 7, 128, 255]
-    ref = oracle.iep_forward_workload(w.subset(sample))
-    for j, i in enumerate(sample):
-        assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
+    errs = assert_every_example(util, got, ref, TOL["bf16"], "config2")         # all 256 examples
+    print(f"config 2: per-example error max {errs.max():.2e} median {np.median(errs):.2e}")
     # batched (improved sort) == standard sort == per-example loop, bit for bit, on a subset
     sub = w.subset(range(0, 256, 16))
     a = util.iep_run(dyn, sub, 0)
@@ -128,36 +136,38 @@ def test_config2_iep_shaped_sampled(dyn, util, oracle):
     assert np.isfinite(got).all() and (got >= 0).all()
 
 
-def test_config2_in_the_benchmarks_launch_configuration(dyn, util, oracle):
-    """Full config 2 as bench.py times it: balanced + throughput plan, prepared weights, four batches in flight
-    on four streams; sampled examples of every lane against the oracle."""
+def test_config2_in_the_benchmarks_launch_configurations(dyn, util, full_refs):
+    """Full config 2 as bench.py times it, every example of every batch against the oracle:
+    (a) one batch at a time: balanced plan, prepared weights, latency layouts;
+    (b) four different batches in flight on four streams: balanced + throughput plan, own workspaces."""
     import torch
-    w = iep.config2()
+    w, ref = full_refs.get("config2", iep.config2)
     weights = util.iep_weights_dev(w)
     weights["packed"] = dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16)
-    feats = util.to_dev(w.feats, "bf16")
+    got = util.iep_run(dyn, w, dyn.DYNB_SCHED_IMPROVED | dyn.DYNB_PLAN_BALANCE, weights=weights)
+    assert_every_example(util, got, ref, TOL["bf16"], "config2, one batch at a time")
     flags = dyn.DYNB_SCHED_IMPROVED | dyn.DYNB_PLAN_BALANCE | dyn.DYNB_PLAN_THROUGHPUT
+    batches = [full_refs.get("config2" if i == 0 else f"config2-lane{i}", lambda i=i: lane_batch(i)) for i in range(4)]
+    for i in range(1, 4):
+        assert (batches[i][0].w3a == w.w3a).all() and not (batches[i][0].feats == w.feats).all()
     torch.cuda.synchronize()
     lanes = []
-    for _ in range(4):
-        plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags)
-        lanes.append(dict(stream=torch.cuda.Stream(), plan=plan, out=torch.empty_like(feats),
+    for wl, _ in batches:
+        plan = dyn.dynbatch_plan(wl.prog, wl.prog_off, wl.arity, flags)
+        feats = util.to_dev(wl.feats, "bf16")
+        lanes.append(dict(stream=torch.cuda.Stream(), plan=plan, feats=feats, out=torch.empty_like(feats),
                           ws=torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16),
                                          dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
     for step in range(8):
         ln = lanes[step % 4]
         if step < 4:
             dyn.dynbatch_plan_upload(ln["plan"], stream=ln["stream"])
-        dyn.dynbatch_execute(ln["plan"], weights, feats, ln["out"], ln["ws"], stream=ln["stream"])
+        dyn.dynbatch_execute(ln["plan"], weights, ln["feats"], ln["out"], ln["ws"], stream=ln["stream"])
     torch.cuda.synchronize()
-    lens = np.diff(w.prog_off)
-    sample = [int(np.argmax(lens)), 3, 200]
-    ref = oracle.iep_forward_workload(w.subset(sample))
-    for ln in lanes:
-        got = util.to_host(ln["out"])
-        for j, i in enumerate(sample):
-            assert util.normwise(got[i], ref[j]) < TOL["bf16"], (i, util.normwise(got[i], ref[j]))
-        assert torch.equal(ln["out"], lanes[0]["out"])
+    for i, (ln, (wl, r)) in enumerate(zip(lanes, batches)):
+        assert_every_example(util, util.to_host(ln["out"]), r, TOL["bf16"], f"lane {i}")
+    assert torch.equal(lanes[0]["out"], util.to_dev(got, "bf16"))               # lane 0 ran config 2 itself
 
 
 def test_execute_error_paths(dyn, util):

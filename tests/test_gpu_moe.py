@@ -38,6 +38,14 @@ def stack(m):
     return W1, W2
 
 
+def oracle_experts(oracle, m, r, W1, W2):
+    """Expert + combine stage of the oracle on a given routing (token by token above its 64-use buffer)."""
+    if m.k <= 64:
+        return oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)
+    return np.stack([oracle.moe_token(m.x[t], r.topk_w[t], [W1[e] for e in r.topk_idx[t]], [W2[e] for e in r.topk_idx[t]])
+                     for t in range(m.T)])
+
+
 def check_routing(oracle, m, aux):
     r = oracle.moe_route(aux["logits"], m.k)
     for name in ("topk_idx", "counts", "offsets", "perm", "inv"):
@@ -49,7 +57,11 @@ def check_routing(oracle, m, aux):
 
 @pytest.mark.parametrize("T,d,h,E,k,empty", [(300, 64, 96, 20, 3, 0.2), (257, 32, 32, 5, 5, 0.0), (1000, 128, 160, 70, 1, 0.1),
                                               (64, 96, 64, 300, 8, 0.5), (1, 32, 32, 2, 2, 0.0),
-                                              (24, 32, 32, 2100, 3, 0.0)])
+                                              (24, 32, 32, 2100, 3, 0.0),
+                                              (200, 64, 96, 64, 16, 0.0),      # k beyond the register-held uses
+                                              (50, 32, 32, 12, 12, 0.0),       # k = E > 8: full softmax
+                                              (90, 40, 72, 12, 3, 0.0),        # d, h multiples of 8 only
+                                              (70, 64, 64, 200, 70, 0.0)])     # k > 64: several selections per lane
 def test_small_layers_every_element(dyn, util, oracle, T, d, h, E, k, empty):
     m = moe.small(seed=T + E, T=T, d=d, h=h, E=E, k=k, empty_frac=empty)
     W1, W2 = stack(m)
@@ -58,8 +70,10 @@ def test_small_layers_every_element(dyn, util, oracle, T, d, h, E, k, empty):
     assert util.normwise(aux["logits"], ref_logits) < LOGIT_TOL                      # (i)
     r = check_routing(oracle, m, aux)                                                # (ii)
     assert (r.counts[m.empty] == 0).all()
-    ref = oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)                       # (iii)
+    ref = oracle_experts(oracle, m, r, W1, W2)                                        # (iii)
     assert util.normwise(out, ref) < OUT_TOL
+    if k > 64:
+        return
     # (iv) end to end: tokens with a clear margin between the k-th and (k+1)-th logit must route identically
     e2e = oracle.moe_forward(m.x, m.Wg, m.Wn, m.noise, W1, W2, k)
     if k < E:
@@ -86,7 +100,8 @@ def test_noiseless_gate_and_ties(dyn, util, oracle):
     assert util.normwise(out, oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)) < OUT_TOL
 
 
-def sampled_layer_check(dyn, util, oracle, m, n_sample):
+def full_layer(dyn, util, m):
+    """Runs a benchmark-size layer with per-expert generated weights; returns (out, aux, device inputs)."""
     import torch
     W1b = np.empty((m.E, m.h, m.d), np.uint16)
     W2b = np.empty((m.E, m.d, m.h), np.uint16)
@@ -94,36 +109,89 @@ def sampled_layer_check(dyn, util, oracle, m, n_sample):
     dev = util.moe_inputs_dev(m, np.zeros((1, 1, 1), np.float32), np.zeros((1, 1, 1), np.float32))
     dev["W1"] = torch.from_numpy(W1b.view(np.int16)).cuda().view(torch.bfloat16)
     dev["W2"] = torch.from_numpy(W2b.view(np.int16)).cuda().view(torch.bfloat16)
-    del W1b, W2b
     out, aux = util.moe_run(dyn, m, dev=dev)
-    rows = np.random.default_rng(0).choice(m.T, n_sample, replace=False)
-    ref_logits = oracle.moe_logits(m.x[rows], m.Wg, m.Wn, m.noise[rows])
-    assert util.normwise(aux["logits"][rows], ref_logits) < LOGIT_TOL                # (i) sampled rows
-    r = check_routing(oracle, m, aux)                                                # (ii) whole layer
-    assert (r.counts[m.empty] == 0).all() and r.counts.sum() == m.A
-    assert (np.sort(aux["perm"]) == np.arange(m.A)).all()
-    for t in rows[:max(8, n_sample // 4)]:                                           # (iii) sampled tokens
-        ws = [m.expert_weights(int(e)) for e in r.topk_idx[t]]
-        ref = oracle.moe_token(m.x[t], r.topk_w[t], [a for a, _ in ws], [b for _, b in ws])
-        assert util.normwise(out[t], ref) < OUT_TOL, t
     out2, aux2 = util.moe_run(dyn, m, dev=dev)
     assert (out2 == out).all() and (aux2["perm"] == aux["perm"]).all()               # deterministic
-    return r
+    return out, aux, dev, (W1b, W2b)
 
 
-def test_config3_sampled(dyn, util, oracle):
+def per_token_errors(got, ref):
+    """max |got - ref| / max |ref| of every token's output row."""
+    den = np.abs(ref).max(axis=1)
+    return np.abs(got - ref).max(axis=1) / np.where(den > 0, den, 1.0)
+
+
+def test_config3_every_token(dyn, util, oracle):
+    from workloads.rng import bf16_to_f32
     m = moe.config3()
-    r = sampled_layer_check(dyn, util, oracle, m, 64)
+    out, aux, dev, (W1b, W2b) = full_layer(dyn, util, m)
+    ref_logits = oracle.moe_logits(m.x, m.Wg, m.Wn, m.noise)                         # (i) every logit
+    assert util.normwise(aux["logits"], ref_logits) < LOGIT_TOL
+    r = check_routing(oracle, m, aux)                                                # (ii) whole layer
+    assert (r.counts[m.empty] == 0).all() and r.counts.sum() == m.A
+    ref = oracle.moe_experts(m.x, r.topk_idx, r.topk_w, bf16_to_f32(W1b), bf16_to_f32(W2b))   # (iii) every token
+    errs = per_token_errors(out, ref)
+    assert errs.max() < OUT_TOL, (int(errs.argmax()), float(errs.max()))
+    print(f"config 3: per-token error max {errs.max():.2e} median {np.median(errs):.2e}")
     load = np.sort(r.counts)[::-1].astype(np.float64)
     ok = load >= 8
     slope = np.polyfit(np.log(np.arange(1, m.E + 1)[ok]), np.log(load[ok]), 1)[0]
     assert abs(slope + 1.1) < 0.15
 
 
-def test_config4_sampled_with_empty_experts(dyn, util, oracle):
+def config4_token_sample(r, k, min_tokens=512):
+    """Tokens of config 4 whose output rows together touch every tile shape of the grouped expert layers:
+    every use of 48 experts with fewer than 16 rows (one live 16-row sub-tile), of four experts with 17..63
+    rows (two or four sub-tiles, ragged), and of the largest expert the first, a middle and the last 64-row
+    tile (every fourth row plus the tile's first and last row); filled up with seeded random tokens."""
+    counts, offsets, perm = r.counts, r.offsets, r.perm
+    g = np.random.default_rng(4)
+    pos = []
+    tail = np.flatnonzero((counts > 0) & (counts < 16))
+    tail = g.choice(tail, 48, replace=False)
+    mid = np.flatnonzero((counts >= 17) & (counts <= 63))
+    mid = np.concatenate([g.choice(mid[counts[mid] <= 32], 2, replace=False), g.choice(mid[counts[mid] > 32], 2, replace=False)])
+    for e in np.concatenate([tail, mid]):
+        pos += list(range(offsets[e], offsets[e + 1]))
+    head = int(counts.argmax())
+    n_tiles = (counts[head] + 63) // 64
+    for tile in (0, n_tiles // 2, n_tiles - 1):
+        lo = offsets[head] + 64 * tile
+        hi = min(lo + 64, offsets[head + 1])
+        pos += sorted(set(range(lo, hi, 4)) | {lo, hi - 1})
+    tokens = set(int(perm[p]) // k for p in pos)
+    T = len(r.topk_idx)
+    while len(tokens) < min_tokens:
+        tokens.add(int(g.integers(T)))
+    return np.array(sorted(tokens)), dict(tail=tail, mid=mid, head=head, n_tiles=int(n_tiles))
+
+
+def test_config4_targeted_tokens_with_empty_experts(dyn, util, oracle):
+    from concurrent.futures import ThreadPoolExecutor
     m = moe.config4()
-    r = sampled_layer_check(dyn, util, oracle, m, 32)
+    out, aux, dev, (W1b, W2b) = full_layer(dyn, util, m)
+    del W1b, W2b
+    r = check_routing(oracle, m, aux)                                                # (ii) whole layer, bit-exact
+    assert (r.counts[m.empty] == 0).all() and r.counts.sum() == m.A
+    assert (np.sort(aux["perm"]) == np.arange(m.A)).all()
     assert (r.counts == 0).sum() >= 51 and len(m.empty) == 51
+    tokens, info = config4_token_sample(r, m.k)
+    assert len(tokens) >= 512 and len(info["tail"]) == 48 and info["n_tiles"] > 100
+    ref_logits = oracle.moe_logits(m.x[tokens], m.Wg, m.Wn, m.noise[tokens])         # (i) the sampled rows
+    assert util.normwise(aux["logits"][tokens], ref_logits) < LOGIT_TOL
+    experts = np.unique(r.topk_idx[tokens])
+    with ThreadPoolExecutor(16) as ex:                                               # weights regenerated per expert
+        packs = dict(zip(experts.tolist(), ex.map(lambda e: m.expert_weights(int(e)), experts)))
+
+    def one(t):
+        es = [int(e) for e in r.topk_idx[t]]
+        return oracle.moe_token(m.x[t], r.topk_w[t], [packs[e][0] for e in es], [packs[e][1] for e in es])
+
+    with ThreadPoolExecutor(16) as ex:                                               # (iii) token by token
+        ref = np.stack(list(ex.map(one, tokens)))
+    errs = per_token_errors(out[tokens], ref)
+    assert errs.max() < OUT_TOL, (int(tokens[errs.argmax()]), float(errs.max()))
+    print(f"config 4: {len(tokens)} tokens through {len(experts)} experts, per-token error max {errs.max():.2e}")
 
 
 def test_naive_per_use_loop_equals_batched_layer(dyn, util):

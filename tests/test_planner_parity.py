@@ -178,7 +178,7 @@ def test_library_exports_every_declared_symbol():
 def test_moe_shape_checks_need_no_gpu(dyn):
     from paper_1707_02402_amd.binding import _MoeShape, lib
     assert dyn.moe_workspace_bytes(64, 64, 64, 8, 2) > 0
-    for bad in ((64, 64, 64, 8, 9), (64, 64, 64, 4, 5), (64, 48, 64, 8, 2), (64, 64, 0, 8, 2)):
+    for bad in ((64, 64, 64, 8, 9), (64, 64, 64, 4, 5), (64, 44, 64, 8, 2), (64, 64, 0, 8, 2)):
         assert dyn.moe_workspace_bytes(*bad) == 0
     # T = 0 succeeds without touching any pointer
     assert lib.moe_forward(ct.byref(_MoeShape(0, 64, 64, 8, 2, 1)), None, None, None, None, None, None, None, None,

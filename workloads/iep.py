@@ -108,10 +108,10 @@ def make_feats(seed: int, B: int, H: int, W: int, C: int, dtype: str) -> np.ndar
     return round_bf16(f) if dtype == "bf16" else f
 
 
-def _assemble(name, seed, dtype, arity, progs, C, H, W, meta=None) -> IepWorkload:
+def _assemble(name, seed, dtype, arity, progs, C, H, W, meta=None, weight_seed=None) -> IepWorkload:
     prog, off = _pack(progs)
     feats = make_feats(seed, len(progs), H, W, C, dtype)
-    w = make_weights(seed, arity, C, dtype)
+    w = make_weights(seed if weight_seed is None else weight_seed, arity, C, dtype)
     return IepWorkload(name, dtype, arity, prog, off, C, H, W, feats, *w, meta=meta or {})
 
 
@@ -200,8 +200,9 @@ def chain_like_program(g: np.random.Generator, length: int, unary, binary,
 
 def config2(seed: int = BASE_SEED * 10 + 2, B: int = 256, C: int = 128, H: int = 14, W: int = 14,
             n_unary: int = 30, n_binary: int = 10, min_len: int = 10, max_len: int = 30,
-            dtype: str = "bf16") -> IepWorkload:
-    """IEP-shaped engine: 40 module types, program length U{10..30}, mostly chains."""
+            dtype: str = "bf16", weight_seed=None) -> IepWorkload:
+    """IEP-shaped engine: 40 module types, program length U{10..30}, mostly chains.
+    weight_seed: draw the module weights from another seed's stream (several batches for one set of modules)."""
     arity = np.array([0] + [1] * n_unary + [2] * n_binary, np.uint8)
     unary = list(range(1, n_unary + 1))
     binary = list(range(n_unary + 1, n_unary + n_binary + 1))
@@ -210,7 +211,7 @@ def config2(seed: int = BASE_SEED * 10 + 2, B: int = 256, C: int = 128, H: int =
     for _ in range(B):
         length = int(g.integers(min_len, max_len + 1))
         progs.append(chain_like_program(g, length, unary, binary))
-    return _assemble("cfg2-iep-bf16", seed, dtype, arity, progs, C, H, W)
+    return _assemble("cfg2-iep-bf16", seed, dtype, arity, progs, C, H, W, weight_seed=weight_seed)
 
 
 def small_mixed(seed: int, B: int, C: int, H: int, W: int, dtype: str, n_unary: int = 3, n_binary: int = 2,
