@@ -78,7 +78,19 @@ enum {
      * node per workgroup, two workgroups sharing a CU) instead of spreading narrow launch groups
      * over idle CUs; kernels of the batches in flight fill the chip together.  Results are
      * bit-identical either way.                                                                 */
-    DYNB_PLAN_THROUGHPUT = 8
+    DYNB_PLAN_THROUGHPUT = 8,
+    /* Optional, any scheduling mode but DYNB_SCHED_NAIVE (ignored there): dynbatch_execute issues ONE
+     * launch for the whole minibatch instead of one per label (Results / IEP expects the stacking and
+     * calling overhead to be reducible further).  Resident workgroups claim units of work (a node, or the
+     * upper / lower half of a node for labels that would leave half of the chip idle) in the plan's
+     * execution order from one device counter and wait, with a bounded spin, until the arguments'
+     * results have been published; a label no longer ends with the whole chip draining.  Arguments
+     * always precede their consumer in the claim order and a claimed unit belongs to a workgroup that
+     * is already running, so the waits always end.  Implies the grouping of DYNB_PLAN_BALANCE; every
+     * node gets a result slot of its own (larger workspace).  Only the fast path (bf16, C = 128,
+     * 14 x 14) has this kernel; other shapes run one launch per label as usual.  Results are
+     * bit-identical either way.  See dynbatch_execute_check for the bounded waits.                 */
+    DYNB_PLAN_PERSISTENT = 16
 };
 
 const char* dynb_last_error(void);
@@ -120,6 +132,11 @@ typedef struct {
     const int32_t* in1;          /* [n_nodes]                                                   */
     const int32_t* out;          /* [n_nodes]                                                   */
     const int32_t* node_launch;  /* [n_nodes] launch group that executes the node, -1 for SCENE   */
+    const int32_t* item_node;    /* [n_compute_nodes] node evaluated by every work item, in execution
+                                    order                                                        */
+    int32_t n_tickets;           /* DYNB_PLAN_PERSISTENT: units of work of the single launch, else 0 */
+    const int32_t* tickets;      /* [n_tickets] in claim order: 4 * item + part; part 0 = the whole
+                                    node, 1 / 2 = its upper / lower half                         */
 } dynb_plan_view;
 
 /* Builds the plan for a minibatch of programs (Background / Visual Reasoning Programs: the fixed
@@ -231,6 +248,18 @@ int dynbatch_execute(const dynb_plan* plan, const dynb_shape* shape, const dynb_
                      const void* feats, void* out, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* After a dynbatch_execute of a DYNB_PLAN_PERSISTENT plan on the fast path: waits for `stream`,
+ * then reads the status word that call left in `workspace`.  DYNB_OK; DYNB_E_HIP if a workgroup's
+ * bounded wait for an argument expired (the kernel then drains without computing and `out` is
+ * invalid: with a correct plan this means the device was not making progress); DYNB_E_INVAL for
+ * NULL arguments or a plan that is not DYNB_PLAN_PERSISTENT.                                     */
+int dynbatch_execute_check(const dynb_plan* plan, const dynb_shape* shape, const void* workspace, void* stream);
+
+/* Polls a workgroup makes before it gives up waiting for an argument (default 1 << 22, about a
+ * second); 0 makes a workgroup give up at once if an argument is not ready.  Process-wide; for tests
+ * of the error path.  Returns the previous value.                                               */
+int32_t dynb_set_spin_limit(int32_t polls);
+
 /* ------------------------------------------------------------------------------------------- */
 /* Mixture of experts                                                                            */
 /* ------------------------------------------------------------------------------------------- */
@@ -337,6 +366,24 @@ int dynb_timing_enable(int on);
  *   n_out     host, receives the number of stages of the call (may exceed capacity)
  * Errors: DYNB_E_INVAL, DYNB_E_HIP.                                                             */
 int dynb_timing_read(dynb_stage_time* out, int32_t capacity, int32_t* n_out);
+
+/* ------------------------------------------------------------------------------------------- */
+/* Measurement helpers: what the card sustains, from the simplest possible kernels.  Not part of */
+/* the method; a benchmark reports these next to the published peaks and times them itself       */
+/* (events on `stream`).                                                                         */
+/* ------------------------------------------------------------------------------------------- */
+
+/* Enqueues a register-only loop of independent 32x32x16 bf16 MFMAs: `workgroups` workgroups of four
+ * waves, `iters` x 8 MFMAs per wave, no memory traffic.
+ *   sink   device, one float (written only if an impossible sum comes out: keeps the loop alive)
+ *   flops  host, receives the flop count of the launch (2 * 32 * 32 * 16 per MFMA)
+ * Errors: DYNB_E_INVAL, DYNB_E_HIP.                                                             */
+int dynb_probe_mfma_bf16(int32_t iters, int32_t workgroups, float* sink, void* stream, double* flops);
+
+/* Enqueues a plain copy kernel (16-byte loads and stores, grid-stride): `bytes` read + `bytes`
+ * written.  dst, src device, 16-byte aligned, not overlapping; bytes a multiple of 16.
+ * Errors: DYNB_E_INVAL, DYNB_E_HIP.                                                             */
+int dynb_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

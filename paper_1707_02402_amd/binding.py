@@ -19,14 +19,15 @@ DYNB_F32, DYNB_BF16 = 0, 1
 DYNB_SCHED_IMPROVED, DYNB_SCHED_STANDARD, DYNB_SCHED_NAIVE, DYNB_SCHED_DEPTH = 0, 1, 2, 3
 DYNB_PLAN_THROUGHPUT = 8
 DYNB_PLAN_BALANCE = 4
+DYNB_PLAN_PERSISTENT = 16
 ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
           -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}
 
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
-           "dynbatch_execute", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
-           "dynb_timing_enable",
+           "dynbatch_execute", "dynbatch_execute_check", "dynb_set_spin_limit", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
+           "dynb_timing_enable", "dynb_probe_mfma_bf16", "dynb_probe_copy",
            "dynb_timing_read"]
 
 
@@ -45,7 +46,8 @@ class _PlanView(ct.Structure):
                                           "n_launches", "max_launch_nodes", "n_slots")] + \
                [(n, I32P) for n in ("node_level", "node_type", "child0", "child1", "root", "bucket_level",
                                     "bucket_type", "bucket_start", "bucket_count", "members", "in0", "in1", "out",
-                                    "node_launch")]
+                                    "node_launch", "item_node")] + \
+               [("n_tickets", ct.c_int32), ("tickets", I32P)]
 
 
 class _Shape(ct.Structure):
@@ -87,6 +89,9 @@ def _load():
     L.dynbatch_workspace_bytes.restype = ct.c_size_t
     L.dynbatch_execute.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p,
                                    ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynbatch_execute_check.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.c_void_p, ct.c_void_p]
+    L.dynb_set_spin_limit.argtypes = [ct.c_int32]
+    L.dynb_set_spin_limit.restype = ct.c_int32
     L.dynbatch_packed_weights_bytes.argtypes = [ct.POINTER(_Shape), ct.c_int32]
     L.dynbatch_packed_weights_bytes.restype = ct.c_size_t
     L.dynbatch_pack_weights.argtypes = [ct.POINTER(_Shape), ct.c_int32, ct.POINTER(_Weights), ct.c_void_p, ct.c_size_t,
@@ -97,6 +102,8 @@ def _load():
                               ct.c_void_p, ct.c_void_p, ct.POINTER(_MoeAux), ct.c_void_p, ct.c_size_t, ct.c_void_p]
     L.moe_forward_naive.argtypes = L.moe_forward.argtypes + [ct.c_int32]
     L.moe_forward_static.argtypes = L.moe_forward.argtypes[:9] + [ct.c_void_p]
+    L.dynb_probe_mfma_bf16.argtypes = [ct.c_int32, ct.c_int32, ct.c_void_p, ct.c_void_p, ct.POINTER(ct.c_double)]
+    L.dynb_probe_copy.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_size_t, ct.c_void_p]
     L.dynb_timing_enable.argtypes = [ct.c_int]
     L.dynb_timing_read.argtypes = [ct.POINTER(_StageTime), ct.c_int32, ct.POINTER(ct.c_int32)]
     return L
@@ -195,7 +202,8 @@ def dynbatch_plan_view(plan: Plan) -> SimpleNamespace:
         child1=arr(v.child1, N), root=arr(v.root, B), bucket_level=arr(v.bucket_level, nb),
         bucket_type=arr(v.bucket_type, nb), bucket_start=arr(v.bucket_start, nb),
         bucket_count=arr(v.bucket_count, nb), members=arr(v.members, N), in0=arr(v.in0, N), in1=arr(v.in1, N),
-        out=arr(v.out, N), node_launch=arr(v.node_launch, N))
+        out=arr(v.out, N), node_launch=arr(v.node_launch, N), item_node=arr(v.item_node, v.n_compute_nodes),
+        n_tickets=v.n_tickets, tickets=arr(v.tickets, v.n_tickets))
 
 
 def dynbatch_plan_device_bytes(plan: Plan) -> int:
@@ -276,6 +284,16 @@ def dynbatch_execute(plan: Plan, weights: dict, feats, out=None, workspace=None,
     _check(lib.dynbatch_execute(plan.handle, ct.byref(shape), ct.byref(w), _ptr(feats), _ptr(out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
+
+
+def dynbatch_execute_check(plan: Plan, feats, workspace, stream=None) -> None:
+    """After executing a DYNB_PLAN_PERSISTENT plan: waits for the stream and raises DynbError(DYNB_E_HIP) if a
+    bounded wait of the dependency-driven kernel expired."""
+    _check(lib.dynbatch_execute_check(plan.handle, ct.byref(_shape_of(feats)), _ptr(workspace), _stream(stream)))
+
+
+def dynb_set_spin_limit(polls: int) -> int:
+    return int(lib.dynb_set_spin_limit(int(polls)))
 
 
 # ------------------------------------------------------------------------------------------ MoE
@@ -371,3 +389,19 @@ def dynb_timing_read():
     buf = (_StageTime * n.value)()
     _check(lib.dynb_timing_read(buf, n.value, ct.byref(n)))
     return [(b.tag, b.units, b.ms) for b in buf]
+
+
+# ------------------------------------------------------------------------------------------ measurement helpers
+def dynb_probe_mfma_bf16(iters: int, workgroups: int, sink, stream=None) -> float:
+    """Enqueues the register-only MFMA loop; returns its flop count (time it with events on the stream)."""
+    fl = ct.c_double(0.0)
+    _check(lib.dynb_probe_mfma_bf16(iters, workgroups, _ptr(sink), _stream(stream), ct.byref(fl)))
+    return fl.value
+
+
+def dynb_probe_copy(dst, src, stream=None) -> int:
+    """Enqueues the plain copy kernel over two equally sized device tensors; returns the bytes copied."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(lib.dynb_probe_copy(_ptr(dst), _ptr(src), n, _stream(stream)))
+    return n

@@ -311,8 +311,10 @@ __device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t
 //           which halves the latency of narrow launch groups at the price of 8/7 of the MFMA work.
 //   WM = 4: the layout of WM = 2 inside at most 256 registers (weight ring of 4 steps), so that two
 //           workgroups share a CU and one's staging, swap and epilogue run under the other's MFMAs.
+// One workgroup's share of a launch group: position `logical` (a node, half a node or a pair of nodes,
+// depending on the layout) of the items a.items[0 .. a.count).
 template <int WMODE>
-__global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs a)
+__device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 {
     using namespace mf;
     constexpr int WM = (WMODE == 4) ? 2 : WMODE;
@@ -324,11 +326,6 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     constexpr bool HALF = (WM == 3);
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
-    // Workgroup -> position in the launch group.  Consecutive workgroup ids land on different
-    // XCDs; give every XCD one contiguous run of items (items are sorted by function id) so that
-    // a function's weights stay in as few L2s as possible.
-    const int per_xcd = gridDim.x >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     const int first = HALF ? (logical >> 1) : logical * NPW;
     if (first >= a.count) return;
     // pixel window of this workgroup: image rows [wrow0, wrow0 + wrows); output rows [orow0, orow1)
@@ -585,6 +582,101 @@ __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs 
     PHASE(9);
 }
 
+template <int WMODE>
+__global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs a)
+{
+    // Workgroup -> position in the launch group.  Consecutive workgroup ids land on different
+    // XCDs; give every XCD one contiguous run of items (items are sorted by function id) so that
+    // a function's weights stay in as few L2s as possible.
+    const int per_xcd = gridDim.x >> 3;
+    module_body<WMODE>(a, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3));
+}
+
+// ---- one dependency-driven launch per batch ---------------------------------------------------------
+// Resident workgroups claim units of work (tickets) in the plan's execution order from one device
+// counter.  A unit's arguments are results of units with smaller tickets; those were claimed by
+// workgroups that are already running and that in turn only wait for still smaller tickets, so the unit
+// with the smallest unfinished ticket never waits and every wait ends.  The waits are bounded all the
+// same: a workgroup that gives up raises the status word, and from then on every workgroup only drains
+// the counter.  ready[slot] counts published halves of a result (a whole node adds 2).
+struct PersistArgs {
+    const int32_t* tickets;   // device [n_tickets]: 4 * item + part
+    int32_t n_tickets;
+    int32_t spin_limit;
+    int32_t* ready;           // device [n_slots], zero before the launch
+    int32_t* counter;         // device, zero before the launch
+    int32_t* status;          // device, zero before the launch; 1 = a wait expired
+};
+
+__device__ __forceinline__ int32_t load_relaxed(const int32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(256, 1) void k_module_persist(MfArgs a, PersistArgs q)
+{
+    __shared__ int32_t s_ticket, s_go;
+    const dynb_item* items = a.items;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            const int32_t tk = __hip_atomic_fetch_add(q.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int32_t go = 0;                                   // 0: stop, 1: compute, 2: skip (draining after an error)
+            if (tk < q.n_tickets) {
+                go = 1;
+                const dynb_item it = items[q.tickets[tk] >> 2];
+                const int nsrc = a.arity[it.type];
+                for (int s = 0; s < nsrc && go == 1; ++s) {
+                    const int32_t src = s == 0 ? it.src0 : it.src1;
+                    if (src < 0) continue;                    // an example's feature map: always there
+                    int32_t polls = 0;
+                    while (load_relaxed(q.ready + src) < 2) {
+                        if (polls >= q.spin_limit || load_relaxed(q.status) != 0) {
+                            __hip_atomic_store(q.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            go = 2;
+                            break;
+                        }
+                        ++polls;
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+                }
+                if (go == 1 && load_relaxed(q.status) != 0) go = 2;
+                // The arguments' maps were written by other CUs, possibly behind another L2: drop what this CU's
+                // vector cache and this L2 may still hold of those addresses.  One wave does it for the
+                // workgroup (its waves share both caches); the others load only after the barrier below.
+                if (go == 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            }
+            s_ticket = tk;
+            s_go = go;
+        }
+        __syncthreads();
+        const int32_t tk = s_ticket, go = s_go;
+        __syncthreads();                                      // both are read before thread 0 writes them again
+        if (go == 0) return;
+        if (go == 2) continue;
+        const int32_t t = q.tickets[tk];
+        MfArgs b = a;
+        b.items = items + (t >> 2);
+        b.count = 1;
+        b.any_binary = (a.arity[b.items[0].type] == 2);
+        const int part = t & 3;
+        if (part == 0) module_body<2>(b, 0);
+        else module_body<3>(b, part - 1);
+        // Publish: every wave waits until its stores of the result have reached the L2 (all waves of a
+        // workgroup sit behind the same one), then one thread writes that L2's dirty lines back to memory,
+        // where every CU can see them, and raises the flag (the agent-scope release does both).
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();                                      // also frees the LDS tile for the next unit
+        const int32_t dst = b.items[0].dst;
+        if (threadIdx.x == 0 && dst >= 0)
+            __hip_atomic_fetch_add(q.ready + dst, part == 0 ? 2 : 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__global__ void k_fill_i32(int32_t* p, size_t n, int32_t v)
+{
+    for (size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += size_t(gridDim.x) * blockDim.x) p[i] = v;
+}
+
 size_t elt_bytes(int dtype) { return dtype == DYNB_BF16 ? 2 : 4; }
 
 bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 128 && s->H == 14 && s->W == 14; }
@@ -604,15 +696,31 @@ extern "C" int dynb_debug_phase_clocks(void* device_buf)
 }
 #endif
 
-// Device buffer layout of an uploaded plan: items | leaf-root example ids | arity table
+// Device buffer layout of an uploaded plan: items | leaf-root example ids | arity table | tickets
 static size_t plan_items_bytes(const dynb_plan* p) { return align256(p->items.size() * sizeof(dynb_item)); }
 static size_t plan_leaf_bytes(const dynb_plan* p) { return align256(p->leaf_roots.size() * sizeof(int32_t)); }
+static size_t plan_arity_bytes(const dynb_plan* p) { return align256(p->arity.size()); }
+static size_t plan_ticket_bytes(const dynb_plan* p) { return align256(p->tickets.size() * sizeof(int32_t)); }
 
 extern "C" size_t dynbatch_plan_device_bytes(const dynb_plan* p)
 {
     if (!p) return 0;
-    return plan_items_bytes(p) + plan_leaf_bytes(p) + align256(p->arity.size()) + 256;
+    return plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p) + plan_ticket_bytes(p) + 256;
 }
+
+// Workspace tail of the dependency-driven launch: ready[n_slots] | counter | status (after the slots and,
+// without prepared weights, the packed weights)
+static size_t persist_sync_bytes(const dynb_plan* p) { return p->persistent ? align256((size_t(p->n_slots) + 2) * sizeof(int32_t)) : 0; }
+
+// offset of that tail: behind the slots and the room for packed weights
+static size_t persist_sync_offset(const dynb_plan* p)
+{
+    return align256(size_t(p->n_slots) * mf::P * mf::C * 2) + align256(packed_weight_bytes(p->n_types));
+}
+
+static std::atomic<int32_t> g_spin_limit{1 << 22};
+
+extern "C" int32_t dynb_set_spin_limit(int32_t polls) { return g_spin_limit.exchange(polls < 0 ? 0 : polls); }
 
 extern "C" int dynbatch_plan_upload(dynb_plan* p, void* dev_buf, size_t bytes, void* stream)
 {
@@ -631,6 +739,10 @@ extern "C" int dynbatch_plan_upload(dynb_plan* p, void* dev_buf, size_t bytes, v
     HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p) + plan_leaf_bytes(p), p->arity.data(), p->arity.size(),
                            hipMemcpyHostToDevice, st),
             "dynbatch_plan_upload(arity)");
+    if (!p->tickets.empty())
+        HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p), p->tickets.data(),
+                               p->tickets.size() * sizeof(int32_t), hipMemcpyHostToDevice, st),
+                "dynbatch_plan_upload(tickets)");
     p->dev_buf = dev_buf;
     p->dev_bytes = bytes;
     return DYNB_OK;
@@ -644,7 +756,8 @@ extern "C" size_t dynbatch_workspace_bytes(const dynb_plan* p, const dynb_shape*
     size_t n = size_t(p->n_slots);
     if (!fast_shape(s)) n += 2 * size_t(p->max_launch);                       // u and mid of one launch group
     size_t bytes = align256(n * map);
-    if (fast_shape(s)) bytes += packed_weight_bytes(p->n_types);              // weights in MFMA fragment order
+    if (fast_shape(s)) bytes += align256(packed_weight_bytes(p->n_types));    // weights in MFMA fragment order
+    if (fast_shape(s)) bytes += persist_sync_bytes(p);                        // ready flags, ticket counter, status
     return std::max<size_t>(bytes, 256);
 }
 
@@ -708,9 +821,16 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
                     hipStream_t st)
 {
     static std::atomic<uint64_t> attr_set{0};                 // one bit per device
+    static int cu_count[64] = {};
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
     if (!(attr_set.load() >> (dev & 63) & 1)) {
+        int cus = 0;
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute");
+        cu_count[dev & 63] = cus > 0 ? cus : 256;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_persist),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_persist)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<2>)");
@@ -744,6 +864,29 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.w3a = pk3a; a.b3a = w->b3a;
     a.w3b = pk3b; a.b3b = w->b3b;
     const bool timed = dynb::timing_on(), coarse = dynb::timing_coarse();
+    if (p->persistent) {
+        // one launch for the whole batch: clear the ready flags, the ticket counter and the status word with a
+        // fill kernel (no memset node: the call may be captured into a graph), then the resident workgroups
+        PersistArgs q;
+        q.tickets = reinterpret_cast<const int32_t*>(d + plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p));
+        q.n_tickets = int32_t(p->tickets.size());
+        q.spin_limit = g_spin_limit.load();
+        q.ready = reinterpret_cast<int32_t*>(ws + persist_sync_offset(p));
+        q.counter = q.ready + p->n_slots;
+        q.status = q.counter + 1;
+        const size_t nsync = size_t(p->n_slots) + 2;
+        hipLaunchKernelGGL(k_fill_i32, dim3(unsigned(std::min<size_t>((nsync + 255) / 256, 256))), dim3(256), 0, st, q.ready, nsync, 0);
+        if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
+        a.items = reinterpret_cast<const dynb_item*>(d);
+        a.count = int32_t(p->items.size());
+        a.any_binary = 0;
+        const int resident = cu_count[dev & 63];              // one workgroup per CU (73 KB of LDS, all registers)
+        const unsigned grid = unsigned(std::min<int>(q.n_tickets, resident));
+        hipLaunchKernelGGL(k_module_persist, dim3(grid), dim3(256), mf::TILE_BYTES, st, a, q);
+        if (timed) dynb::timing_mark(st, 0, a.count);
+        HIP_TRY(hipGetLastError(), "dynbatch_execute(dependency-driven kernel)");
+        return DYNB_OK;
+    }
     if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
     int32_t evals = 0;
     for (const dynb_launch& l : p->launches) {
@@ -831,4 +974,19 @@ extern "C" int dynbatch_execute(const dynb_plan* p, const dynb_shape* s, const d
     if (fast_shape(s)) return run_mfma(p, w, feats, out, ws, st);
     if (s->dtype == DYNB_BF16) return run_generic<bf16_t>(p, s, w, feats, out, ws, st);
     return run_generic<float>(p, s, w, feats, out, ws, st);
+}
+
+extern "C" int dynbatch_execute_check(const dynb_plan* p, const dynb_shape* s, const void* workspace, void* stream)
+{
+    if (!p || !s || !workspace) return fail(DYNB_E_INVAL, "dynbatch_execute_check: NULL argument");
+    if (!p->persistent) return fail(DYNB_E_INVAL, "dynbatch_execute_check: the plan was not made with DYNB_PLAN_PERSISTENT");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipStreamSynchronize(st), "dynbatch_execute_check(synchronize)");
+    if (!fast_shape(s) || p->items.empty()) return DYNB_OK;   // those run one launch per label: nothing waits
+    int32_t status = 0;
+    const char* w = static_cast<const char*>(workspace) + persist_sync_offset(p) + (size_t(p->n_slots) + 1) * sizeof(int32_t);
+    HIP_TRY(hipMemcpy(&status, w, sizeof(status), hipMemcpyDeviceToHost), "dynbatch_execute_check(read status)");
+    if (status != 0)
+        return fail(DYNB_E_HIP, "dynbatch_execute: a workgroup gave up waiting for an argument of its node; the results are invalid");
+    return DYNB_OK;
 }

@@ -36,6 +36,11 @@ struct dynb_plan {
     int32_t n_slots = 0, max_launch = 0;
     bool has_binary = false;
     bool throughput = false;             // DYNB_PLAN_THROUGHPUT: most work per CU instead of lowest latency
+    bool persistent = false;             // DYNB_PLAN_PERSISTENT: one dependency-driven launch per batch
+    std::vector<int32_t> item_node;      // node id of every item
+    // DYNB_PLAN_PERSISTENT: units of work in the order workgroups claim them: 4 * item + part, part 0 = the
+    // whole node, 1 / 2 = its upper / lower half.  Every unit of a node's arguments precedes the node's units.
+    std::vector<int32_t> tickets;
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };

@@ -255,8 +255,10 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         // alternating halves suffice.  Balanced and dependency-depth plans keep a result for several
         // groups: they recycle slots through a free list once the consuming group has been issued.
         // A shared node lives until its last consumer has been issued (use counts).
-        const bool pingpong = improved && !balance && !shared;
-        const bool recycle = (improved && balance) || by_depth || shared;
+        // One dependency-driven launch per batch has no label boundary after which a slot could be reused:
+        // every result keeps a slot of its own.
+        const bool pingpong = improved && !balance && !shared && !p->persistent;
+        const bool recycle = ((improved && balance) || by_depth || shared) && !p->persistent;
         std::vector<int32_t> uses;
         if (recycle) {
             uses.assign(N, 0);
@@ -304,9 +306,21 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
             ++p->launches.back().count;
             if (arity[it.type] == 2) p->launches.back().any_binary = 1;
             p->items.push_back(it);
+            p->item_node.push_back(n);
         }
         p->n_slots = pingpong ? 2 * maxw : running;
         for (const auto& l : p->launches) p->max_launch = std::max(p->max_launch, l.count);
+    }
+    // 4. units of work of the dependency-driven launch, in claim order = execution order of the items
+    // (arguments always come earlier in it).  Groups that leave half of the chip idle are run with two
+    // workgroups per node (upper and lower half of the map), like the per-label executor does.
+    if (p->persistent) {
+        p->tickets.reserve(2 * p->items.size());
+        for (const auto& l : p->launches)
+            for (int32_t i = l.start; i < l.start + l.count; ++i) {
+                if (l.count <= 128) { p->tickets.push_back(4 * i + 1); p->tickets.push_back(4 * i + 2); }
+                else p->tickets.push_back(4 * i);
+            }
     }
     for (int32_t i = 0; i < B; ++i)
         if (arity[p->type[p->root[i]]] == 0) p->leaf_roots.push_back(i);
@@ -322,9 +336,11 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     if (out) *out = nullptr;
     if (!prog || !prog_off || !arity || !out) return fail(DYNB_E_INVAL, "dynbatch_plan: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
-    const bool balance = (flags & DYNB_PLAN_BALANCE) != 0;
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
+    // one dependency-driven launch per batch sizes its units of work by the balanced launch groups
+    const bool persistent = (flags & DYNB_PLAN_PERSISTENT) != 0 && mode != DYNB_SCHED_NAIVE;
+    const bool balance = (flags & DYNB_PLAN_BALANCE) != 0 || persistent;
     for (int32_t t = 0; t < n_types; ++t)
         if (arity[t] > 2)
             return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: function " + std::to_string(t) + " has arity > 2");
@@ -338,6 +354,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         const int32_t N = prog_off[B];
         p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
         p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
+        p->persistent = persistent;
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(prog, prog + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);
@@ -458,7 +475,7 @@ extern "C" int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const
     if (!type || !arg0 || !arg1 || !node_off || !root || !arity || !out)
         return fail(DYNB_E_INVAL, "dynbatch_plan_dag: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan_dag: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT))
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT))
         return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan_dag: unknown flag bits");
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
     if (mode != DYNB_SCHED_IMPROVED && mode != DYNB_SCHED_DEPTH)
@@ -476,6 +493,7 @@ extern "C" int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const
         const int32_t N = node_off[B];
         p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
         p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
+        p->persistent = (flags & DYNB_PLAN_PERSISTENT) != 0;
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(type, type + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);
@@ -536,6 +554,9 @@ extern "C" int dynbatch_plan_view(const dynb_plan* p, dynb_plan_view* v)
     v->in0 = p->in0.data();
     v->in1 = p->in1.data();
     v->out = p->out.data();
+    v->item_node = p->item_node.data();
+    v->n_tickets = int32_t(p->tickets.size());
+    v->tickets = p->tickets.data();
     return DYNB_OK;
 }
 

@@ -335,3 +335,102 @@ def test_random_shapes_and_schedules(dyn, util, oracle):
             if base is None:
                 base = got
             assert (got == base).all(), (case, flags)   # every schedule gives the same bits
+
+
+# ------------------------------------------------------------------------------------------------
+# DYNB_PLAN_PERSISTENT: one dependency-driven launch per batch
+# ------------------------------------------------------------------------------------------------
+def run_persistent(dyn, util, w, flags, weights=None, feats=None):
+    """plan -> upload -> execute -> check; returns the root maps (device tensor)."""
+    import torch
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, flags | dyn.DYNB_PLAN_PERSISTENT)
+    assert dyn.dynbatch_plan_view(plan).n_tickets >= dyn.dynbatch_plan_view(plan).n_compute_nodes
+    dyn.dynbatch_plan_upload(plan)
+    weights = weights if weights is not None else util.iep_weights_dev(w)
+    feats = feats if feats is not None else util.to_dev(w.feats, w.dtype)
+    ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16 if w.dtype == "bf16" else dyn.DYNB_F32),
+                     dtype=torch.uint8, device="cuda")
+    out = dyn.dynbatch_execute(plan, weights, feats, workspace=ws)
+    dyn.dynbatch_execute_check(plan, feats, ws)              # synchronises; raises if a bounded wait expired
+    return out
+
+
+@pytest.mark.parametrize("mode", [0, 1, 3])
+def test_one_launch_per_batch_small_batches_every_element(dyn, util, oracle, mode):
+    """Halves and whole nodes, unary and binary functions, single-SCENE programs; against the oracle and, bit for
+    bit, against one launch per label."""
+    w = iep.small_mixed(seed=21, B=11, C=128, H=14, W=14, dtype="bf16", min_len=1, max_len=8)
+    ref = oracle.iep_forward_workload(w)
+    got = util.to_host(run_persistent(dyn, util, w, mode))
+    for i in range(w.B):
+        assert util.normwise(got[i], ref[i]) < TOL["bf16"], (i, util.normwise(got[i], ref[i]))
+    assert (got == util.iep_run(dyn, w, mode)).all()
+    wide = iep.small_mixed(seed=5, B=301, C=128, H=14, W=14, dtype="bf16", min_len=2, max_len=5)   # whole-node units
+    assert (util.to_host(run_persistent(dyn, util, wide, mode)) == util.iep_run(dyn, wide, mode)).all()
+
+
+def test_one_launch_per_batch_full_configurations(dyn, util, full_refs):
+    """Configs 1 and 2 in one dependency-driven launch each: every example against the oracle, and the same bits
+    as one launch per label; twice in a row on the same workspace (flags and counters are cleared by the call)."""
+    import torch
+    for key, make in (("config1", iep.config1), ("config2", iep.config2)):
+        w, ref = full_refs.get(key, make)
+        weights = util.iep_weights_dev(w)
+        weights["packed"] = dyn.dynbatch_pack_weights(weights, w.C, w.H, w.W, dyn.DYNB_BF16)
+        feats = util.to_dev(w.feats, "bf16")
+        plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_SCHED_IMPROVED | dyn.DYNB_PLAN_PERSISTENT)
+        dyn.dynbatch_plan_upload(plan)
+        ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+        out = torch.empty_like(feats)
+        for rep in range(2):
+            out.fill_(float("nan"))
+            dyn.dynbatch_execute(plan, weights, feats, out, ws)
+            dyn.dynbatch_execute_check(plan, feats, ws)
+            got = util.to_host(out)
+            assert_every_example(util, got, ref, TOL["bf16"], f"{key}, one launch per batch, run {rep}")
+        assert (got == util.iep_run(dyn, w, dyn.DYNB_PLAN_BALANCE, weights=weights)).all()
+
+
+def test_one_launch_per_batch_dependency_graphs(dyn, util):
+    d = iep.dag_batch(seed=8, B=150, C=128, H=14, W=14, dtype="bf16", max_nodes=10)
+    import torch
+    ref = util.dag_run(dyn, d, 0)
+    plan = dyn.dynbatch_plan_dag(d.node_type, d.arg0, d.arg1, d.node_off, d.root, d.arity, dyn.DYNB_PLAN_PERSISTENT)
+    dyn.dynbatch_plan_upload(plan)
+    feats = util.to_dev(d.feats, "bf16")
+    ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, d.C, d.H, d.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+    out = dyn.dynbatch_execute(plan, util.iep_weights_dev(d), feats, workspace=ws)
+    dyn.dynbatch_execute_check(plan, feats, ws)
+    assert (util.to_host(out) == ref).all()
+
+
+def test_one_launch_per_batch_generic_shapes_fall_back_to_labels(dyn, util, oracle):
+    w = iep.small_mixed(seed=9, B=7, C=6, H=3, W=4, dtype="f32", min_len=1, max_len=7)
+    got = util.to_host(run_persistent(dyn, util, w, 0))
+    assert util.normwise(got, oracle.iep_forward_workload(w)) < TOL["f32"]
+
+
+def test_a_wait_that_expires_is_reported_and_every_workgroup_still_exits(dyn, util):
+    """Error path forced from the host: with a spin limit of 0 a workgroup gives up as soon as an argument is not
+    ready.  A chain of 6 nodes claimed by 6 resident workgroups at once cannot have its arguments ready (a node
+    takes tens of microseconds), so the status word is raised, the kernel drains and the check reports it."""
+    import torch
+    w = iep.small_mixed(seed=4, B=1, C=128, H=14, W=14, dtype="bf16", min_len=7, max_len=7)
+    w.prog, w.prog_off = np.array([1, 2, 3, 1, 2, 3, 0], np.int32), np.array([0, 7], np.int32)     # a chain of 6 unary modules
+    assert w.n_module_evals == 6
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_PLAN_PERSISTENT)
+    dyn.dynbatch_plan_upload(plan)
+    feats = util.to_dev(w.feats, "bf16")
+    weights = util.iep_weights_dev(w)
+    ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+    old = dyn.dynb_set_spin_limit(0)
+    try:
+        dyn.dynbatch_execute(plan, weights, feats, workspace=ws)
+        with pytest.raises(dyn.DynbError) as e:
+            dyn.dynbatch_execute_check(plan, feats, ws)
+        assert e.value.name == "DYNB_E_HIP"
+    finally:
+        dyn.dynb_set_spin_limit(old)
+    good = dyn.dynbatch_execute(plan, weights, feats, workspace=ws)          # the next call clears the status word
+    dyn.dynbatch_execute_check(plan, feats, ws)
+    assert (util.to_host(good) == util.iep_run(dyn, w)).all()

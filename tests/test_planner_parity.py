@@ -153,7 +153,7 @@ def test_error_codes(dyn):
     assert e.value.name == "DYNB_E_UNSUPPORTED"
     dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=dyn.DYNB_PLAN_THROUGHPUT | dyn.DYNB_PLAN_BALANCE)
     with pytest.raises(dyn.DynbError) as e:
-        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=16)
+        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=32)
     assert e.value.name == "DYNB_E_UNSUPPORTED"
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_plan(ok, np.array([1, 2], np.int32), ar)
@@ -183,3 +183,82 @@ def test_moe_shape_checks_need_no_gpu(dyn):
     # T = 0 succeeds without touching any pointer
     assert lib.moe_forward(ct.byref(_MoeShape(0, 64, 64, 8, 2, 1)), None, None, None, None, None, None, None, None,
                            None, 0, None) == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# DYNB_PLAN_PERSISTENT: the claim order of the single dependency-driven launch, checked on the host
+# ------------------------------------------------------------------------------------------------
+def _persistent_cases(dyn):
+    cases = []
+    for mode in (dyn.DYNB_SCHED_IMPROVED, dyn.DYNB_SCHED_STANDARD, dyn.DYNB_SCHED_DEPTH):
+        for w in (iep.config0(), iep.config1(), iep.config2(), iep.small_mixed(seed=11, B=40, C=4, H=2, W=2, dtype="f32", min_len=1)):
+            plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, mode | dyn.DYNB_PLAN_PERSISTENT)
+            cases.append((f"{w.name}/mode{mode}", w.arity, dyn.dynbatch_plan_view(plan)))
+    for mode in (dyn.DYNB_SCHED_IMPROVED, dyn.DYNB_SCHED_DEPTH):
+        d = iep.dag_batch(seed=5, B=60, C=4, H=2, W=2, dtype="f32", max_nodes=14)
+        plan = dyn.dynbatch_plan_dag(d.node_type, d.arg0, d.arg1, d.node_off, d.root, d.arity, mode | dyn.DYNB_PLAN_PERSISTENT)
+        cases.append((f"dag/mode{mode}", d.arity, dyn.dynbatch_plan_view(plan)))
+    return cases
+
+
+def test_persistent_tickets_cover_every_node_and_follow_their_arguments(dyn):
+    """Every unit of work is claimed after every unit of its node's arguments: the condition under which the
+    bounded waits of the dependency-driven kernel always end (the unit with the smallest unfinished ticket has
+    all its arguments finished)."""
+    for name, arity, v in _persistent_cases(dyn):
+        assert v.n_tickets == len(v.tickets) and v.n_tickets >= v.n_compute_nodes, name
+        item_of_node = {int(n): i for i, n in enumerate(v.item_node)}
+        assert len(item_of_node) == v.n_compute_nodes
+        parts = {}
+        last_ticket_of_item = {}
+        for tk, t in enumerate(v.tickets):
+            item, part = int(t) >> 2, int(t) & 3
+            parts.setdefault(item, []).append(part)
+            last_ticket_of_item[item] = tk
+            node = int(v.item_node[item])
+            for c in (v.child0[node], v.child1[node]):
+                if c >= 0 and arity[v.node_type[c]] > 0:
+                    ci = item_of_node[int(c)]
+                    assert sorted(parts.get(ci, [])) in ([0], [1, 2]), (name, "argument not fully claimed before", tk)
+                    assert last_ticket_of_item[ci] < tk
+        assert sorted(parts) == list(range(v.n_compute_nodes)), name
+        assert all(sorted(p) in ([0], [1, 2]) for p in parts.values()), name      # a whole node, or both halves once
+
+
+def test_persistent_schedule_simulated_with_few_and_many_workers(dyn):
+    """Host simulation of the kernel's protocol: workers claim tickets in order from one counter, wait until
+    both halves (or the whole) of every argument have been published, work for a while and publish.  With any
+    number of workers, any durations and any interleaving every ticket completes."""
+    import heapq
+    g = np.random.default_rng(3)
+    for name, arity, v in _persistent_cases(dyn):
+        item_of_node = {int(n): i for i, n in enumerate(v.item_node)}
+        deps = []
+        for t in v.tickets:
+            node = int(v.item_node[int(t) >> 2])
+            deps.append([item_of_node[int(c)] for c in (v.child0[node], v.child1[node]) if c >= 0 and arity[v.node_type[c]] > 0])
+        for workers in (1, 3, 256):
+            ready = np.zeros(v.n_compute_nodes, np.int64)            # published halves per item
+            free_at = [(0.0, i) for i in range(workers)]             # (time a worker becomes free, id)
+            heapq.heapify(free_at)
+            publish = []                                             # (time, item, amount), applied in time order
+            next_ticket, now, done = 0, 0.0, 0
+            while next_ticket < v.n_tickets:
+                now, wid = heapq.heappop(free_at)
+                while publish and publish[0][0] <= now:
+                    _, it, amt = heapq.heappop(publish)
+                    ready[it] += amt
+                tk = next_ticket
+                next_ticket += 1
+                start = now
+                for dpd in deps[tk]:
+                    while ready[dpd] < 2:                            # the wait: advance time to the next publication
+                        assert publish, (name, workers, "deadlock at ticket", tk)
+                        tpub, it, amt = heapq.heappop(publish)
+                        ready[it] += amt
+                        start = max(start, tpub)
+                end = start + float(g.uniform(0.5, 2.0))
+                heapq.heappush(publish, (end, int(v.tickets[tk]) >> 2, 2 if int(v.tickets[tk]) & 3 == 0 else 1))
+                heapq.heappush(free_at, (end, wid))
+                done += 1
+            assert done == v.n_tickets
