@@ -342,6 +342,15 @@ def main():
                 stages[dyn.MOE_STAGES[tag]].append(ms)
         dyn.dynb_timing_enable(False)
         stage_ms = {n: float(np.median(v)) for n, v in stages.items() if v}
+        # the stacking as a kernel of its own (MOE_SEPARATE_PERMUTE): the HBM-bound scatter, timed alone
+        dyn.dynb_timing_enable(True)
+        perm_alone = []
+        for _ in range(K):
+            dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, out=mout, workspace=mws,
+                            flags=dyn.MOE_SEPARATE_PERMUTE)
+            perm_alone += [ms for tag, _, ms in dyn.dynb_timing_read() if dyn.MOE_STAGES[tag] == "permute"]
+        dyn.dynb_timing_enable(False)
+        permute_ms = float(np.median(perm_alone))
         _, aux = dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k, want_aux=True,
                                  workspace=mws)
         counts = aux.counts.cpu().numpy()
@@ -377,7 +386,8 @@ def main():
                    "protocol": "one layer at a time on one stream",
                    "in_flight": None if moe_fly_ms is None else {"layers_in_flight": MS, "ms_per_step": round(moe_fly_ms, 4),
                                                                  "tokens_per_sec": round(m.T / moe_fly_ms * 1e3, 1)},
-                   "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "active_experts": n_active,
+                   "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "permute_kernel_alone_ms": round(permute_ms, 4),
+                   "active_experts": n_active,
                    "max_expert_rows": int(counts.max()),
                    "expert_layers_bound_ms": round(bound_ms, 4), "expert_layers_frac_of_bound": round(bound_ms / ffn_ms, 4),
                    "naive_gpu": moe_naive}
@@ -386,8 +396,8 @@ def main():
             return dict(kernel=kernel, bound="hbm", achieved=round(nbytes / ms / 1e6, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4), traffic=None, **extra)
 
-        if stage_ms.get("permute", 0.0) > 0:
-            moe_roof.append(roof("k_permute", by_perm, stage_ms["permute"]))
+        moe_roof.append(roof("k_permute", by_perm, permute_ms, note="as a kernel of its own (MOE_SEPARATE_PERMUTE); by default the "
+                             "first expert layer gathers the token rows itself and this kernel does not run"))
         moe_roof.append(roof("k_combine", by_comb, stage_ms["combine"]))
         moe_roof.append(roof("k_grouped_gemm (both expert layers)", by_ffn, ffn_ms, mfma_tflops=round(fl_ffn / ffn_ms / 1e9, 1)))
 

@@ -271,7 +271,15 @@ typedef struct {
     int32_t E;                /* experts (the paper's n)                                        */
     int32_t k;                /* experts per token, 1 <= k <= E                                 */
     int32_t dtype;            /* DYNB_BF16 only                                                 */
+    uint32_t flags;           /* 0, or MOE_SEPARATE_PERMUTE                                     */
 } moe_shape;
+
+/* moe_shape.flags.  By default the stacking of the tokens by expert (Results / Sparsely Gated Mixture
+ * of Experts counts it as "data stacking" next to the expert calls) happens inside the first expert
+ * layer's operand load: the permuted copy of x is never written.  With MOE_SEPARATE_PERMUTE it is a
+ * kernel of its own that writes the copy (an HBM-bound scatter that can be timed and profiled alone);
+ * the results are bit-identical.                                                                   */
+enum { MOE_SEPARATE_PERMUTE = 1 };
 
 /* Optional outputs of the routing stages; any pointer may be NULL.  All device memory.          */
 typedef struct {

@@ -59,7 +59,7 @@ class _Weights(ct.Structure):
 
 
 class _MoeShape(ct.Structure):
-    _fields_ = [(n, ct.c_int32) for n in ("T", "d", "h", "E", "k", "dtype")]
+    _fields_ = [(n, ct.c_int32) for n in ("T", "d", "h", "E", "k", "dtype")] + [("flags", ct.c_uint32)]
 
 
 class _StageTime(ct.Structure):
@@ -302,6 +302,7 @@ def moe_workspace_bytes(T: int, d: int, h: int, E: int, k: int, dtype: int = DYN
 
 
 MOE_STATIC_SCRATCH_BYTES = 48 << 20
+MOE_SEPARATE_PERMUTE = 1
 
 
 def moe_forward_static(x, Wg, Wn, noise, W1, W2, k: int, out, aux=None, stream=None):
@@ -321,7 +322,7 @@ def moe_forward_static(x, Wg, Wn, noise, W1, W2, k: int, out, aux=None, stream=N
 
 
 def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = False, workspace=None, stream=None,
-                naive_stride: int = 0):
+                naive_stride: int = 0, flags: int = 0):
     """x [T,d] bf16; Wg, Wn [E,d] bf16; noise [T,E] f32 or None; W1 [E,h,d]; W2 [E,d,h] bf16 (all device,
     contiguous).  Returns out [T,d] bf16, or (out, aux namespace of device tensors) if want_aux.
     naive_stride >= 1 calls moe_forward_naive (one expert call per use) instead."""
@@ -334,7 +335,7 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int, out=None, want_aux: bool = Fal
     assert Wn is None or (Wn.is_cuda and Wn.is_contiguous() and Wn.dtype == torch.bfloat16 and Wn.shape == (E, d))
     assert noise is None or (noise.is_cuda and noise.is_contiguous() and noise.dtype == torch.float32
                              and noise.shape == (T, E))
-    shape = _MoeShape(T, d, h, E, k, DYNB_BF16)
+    shape = _MoeShape(T, d, h, E, k, DYNB_BF16, flags)
     side = stream is not None and stream != torch.cuda.current_stream()
     if out is None:
         out = torch.empty_like(x)

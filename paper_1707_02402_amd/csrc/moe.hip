@@ -360,10 +360,13 @@ __global__ __launch_bounds__(256) void k_combine(const bf16_t* __restrict__ y, c
 constexpr int KC = 64;                 // K-chunk
 constexpr int LDP = KC + 8;            // LDS row pitch in elements (144 bytes)
 
+// gather != nullptr: the tile's input rows are not in[row0 ..] but rows of `in` picked through the
+// grouping: row r of the tile is in[gather[row0 + r] / kdiv] (the token of that expert use), i.e. the
+// stacking of the tokens happens inside the operand load and the permuted copy is never written.
 template <bool RELU, int ML>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const bf16_t* __restrict__ We,
                                           bf16_t* __restrict__ out, int row0, int rows, int nb, int N, int K,
-                                          bf16_t* Ws, bf16_t* Xs)
+                                          bf16_t* Ws, bf16_t* Xs, const int32_t* __restrict__ gather, int kdiv)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     constexpr int PARTS = KC / 8;                  // 16-byte pieces of one chunk row
@@ -376,7 +379,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ in, const b
 #pragma unroll
     for (int i = 0; i < WPASS; ++i) wsrc[i] = We + size_t(min(nb + prow + i * RPP, N - 1)) * K + part * 8;
 #pragma unroll
-    for (int i = 0; i < XPASS; ++i) xsrc[i] = in + size_t(row0 + min(prow + i * RPP, rows - 1)) * K + part * 8;
+    for (int i = 0; i < XPASS; ++i) {
+        const int r = row0 + min(prow + i * RPP, rows - 1);
+        xsrc[i] = in + size_t(gather ? gather[r] / kdiv : r) * K + part * 8;
+    }
     u32x4 wreg[WPASS], xreg[XPASS];
     auto fetch = [&](int kc) {
         const bool inside = kc * KC + part * 8 < K;   // K is a multiple of 8: the last chunk may be partly empty
@@ -492,7 +498,7 @@ template <bool RELU>
 __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__ in, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ offsets,
                                                       const int32_t* __restrict__ tile_start, int E, int N, int K,
-                                                      int n_tiles_n, int chunk)
+                                                      int n_tiles_n, int chunk, const int32_t* __restrict__ gather, int kdiv)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Ws[TN * LDP];
     __shared__ __attribute__((aligned(16))) bf16_t Xs[TM * LDP];
@@ -524,9 +530,9 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(const bf16_t* __restrict__
     const int mlive = (rows + 15) >> 4;
     const bf16_t* We = W + size_t(e) * N * K;
     const int nb = ntile * TN;
-    if (mlive <= 1) gemm_tile<RELU, 1>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
-    else if (mlive == 2) gemm_tile<RELU, 2>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
-    else gemm_tile<RELU, 4>(in, We, out, row0, rows, nb, N, K, Ws, Xs);
+    if (mlive <= 1) gemm_tile<RELU, 1>(in, We, out, row0, rows, nb, N, K, Ws, Xs, gather, kdiv);
+    else if (mlive == 2) gemm_tile<RELU, 2>(in, We, out, row0, rows, nb, N, K, Ws, Xs, gather, kdiv);
+    else gemm_tile<RELU, 4>(in, We, out, row0, rows, nb, N, K, Ws, Xs, gather, kdiv);
 }
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -570,6 +576,7 @@ int check_shape(const moe_shape* s, const char* who)
     if (s->d % 8 || s->h % 8)
         return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": d and h must be multiples of 8 (rows are moved in 16-byte pieces)");
     if (s->dtype != DYNB_BF16) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": only bf16");
+    if (s->flags & ~uint32_t(MOE_SEPARATE_PERMUTE)) return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": unknown flag bits");
     if (size_t(s->T) * size_t(s->k) >= (size_t(1) << 30) || size_t(s->T) * size_t(s->E) >= (size_t(1) << 40))
         return fail(DYNB_E_UNSUPPORTED, std::string(who) + ": too many expert uses");
     // the grouped expert layers launch one workgroup per (row tile, feature tile): at most ceil(A/TM) + E row tiles
@@ -649,8 +656,10 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     hipLaunchKernelGGL(k_offsets, dim3(1), dim3(64), 0, st, counts, offsets, tile_start, E);
     hipLaunchKernelGGL(k_place, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, offsets, perm, inv, A, L.nblk);
     if (timed) dynb::timing_mark(st, dynb::ST_SORT, 0);
-    // m4 permute
-    hipLaunchKernelGGL(k_permute, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv, xs, T, d, k);
+    // m4 permute: as a kernel of its own (MOE_SEPARATE_PERMUTE, and for the per-use loop), else inside the
+    // first expert layer's operand load, which reads token perm[pos] / k for sorted position pos
+    const bool fused_permute = !(s->flags & MOE_SEPARATE_PERMUTE) && naive_stride <= 0;
+    if (!fused_permute) hipLaunchKernelGGL(k_permute, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv, xs, T, d, k);
     if (timed) dynb::timing_mark(st, dynb::ST_PERMUTE, 0);
     // m5 grouped expert FFN: at most ceil(A/TM) + E row tiles exist
     const long long max_mtiles = (long long)(A + TM - 1) / TM + E;
@@ -658,10 +667,11 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     if (naive_stride <= 0) {
         const long long span = 8ll * XCD_CHUNK;
         hipLaunchKernelGGL((k_grouped_gemm<true>), dim3(unsigned((max_mtiles * nt1 + span - 1) / span * span)), dim3(256), 0, st,
-                           xs, static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1, XCD_CHUNK);
+                           fused_permute ? xb : xs, static_cast<const bf16_t*>(W1), hid, offsets, tile_start, E, h, d, nt1,
+                           XCD_CHUNK, fused_permute ? perm : nullptr, k);
         if (timed) dynb::timing_mark(st, dynb::ST_FFN1, 0);
         hipLaunchKernelGGL((k_grouped_gemm<false>), dim3(unsigned((max_mtiles * nt2 + span - 1) / span * span)), dim3(256), 0, st,
-                           hid, static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2, XCD_CHUNK);
+                           hid, static_cast<const bf16_t*>(W2), y, offsets, tile_start, E, d, h, nt2, XCD_CHUNK, nullptr, 1);
         if (timed) dynb::timing_mark(st, dynb::ST_FFN2, 0);
     } else {
         // the paper's naive version: loop over the k*b expert uses, one expert call (two layers) per use
@@ -676,9 +686,9 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
             for (int pos = off[e]; pos < off[e + 1]; ++pos) {
                 if (pos % naive_stride) continue;
                 hipLaunchKernelGGL((k_grouped_gemm<true>), dim3((nt1 + 7) / 8 * 8), dim3(256), 0, st, xs + size_t(pos) * d,
-                                   w1 + size_t(e) * h * d, hid + size_t(pos) * h, unit, unit + 2, 1, h, d, nt1, 1);
+                                   w1 + size_t(e) * h * d, hid + size_t(pos) * h, unit, unit + 2, 1, h, d, nt1, 1, nullptr, 1);
                 hipLaunchKernelGGL((k_grouped_gemm<false>), dim3((nt2 + 7) / 8 * 8), dim3(256), 0, st, hid + size_t(pos) * h,
-                                   w2 + size_t(e) * d * h, y + size_t(pos) * d, unit, unit + 2, 1, d, h, nt2, 1);
+                                   w2 + size_t(e) * d * h, y + size_t(pos) * d, unit, unit + 2, 1, d, h, nt2, 1, nullptr, 1);
             }
         if (timed) { dynb::timing_mark(st, dynb::ST_FFN1, 0); dynb::timing_mark(st, dynb::ST_FFN2, 0); }
     }

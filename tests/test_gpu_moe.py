@@ -86,6 +86,22 @@ def test_small_layers_every_element(dyn, util, oracle, T, d, h, E, k, empty):
     assert util.normwise(out[clear], e2e.out[clear]) < OUT_TOL
 
 
+@pytest.mark.parametrize("T,d,h,E,k", [(300, 64, 96, 20, 3), (1000, 128, 160, 70, 1), (200, 64, 96, 64, 16), (577, 64, 96, 3, 2)])
+def test_permute_inside_the_operand_load_equals_the_separate_kernel(dyn, util, T, d, h, E, k):
+    """Default: the first expert layer gathers token rows through the grouping; MOE_SEPARATE_PERMUTE writes the
+    permuted copy with k_permute first.  Same arithmetic on the same rows: identical bits."""
+    m = moe.small(seed=T + E, T=T, d=d, h=h, E=E, k=k, empty_frac=0.1 if E > 10 else 0.0)
+    W1, W2 = stack(m)
+    dev = util.moe_inputs_dev(m, W1, W2)
+    args = (dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k)
+    a = dyn.moe_forward(*args)
+    b = dyn.moe_forward(*args, flags=dyn.MOE_SEPARATE_PERMUTE)
+    assert (util.to_host(a) == util.to_host(b)).all()
+    with pytest.raises(dyn.DynbError) as e:
+        dyn.moe_forward(*args, flags=2)
+    assert e.value.name == "DYNB_E_UNSUPPORTED"
+
+
 def test_noiseless_gate_and_ties(dyn, util, oracle):
     """noise = NULL drops the softplus term; duplicated gate columns give exactly equal logits: lower id wins."""
     m = moe.small(seed=9, T=128, d=64, h=64, E=16, k=4)
@@ -112,6 +128,9 @@ def full_layer(dyn, util, m):
     out, aux = util.moe_run(dyn, m, dev=dev)
     out2, aux2 = util.moe_run(dyn, m, dev=dev)
     assert (out2 == out).all() and (aux2["perm"] == aux["perm"]).all()               # deterministic
+    sep = dyn.moe_forward(dev["x"], dev["Wg"], dev["Wn"], dev["noise"], dev["W1"], dev["W2"], m.k,
+                          flags=dyn.MOE_SEPARATE_PERMUTE)
+    assert (util.to_host(sep) == out).all()              # permute as its own kernel or inside the operand load: same bits
     return out, aux, dev, (W1b, W2b)
 
 
