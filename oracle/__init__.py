@@ -256,3 +256,19 @@ def moe_forward(x, Wg, Wn, noise, W1, W2, k: int) -> SimpleNamespace:
     r = moe_route(lg.astype(np.float32), k)
     out = moe_experts(x, r.topk_idx, r.topk_w, W1, W2)
     return SimpleNamespace(logits=lg, out=out, **vars(r))
+
+
+def classify(x, wc, bc, wf1, bf1, wf2, bf2, want_logits: bool = False):
+    """Classifier head on root maps x [B,H,W,C]: conv1x1 (wc [Cc,C]) + ReLU, flatten [H,W,Cc], FC (wf1 [F,H*W*Cc]) +
+    ReLU, FC (wf2 [A,F]), softmax.  Returns probs float64 [B,A] (and the logits if wanted)."""
+    x, wc, bc, wf1, bf1, wf2, bf2 = map(_f32, (x, wc, bc, wf1, bf1, wf2, bf2))
+    B, H, W, C = x.shape
+    Cc, F, A = wc.shape[0], wf1.shape[0], wf2.shape[0]
+    assert wc.shape == (Cc, C) and wf1.shape == (F, H * W * Cc) and wf2.shape == (A, F)
+    probs = np.empty((B, A), np.float64)
+    logits = np.empty((B, A), np.float64)
+    Fp, I = ct.c_float, ct.c_int32
+    rc = lib().oracle_classify(_p(x, Fp), I(B), I(C), I(H), I(W), I(Cc), I(F), I(A), _p(wc, Fp), _p(bc, Fp), _p(wf1, Fp),
+                               _p(bf1, Fp), _p(wf2, Fp), _p(bf2, Fp), _p(probs, ct.c_double), _p(logits, ct.c_double))
+    assert rc == 0, rc
+    return (probs, logits) if want_logits else probs

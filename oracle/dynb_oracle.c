@@ -19,6 +19,9 @@
  *     time; the batched version builds the same network, so outputs must agree.
  *   - Results / Sparsely Gated Mixture of Experts: n experts, k active per example; the
  *     naive version runs the k*b expert uses one by one.
+ *   - Background / Visual Reasoning Programs, last step: the executed program's output map goes through a
+ *     small classifier (one convolutional and two fully connected layers) that yields a softmax
+ *     distribution over answers (oracle_classify).
  *   - Discussion: batching by dependency depth (labels counted up from the argument-free nodes),
  *     and architectures given as a general dependency graph in which a node may have several
  *     consumers (there the label is the MAXIMUM distance from the root, as Methods words it).
@@ -598,4 +601,57 @@ void oracle_moe_experts(const float* x, const int32_t* topk_idx, const double* t
         }
         oracle_moe_token(x + (size_t)t * d, d, h, k, topk_w + (size_t)t * k, p1, p2, out + (size_t)t * d);
     }
+}
+
+/* ----------------------------------------------------------------------------------------
+ * Classifier head (Background / Visual Reasoning Programs: the root map passes through one convolutional
+ * and two fully connected layers, then a softmax over the answers).  The paper gives no sizes or kernel
+ * shape; the reading taken: a 1x1 convolution C -> Cc with ReLU, the map flattened in [H][W][Cc] order,
+ * a fully connected layer to F units with ReLU, a fully connected layer to A answers, softmax.
+ *   x    [B][H][W][C]        root maps
+ *   wc   [Cc][C], bc [Cc]    convolution (bias NULL = none)
+ *   wf1  [F][H*W*Cc], bf1 [F]
+ *   wf2  [A][F], bf2 [A]
+ *   probs [B][A]  (double), logits [B][A] (double, may be NULL)
+ * One example at a time, every sum written out. */
+int oracle_classify(const float* x, int32_t B, int32_t C, int32_t H, int32_t W, int32_t Cc, int32_t F, int32_t A,
+                    const float* wc, const float* bc, const float* wf1, const float* bf1,
+                    const float* wf2, const float* bf2, double* probs, double* logits)
+{
+    if (!x || !wc || !wf1 || !wf2 || !probs || B <= 0 || C <= 0 || H <= 0 || W <= 0 || Cc <= 0 || F <= 0 || A <= 0)
+        return ORC_E_INVAL;
+    const size_t P = (size_t)H * W, J = P * (size_t)Cc;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < B; ++i) {
+        double* z = (double*)malloc(sizeof(double) * J);
+        double* h1 = (double*)malloc(sizeof(double) * (size_t)F);
+        double* lg = (double*)malloc(sizeof(double) * (size_t)A);
+        const float* xi = x + (size_t)i * P * C;
+        for (size_t p = 0; p < P; ++p)
+            for (int32_t cc = 0; cc < Cc; ++cc) {
+                double acc = bc ? (double)bc[cc] : 0.0;
+                for (int32_t c = 0; c < C; ++c) acc += (double)xi[p * C + c] * (double)wc[(size_t)cc * C + c];
+                z[p * Cc + cc] = acc > 0.0 ? acc : 0.0;
+            }
+        for (int32_t f = 0; f < F; ++f) {
+            double acc = bf1 ? (double)bf1[f] : 0.0;
+            for (size_t j = 0; j < J; ++j) acc += z[j] * (double)wf1[(size_t)f * J + j];
+            h1[f] = acc > 0.0 ? acc : 0.0;
+        }
+        double mx = -INFINITY;
+        for (int32_t a = 0; a < A; ++a) {
+            double acc = bf2 ? (double)bf2[a] : 0.0;
+            for (int32_t f = 0; f < F; ++f) acc += h1[f] * (double)wf2[(size_t)a * F + f];
+            lg[a] = acc;
+            if (acc > mx) mx = acc;
+        }
+        double den = 0.0;
+        for (int32_t a = 0; a < A; ++a) den += exp(lg[a] - mx);
+        for (int32_t a = 0; a < A; ++a) {
+            probs[(size_t)i * A + a] = exp(lg[a] - mx) / den;
+            if (logits) logits[(size_t)i * A + a] = lg[a];
+        }
+        free(z); free(h1); free(lg);
+    }
+    return ORC_OK;
 }
