@@ -261,6 +261,48 @@ int dynbatch_execute_check(const dynb_plan* plan, const dynb_shape* shape, const
 int32_t dynb_set_spin_limit(int32_t polls);
 
 /* ------------------------------------------------------------------------------------------- */
+/* Classifier head                                                                               */
+/* ------------------------------------------------------------------------------------------- */
+
+/* Background / Visual Reasoning Programs: the output of the executed program passes through a small
+ * classifier, one convolutional and two fully connected layers, that yields a softmax distribution
+ * over the answers.  The paper gives neither sizes nor the kernel shape; this library takes
+ *   z  = ReLU(conv1x1_{C -> Cc}(root) + bc)         per pixel
+ *   h1 = ReLU(wf1 . flatten(z) + bf1)               flatten in [H][W][Cc] order, F units
+ *   p  = softmax(wf2 . h1 + bf2)                    n_answers entries                           */
+typedef struct {
+    int32_t C, H, W;
+    int32_t dtype;            /* DYNB_F32 or DYNB_BF16: element type of the root maps and the three
+                                 weight tensors (z and h1 are kept in it too); sums are fp32    */
+    int32_t Cc;               /* channels after the convolution                                  */
+    int32_t F;                /* units of the first fully connected layer                        */
+    int32_t n_answers;
+} dynb_head_shape;
+
+typedef struct {
+    const void* wc;           /* device [Cc][C]             dtype                                 */
+    const float* bc;          /* device [Cc]                fp32; NULL = no bias                  */
+    const void* wf1;          /* device [F][H*W*Cc]         dtype                                 */
+    const float* bf1;         /* device [F]                 fp32; NULL = no bias                  */
+    const void* wf2;          /* device [n_answers][F]      dtype                                 */
+    const float* bf2;         /* device [n_answers]         fp32; NULL = no bias                  */
+} dynb_head_weights;
+
+/* Bytes of device workspace dynbatch_classify needs for B root maps (0 on bad input). */
+size_t dynbatch_classify_workspace_bytes(const dynb_head_shape* shape, int32_t B);
+
+/* Runs the classifier on B root maps, asynchronously on `stream`.
+ *   roots      device [B][H][W][C] dtype: what dynbatch_execute wrote to its `out`
+ *   probs      device [B][n_answers] fp32
+ *   logits     device [B][n_answers] fp32 or NULL: the inputs of the softmax, if wanted
+ *   workspace  device, >= dynbatch_classify_workspace_bytes, 256-byte aligned, scratch
+ * Any sizes are accepted; bf16 layers whose inner extent (C, H*W*Cc, F) is a multiple of 8 run on
+ * MFMAs, the others on plain FMAs.  B = 0 succeeds without work.  Errors: DYNB_E_INVAL (NULL,
+ * sizes <= 0, misaligned), DYNB_E_WORKSPACE, DYNB_E_UNSUPPORTED (dtype, batch too large), DYNB_E_HIP. */
+int dynbatch_classify(const dynb_head_shape* shape, const dynb_head_weights* w, const void* roots, int32_t B,
+                      float* probs, float* logits, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------- */
 /* Mixture of experts                                                                            */
 /* ------------------------------------------------------------------------------------------- */
 

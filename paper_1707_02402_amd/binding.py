@@ -26,6 +26,7 @@ ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "D
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
+           "dynbatch_classify_workspace_bytes", "dynbatch_classify",
            "dynbatch_execute", "dynbatch_execute_check", "dynb_set_spin_limit", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
            "dynb_timing_enable", "dynb_probe_mfma_bf16", "dynb_probe_copy",
            "dynb_timing_read"]
@@ -56,6 +57,14 @@ class _Shape(ct.Structure):
 
 class _Weights(ct.Structure):
     _fields_ = [(n, ct.c_void_p) for n in ("w1", "b1", "w3a", "b3a", "w3b", "b3b", "packed")]
+
+
+class _HeadShape(ct.Structure):
+    _fields_ = [(n, ct.c_int32) for n in ("C", "H", "W", "dtype", "Cc", "F", "n_answers")]
+
+
+class _HeadWeights(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("wc", "bc", "wf1", "bf1", "wf2", "bf2")]
 
 
 class _MoeShape(ct.Structure):
@@ -89,6 +98,10 @@ def _load():
     L.dynbatch_workspace_bytes.restype = ct.c_size_t
     L.dynbatch_execute.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p,
                                    ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynbatch_classify_workspace_bytes.argtypes = [ct.POINTER(_HeadShape), ct.c_int32]
+    L.dynbatch_classify_workspace_bytes.restype = ct.c_size_t
+    L.dynbatch_classify.argtypes = [ct.POINTER(_HeadShape), ct.POINTER(_HeadWeights), ct.c_void_p, ct.c_int32, ct.c_void_p,
+                                    ct.c_void_p, ct.c_void_p, ct.c_size_t, ct.c_void_p]
     L.dynbatch_execute_check.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.c_void_p, ct.c_void_p]
     L.dynb_set_spin_limit.argtypes = [ct.c_int32]
     L.dynb_set_spin_limit.restype = ct.c_int32
@@ -294,6 +307,44 @@ def dynbatch_execute_check(plan: Plan, feats, workspace, stream=None) -> None:
 
 def dynb_set_spin_limit(polls: int) -> int:
     return int(lib.dynb_set_spin_limit(int(polls)))
+
+
+# ------------------------------------------------------------------------------------------ classifier head
+def _head_shape(roots, head: dict) -> _HeadShape:
+    import torch
+    B, H, W, C = roots.shape
+    dt = DYNB_F32 if roots.dtype == torch.float32 else DYNB_BF16
+    Cc, F, A = head["wc"].shape[0], head["wf1"].shape[0], head["wf2"].shape[0]
+    assert head["wc"].shape == (Cc, C) and head["wf1"].shape == (F, H * W * Cc) and head["wf2"].shape == (A, F)
+    return _HeadShape(C, H, W, dt, Cc, F, A)
+
+
+def dynbatch_classify_workspace_bytes(C, H, W, dtype, Cc, F, n_answers, B) -> int:
+    return int(lib.dynbatch_classify_workspace_bytes(ct.byref(_HeadShape(C, H, W, dtype, Cc, F, n_answers)), B))
+
+
+def dynbatch_classify(roots, head: dict, probs=None, want_logits: bool = False, workspace=None, stream=None):
+    """roots: device [B,H,W,C] float32 or bfloat16 (the output of dynbatch_execute); head: dict of device tensors
+    wc [Cc,C], wf1 [F,H*W*Cc], wf2 [A,F] in the dtype of roots and bc, bf1, bf2 float32 or None.
+    Returns probs [B,A] float32 (and the logits if wanted)."""
+    import torch
+    assert roots.is_cuda and roots.is_contiguous() and roots.dtype in (torch.float32, torch.bfloat16)
+    for key in ("wc", "wf1", "wf2"):
+        assert head[key].is_cuda and head[key].is_contiguous() and head[key].dtype == roots.dtype, key
+    for key in ("bc", "bf1", "bf2"):
+        t = head.get(key)
+        assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32), key
+    shape = _head_shape(roots, head)
+    B, A = roots.shape[0], shape.n_answers
+    if probs is None:
+        probs = torch.empty((B, A), dtype=torch.float32, device=roots.device)
+    logits = torch.empty((B, A), dtype=torch.float32, device=roots.device) if want_logits else None
+    if workspace is None:
+        workspace = _scratch(lib.dynbatch_classify_workspace_bytes(ct.byref(shape), B), roots.device, stream)
+    w = _HeadWeights(*[(head.get(k).data_ptr() if head.get(k) is not None else None) for k in ("wc", "bc", "wf1", "bf1", "wf2", "bf2")])
+    _check(lib.dynbatch_classify(ct.byref(shape), ct.byref(w), _ptr(roots), B, _ptr(probs), _ptr(logits), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+    return (probs, logits) if want_logits else probs
 
 
 # ------------------------------------------------------------------------------------------ MoE

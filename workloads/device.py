@@ -76,3 +76,8 @@ def moe_run(dyn, m, W1=None, W2=None, dev=None, noise: bool = True):
                                dev["W1"], dev["W2"], m.k, want_aux=True)
     torch.cuda.synchronize()
     return to_host(out), {k: v.cpu().numpy() for k, v in vars(aux).items()}
+
+
+def head_dev(head: dict, dtype: str) -> dict:
+    """Classifier-head weights on the device (weights in `dtype`, biases float32)."""
+    return {k: (to_dev(v, dtype) if k in ("wc", "wf1", "wf2") else to_dev(v, "f32")) for k, v in head.items()}

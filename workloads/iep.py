@@ -115,6 +115,27 @@ def _assemble(name, seed, dtype, arity, progs, C, H, W, meta=None, weight_seed=N
     return IepWorkload(name, dtype, arity, prog, off, C, H, W, feats, *w, meta=meta or {})
 
 
+_S_HEAD = 4
+
+
+def make_head(seed: int, C: int, H: int, W: int, Cc: int, F: int, n_answers: int, dtype: str, bias_std: float = 0.01) -> dict:
+    """He-normal weights of the classifier head (1x1 convolution C -> Cc, fully connected H*W*Cc -> F -> n_answers)
+    and small biases: wc [Cc,C], wf1 [F,H*W*Cc], wf2 [n_answers,F], bc, bf1, bf2 (float32; weights bf16-representable
+    if dtype is "bf16")."""
+    g = stream(seed, _S_HEAD)
+    J = H * W * Cc
+    head = dict(wc=g.standard_normal((Cc, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / C)),
+                wf1=g.standard_normal((F, J), dtype=np.float32) * np.float32(np.sqrt(2.0 / J)),
+                wf2=g.standard_normal((n_answers, F), dtype=np.float32) * np.float32(np.sqrt(2.0 / F)),
+                bc=g.standard_normal(Cc, dtype=np.float32) * np.float32(bias_std),
+                bf1=g.standard_normal(F, dtype=np.float32) * np.float32(bias_std),
+                bf2=g.standard_normal(n_answers, dtype=np.float32) * np.float32(bias_std))
+    if dtype == "bf16":
+        for k in ("wc", "wf1", "wf2"):
+            head[k] = round_bf16(head[k])
+    return head
+
+
 # --------------------------------------------------------------------------- config 0
 def random_small_tree(g: np.random.Generator, unary, binary, max_levels=4, max_nodes=12):
     """Random prefix program: root never SCENE, at most max_levels levels, at most max_nodes nodes."""
