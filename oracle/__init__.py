@@ -272,3 +272,33 @@ def classify(x, wc, bc, wf1, bf1, wf2, bf2, want_logits: bool = False):
                                _p(bf1, Fp), _p(wf2, Fp), _p(bf2, Fp), _p(probs, ct.c_double), _p(logits, ct.c_double))
     assert rc == 0, rc
     return (probs, logits) if want_logits else probs
+
+
+def iep_backward(prog, prog_off, arity, feats, w1, b1, w3a, b3a, w3b, b3b, dout) -> SimpleNamespace:
+    """Gradients of L = sum_i <dout[i], root_i> with respect to the feature maps and every module parameter
+    (float64 arrays in the shapes of the inputs): dfeats, dw1, db1, dw3a, db3a, dw3b, db3b."""
+    prog, prog_off = _i32(prog), _i32(prog_off)
+    arity = np.ascontiguousarray(arity, dtype=np.uint8)
+    plan(prog, prog_off, arity)                       # raises on malformed programs
+    feats, dout = _f32(feats), _f32(dout)
+    B, H, W, C = feats.shape
+    assert dout.shape == feats.shape and B == len(prog_off) - 1
+    w1, b1, w3a, b3a, w3b, b3b = map(_f32, (w1, b1, w3a, b3a, w3b, b3b))
+    n_types = len(arity)
+    if w1 is None:
+        assert not (arity == 2).any()
+    D = np.float64
+    g = SimpleNamespace(dfeats=np.empty((B, H, W, C), D), dw1=np.empty((n_types, C, 2 * C), D), db1=np.empty((n_types, C), D),
+                        dw3a=np.empty((n_types, C, 3, 3, C), D), db3a=np.empty((n_types, C), D),
+                        dw3b=np.empty((n_types, C, 3, 3, C), D), db3b=np.empty((n_types, C), D))
+    I, F, Dp = ct.c_int32, ct.c_float, ct.c_double
+    rc = lib().oracle_iep_backward(_p(prog, I), _p(prog_off, I), I(B), _p(arity, ct.c_uint8), I(n_types), I(C), I(H), I(W),
+                                   _p(feats, F), _p(w1, F), _p(b1, F), _p(w3a, F), _p(b3a, F), _p(w3b, F), _p(b3b, F),
+                                   _p(dout, F), _p(g.dfeats, Dp), _p(g.dw1, Dp), _p(g.db1, Dp), _p(g.dw3a, Dp), _p(g.db3a, Dp),
+                                   _p(g.dw3b, Dp), _p(g.db3b, Dp))
+    assert rc == 0, rc
+    return g
+
+
+def iep_backward_workload(w, dout) -> SimpleNamespace:
+    return iep_backward(w.prog, w.prog_off, w.arity, w.feats, w.w1, w.b1, w.w3a, w.b3a, w.w3b, w.b3b, dout)

@@ -22,6 +22,9 @@
  *   - Background / Visual Reasoning Programs, last step: the executed program's output map goes through a
  *     small classifier (one convolutional and two fully connected layers) that yields a softmax
  *     distribution over answers (oracle_classify).
+ *   - Results / IEP also times the backward pass: oracle_iep_backward is the gradient of the executed
+ *     programs (weights, biases and input feature maps) by the chain rule, node by node, written as the
+ *     transpose of the forward loops.
  *   - Discussion: batching by dependency depth (labels counted up from the argument-free nodes),
  *     and architectures given as a general dependency graph in which a node may have several
  *     consumers (there the label is the MAXIMUM distance from the root, as Methods words it).
@@ -652,6 +655,176 @@ int oracle_classify(const float* x, int32_t B, int32_t C, int32_t H, int32_t W, 
             if (logits) logits[(size_t)i * A + a] = lg[a];
         }
         free(z); free(h1); free(lg);
+    }
+    return ORC_OK;
+}
+
+/* ----------------------------------------------------------------------------------------
+ * Backward pass of the executed programs (Results / IEP times it next to inference).
+ * With dout[i] the gradient of a scalar loss with respect to example i's root map, this computes the
+ * gradient with respect to every module parameter (summed over all nodes that use the function, in all
+ * examples) and with respect to every example's input feature map (summed over its SCENE leaves).
+ * Per example: the tree is evaluated once keeping every node's u (input of the residual block), mid
+ * (after the first ReLU) and y; then the chain rule walks from the root down, each step the literal
+ * transpose of the forward loop nest it differentiates.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct bnode {
+    int t;
+    struct bnode *a, *b;          /* arguments (NULL for SCENE / unary's second) */
+    double *y, *u, *mid;          /* y owned; u owned for binary nodes, else an alias of a->y; mid owned */
+} bnode;
+
+typedef struct {
+    double *dw1, *db1, *dw3a, *db3a, *dw3b, *db3b;   /* shapes of the parameters, [n_types, ...] */
+} grads;
+
+static bnode* bfwd(const modules* m, const int32_t* prog, int32_t* pos, const float* feat)
+{
+    size_t n = (size_t)m->H * m->W * m->C, w3 = (size_t)m->C * 9 * m->C;
+    bnode* nd = (bnode*)calloc(1, sizeof(bnode));
+    nd->t = prog[(*pos)++];
+    nd->y = (double*)malloc(n * sizeof(double));
+    if (m->arity[nd->t] == 0) {
+        for (size_t i = 0; i < n; ++i) nd->y[i] = (double)feat[i];
+        return nd;
+    }
+    nd->a = bfwd(m, prog, pos, feat);
+    if (m->arity[nd->t] == 2) {
+        nd->b = bfwd(m, prog, pos, feat);
+        nd->u = (double*)malloc(n * sizeof(double));
+        join1x1(m, nd->t, nd->a->y, nd->b->y, nd->u);
+    } else {
+        nd->u = nd->a->y;
+    }
+    nd->mid = (double*)malloc(n * sizeof(double));
+    conv3x3(nd->u, m->w3a + nd->t * w3, m->b3a ? m->b3a + (size_t)nd->t * m->C : NULL, nd->mid, m->C, m->H, m->W);
+    relu_inplace(nd->mid, n);
+    conv3x3(nd->mid, m->w3b + nd->t * w3, m->b3b ? m->b3b + (size_t)nd->t * m->C : NULL, nd->y, m->C, m->H, m->W);
+    for (size_t i = 0; i < n; ++i) nd->y[i] += nd->u[i];
+    relu_inplace(nd->y, n);
+    return nd;
+}
+
+static void bfree(const modules* m, bnode* nd)
+{
+    if (!nd) return;
+    bfree(m, nd->a); bfree(m, nd->b);
+    if (m->arity[nd->t] == 2) free(nd->u);
+    free(nd->mid); free(nd->y); free(nd);
+}
+
+/* Transpose of conv3x3: given gout = dL/d(out), adds dL/dw to dw and dL/db to db, and writes gin = dL/d(in). */
+static void conv3x3_backward(const double* gout, const double* in, const float* w, double* gin, double* dw, double* db,
+                             int C, int H, int W)
+{
+    memset(gin, 0, sizeof(double) * (size_t)H * W * C);
+    for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x)
+            for (int co = 0; co < C; ++co) {
+                const double g = gout[((size_t)y * W + x) * C + co];
+                db[co] += g;                                   /* out = b[co] + ... */
+                for (int kh = 0; kh < 3; ++kh) {
+                    int iy = y + kh - 1;
+                    if (iy < 0 || iy >= H) continue;
+                    for (int kw = 0; kw < 3; ++kw) {
+                        int ix = x + kw - 1;
+                        if (ix < 0 || ix >= W) continue;
+                        const double* px = in + ((size_t)iy * W + ix) * C;
+                        double* gpx = gin + ((size_t)iy * W + ix) * C;
+                        const size_t wo = (((size_t)co * 3 + kh) * 3 + kw) * C;
+                        for (int ci = 0; ci < C; ++ci) {       /* out += px[ci] * w[wo + ci] */
+                            dw[wo + ci] += g * px[ci];
+                            gpx[ci] += g * (double)w[wo + ci];
+                        }
+                    }
+                }
+            }
+}
+
+static void bbwd(const modules* m, const grads* gr, const bnode* nd, const double* dy, double* dfeat)
+{
+    const int C = m->C;
+    const size_t P = (size_t)m->H * m->W, n = P * C, w3 = (size_t)C * 9 * C;
+    const int t = nd->t;
+    if (m->arity[t] == 0) {                        /* SCENE: y = feat */
+        for (size_t i = 0; i < n; ++i) dfeat[i] += dy[i];
+        return;
+    }
+    double* g = (double*)malloc(n * sizeof(double));       /* through y = ReLU(s), s = u + conv_b(mid) + b_b */
+    for (size_t i = 0; i < n; ++i) g[i] = nd->y[i] > 0.0 ? dy[i] : 0.0;
+    double* dmid = (double*)malloc(n * sizeof(double));
+    conv3x3_backward(g, nd->mid, m->w3b + t * w3, dmid, gr->dw3b + t * w3, gr->db3b + (size_t)t * C, C, m->H, m->W);
+    for (size_t i = 0; i < n; ++i) if (!(nd->mid[i] > 0.0)) dmid[i] = 0.0;    /* mid = ReLU(conv_a(u) + b_a) */
+    double* du = (double*)malloc(n * sizeof(double));
+    conv3x3_backward(dmid, nd->u, m->w3a + t * w3, du, gr->dw3a + t * w3, gr->db3a + (size_t)t * C, C, m->H, m->W);
+    for (size_t i = 0; i < n; ++i) du[i] += g[i];          /* the residual path: s = u + ... */
+    free(g); free(dmid);
+    if (m->arity[t] == 1) {
+        bbwd(m, gr, nd->a, du, dfeat);
+    } else {                                       /* u = ReLU(c), c[p][co] = b1[co] + sum_ci cat[p][ci] * w1[co][ci] */
+        const float* w = m->w1 + (size_t)t * C * 2 * C;
+        double* dw = gr->dw1 + (size_t)t * C * 2 * C;
+        double* da = (double*)calloc(n, sizeof(double));
+        double* dbm = (double*)calloc(n, sizeof(double));
+        for (size_t p = 0; p < P; ++p)
+            for (int co = 0; co < C; ++co) {
+                const double dc = nd->u[p * C + co] > 0.0 ? du[p * C + co] : 0.0;
+                gr->db1[(size_t)t * C + co] += dc;
+                for (int ci = 0; ci < C; ++ci) {
+                    dw[(size_t)co * 2 * C + ci] += dc * nd->a->y[p * C + ci];
+                    da[p * C + ci] += dc * (double)w[(size_t)co * 2 * C + ci];
+                    dw[(size_t)co * 2 * C + C + ci] += dc * nd->b->y[p * C + ci];
+                    dbm[p * C + ci] += dc * (double)w[(size_t)co * 2 * C + C + ci];
+                }
+            }
+        bbwd(m, gr, nd->a, da, dfeat);
+        bbwd(m, gr, nd->b, dbm, dfeat);
+        free(da); free(dbm);
+    }
+    free(du);
+}
+
+/* Programs must be well formed.  dout: float [B,H,W,C].  Outputs (double, overwritten): dfeats [B,H,W,C] and the
+ * parameter gradients in the shapes of the parameters; dw1/db1 may be NULL if no function is binary. */
+int oracle_iep_backward(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
+                        int32_t n_types, int32_t C, int32_t H, int32_t W, const float* feats,
+                        const float* w1, const float* b1, const float* w3a, const float* b3a,
+                        const float* w3b, const float* b3b, const float* dout, double* dfeats,
+                        double* dw1, double* db1, double* dw3a, double* db3a, double* dw3b, double* db3b)
+{
+    if (!prog || !prog_off || B <= 0 || !feats || !dout || !dfeats || !w3a || !w3b || !dw3a || !db3a || !dw3b || !db3b)
+        return ORC_E_INVAL;
+    modules m = { C, H, W, n_types, arity, w1, b1, w3a, b3a, w3b, b3b };
+    const size_t n = (size_t)H * W * C, s3 = (size_t)n_types * C * 9 * C, s1 = (size_t)n_types * C * 2 * C, sb = (size_t)n_types * C;
+    memset(dfeats, 0, sizeof(double) * n * B);
+    memset(dw3a, 0, sizeof(double) * s3); memset(dw3b, 0, sizeof(double) * s3);
+    memset(db3a, 0, sizeof(double) * sb); memset(db3b, 0, sizeof(double) * sb);
+    if (dw1) memset(dw1, 0, sizeof(double) * s1);
+    if (db1) memset(db1, 0, sizeof(double) * sb);
+#pragma omp parallel
+    {
+        grads gr;                                   /* this thread's sums, added to the result at the end */
+        gr.dw3a = (double*)calloc(s3, sizeof(double)); gr.dw3b = (double*)calloc(s3, sizeof(double));
+        gr.db3a = (double*)calloc(sb, sizeof(double)); gr.db3b = (double*)calloc(sb, sizeof(double));
+        gr.dw1 = (double*)calloc(s1, sizeof(double)); gr.db1 = (double*)calloc(sb, sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t i = 0; i < B; ++i) {
+            int32_t pos = prog_off[i];
+            bnode* root = bfwd(&m, prog, &pos, feats + (size_t)i * n);
+            double* dy = (double*)malloc(n * sizeof(double));
+            for (size_t e = 0; e < n; ++e) dy[e] = (double)dout[(size_t)i * n + e];
+            bbwd(&m, &gr, root, dy, dfeats + (size_t)i * n);
+            free(dy);
+            bfree(&m, root);
+        }
+#pragma omp critical
+        {
+            for (size_t e = 0; e < s3; ++e) { dw3a[e] += gr.dw3a[e]; dw3b[e] += gr.dw3b[e]; }
+            for (size_t e = 0; e < sb; ++e) { db3a[e] += gr.db3a[e]; db3b[e] += gr.db3b[e]; }
+            if (dw1) for (size_t e = 0; e < s1; ++e) dw1[e] += gr.dw1[e];
+            if (db1) for (size_t e = 0; e < sb; ++e) db1[e] += gr.db1[e];
+        }
+        free(gr.dw3a); free(gr.dw3b); free(gr.db3a); free(gr.db3b); free(gr.dw1); free(gr.db1);
     }
     return ORC_OK;
 }
