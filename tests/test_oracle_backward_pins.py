@@ -114,7 +114,7 @@ def test_closed_forms(oracle):
     assert (g.dfeats[2] == 6.0 * dout[2].astype(np.float64)).all()    # binary: 2 (x + 2x): both leaves are the same map
     # bias gradients: db3b of the unary function = sum over its nodes of the gradient arriving at them
     # (example 0: 1 + 2 + 4 times dout summed over pixels; example 2's unary node receives 2 dout)
-    want = (1 + 2 + 4) * dout[0].sum((0, 1)).astype(np.float64) + 2 * dout[2].sum((0, 1)).astype(np.float64)
+    want = (1 + 2 + 4) * dout[0].astype(np.float64).sum((0, 1)) + 2 * dout[2].astype(np.float64).sum((0, 1))
     assert np.allclose(g.db3b[1], want, rtol=1e-12)
     one = oracle.iep_backward(progs[0], np.array([0, 4], np.int32), arity, feats[:1], w1, zb, w3, zb, w3.copy(), zb, dout[:1])
     two = oracle.iep_backward(progs[2], np.array([0, 4], np.int32), arity, feats[2:], w1, zb, w3, zb, w3.copy(), zb, dout[2:])
