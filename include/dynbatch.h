@@ -90,7 +90,10 @@ enum {
      * node gets a result slot of its own (larger workspace).  Only the fast path (bf16, C = 128,
      * 14 x 14) has this kernel; other shapes run one launch per label as usual.  Results are
      * bit-identical either way.  See dynbatch_execute_check for the bounded waits.                 */
-    DYNB_PLAN_PERSISTENT = 16
+    DYNB_PLAN_PERSISTENT = 16,
+    /* Optional, any scheduling mode: keep every node's result (a slot of its own in the workspace, no
+     * reuse) so that dynbatch_backward can run after dynbatch_execute.  Larger workspace.         */
+    DYNB_PLAN_KEEP = 32
 };
 
 const char* dynb_last_error(void);
@@ -259,6 +262,42 @@ int dynbatch_execute_check(const dynb_plan* plan, const dynb_shape* shape, const
  * second); 0 makes a workgroup give up at once if an argument is not ready.  Process-wide; for tests
  * of the error path.  Returns the previous value.                                               */
 int32_t dynb_set_spin_limit(int32_t polls);
+
+/* ------------------------------------------------------------------------------------------- */
+/* Backward pass of an executed plan                                                             */
+/* ------------------------------------------------------------------------------------------- */
+
+/* Gradients, all device fp32, in the shapes of the tensors they belong to; overwritten by the call. */
+typedef struct {
+    float* dfeats;            /* [B][H][W][C]            gradient of every example's input feature map */
+    float* dw1;               /* [n_types][C][2C]        may be NULL if no function takes two arguments */
+    float* db1;               /* [n_types][C]            may be NULL if no function takes two arguments */
+    float* dw3a;              /* [n_types][C][3][3][C]                                                 */
+    float* db3a;              /* [n_types][C]                                                          */
+    float* dw3b;              /* [n_types][C][3][3][C]                                                 */
+    float* db3b;              /* [n_types][C]                                                          */
+} dynb_module_grads;
+
+/* Bytes of device workspace dynbatch_backward needs (0 on bad input or a plan without DYNB_PLAN_KEEP). */
+size_t dynbatch_backward_workspace_bytes(const dynb_plan* plan, const dynb_shape* shape);
+
+/* Backward pass of the programs a dynbatch_execute call ran (Results / IEP times it beside inference; the
+ * batching is the same: the plan's launch groups in reverse order, parameter gradients summed pool by pool).
+ * With dout[i] = dL/d(root map of example i) for some scalar loss L it writes dL/d(feature maps) and
+ * dL/d(every module parameter), the latter summed over all nodes that use the function.
+ *   plan               made with DYNB_PLAN_KEEP by dynbatch_plan (not dynbatch_plan_dag), uploaded
+ *   w, feats           as passed to dynbatch_execute (w->packed is not used)
+ *   out                device [B][H][W][C] dtype: what dynbatch_execute wrote
+ *   forward_workspace  device: the workspace of that dynbatch_execute call, unchanged since
+ *   dout               device [B][H][W][C] fp32
+ *   grads              host struct of device pointers
+ *   workspace          device, >= dynbatch_backward_workspace_bytes, 256-byte aligned, scratch
+ * Any shape and both dtypes; the kernels are plain FMA kernels (one thread per output element); every sum
+ * has a fixed order, so two calls give the same bits.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small, plan
+ * not uploaded), DYNB_E_UNSUPPORTED (plan without DYNB_PLAN_KEEP, dependency graphs, dtype), DYNB_E_HIP. */
+int dynbatch_backward(const dynb_plan* plan, const dynb_shape* shape, const dynb_module_weights* w, const void* feats,
+                      const void* out, const void* forward_workspace, const float* dout, const dynb_module_grads* grads,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------- */
 /* Classifier head                                                                               */

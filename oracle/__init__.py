@@ -274,9 +274,11 @@ def classify(x, wc, bc, wf1, bf1, wf2, bf2, want_logits: bool = False):
     return (probs, logits) if want_logits else probs
 
 
-def iep_backward(prog, prog_off, arity, feats, w1, b1, w3a, b3a, w3b, b3b, dout) -> SimpleNamespace:
+def iep_backward(prog, prog_off, arity, feats, w1, b1, w3a, b3a, w3b, b3b, dout, round_bf16: bool = False) -> SimpleNamespace:
     """Gradients of L = sum_i <dout[i], root_i> with respect to the feature maps and every module parameter
-    (float64 arrays in the shapes of the inputs): dfeats, dw1, db1, dw3a, db3a, dw3b, db3b."""
+    (float64 arrays in the shapes of the inputs): dfeats, dw1, db1, dw3a, db3a, dw3b, db3b; roots = the root maps
+    of the forward evaluation they belong to.  round_bf16: every stored activation (u of two-argument functions,
+    mid, y) is rounded to bfloat16 in that forward evaluation, as an implementation with bf16 storage holds them."""
     prog, prog_off = _i32(prog), _i32(prog_off)
     arity = np.ascontiguousarray(arity, dtype=np.uint8)
     plan(prog, prog_off, arity)                       # raises on malformed programs
@@ -290,15 +292,16 @@ def iep_backward(prog, prog_off, arity, feats, w1, b1, w3a, b3a, w3b, b3b, dout)
     D = np.float64
     g = SimpleNamespace(dfeats=np.empty((B, H, W, C), D), dw1=np.empty((n_types, C, 2 * C), D), db1=np.empty((n_types, C), D),
                         dw3a=np.empty((n_types, C, 3, 3, C), D), db3a=np.empty((n_types, C), D),
-                        dw3b=np.empty((n_types, C, 3, 3, C), D), db3b=np.empty((n_types, C), D))
+                        dw3b=np.empty((n_types, C, 3, 3, C), D), db3b=np.empty((n_types, C), D),
+                        roots=np.empty((B, H, W, C), D))
     I, F, Dp = ct.c_int32, ct.c_float, ct.c_double
     rc = lib().oracle_iep_backward(_p(prog, I), _p(prog_off, I), I(B), _p(arity, ct.c_uint8), I(n_types), I(C), I(H), I(W),
                                    _p(feats, F), _p(w1, F), _p(b1, F), _p(w3a, F), _p(b3a, F), _p(w3b, F), _p(b3b, F),
-                                   _p(dout, F), _p(g.dfeats, Dp), _p(g.dw1, Dp), _p(g.db1, Dp), _p(g.dw3a, Dp), _p(g.db3a, Dp),
-                                   _p(g.dw3b, Dp), _p(g.db3b, Dp))
+                                   _p(dout, F), I(int(round_bf16)), _p(g.dfeats, Dp), _p(g.dw1, Dp), _p(g.db1, Dp), _p(g.dw3a, Dp),
+                                   _p(g.db3a, Dp), _p(g.dw3b, Dp), _p(g.db3b, Dp), _p(g.roots, Dp))
     assert rc == 0, rc
     return g
 
 
-def iep_backward_workload(w, dout) -> SimpleNamespace:
-    return iep_backward(w.prog, w.prog_off, w.arity, w.feats, w.w1, w.b1, w.w3a, w.b3a, w.w3b, w.b3b, dout)
+def iep_backward_workload(w, dout, round_bf16: bool = False) -> SimpleNamespace:
+    return iep_backward(w.prog, w.prog_off, w.arity, w.feats, w.w1, w.b1, w.w3a, w.b3a, w.w3b, w.b3b, dout, round_bf16)

@@ -678,6 +678,31 @@ typedef struct {
     double *dw1, *db1, *dw3a, *db3a, *dw3b, *db3b;   /* shapes of the parameters, [n_types, ...] */
 } grads;
 
+/* Nearest bfloat16 (round to nearest even) of a double, as a double. */
+static double to_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return v;              /* NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* round_bf16 != 0: every stored activation (the 1x1 output u, mid, y) is rounded to bfloat16 where a bf16
+ * implementation stores it, so that the ReLU decisions of the backward pass are taken on the values such an
+ * implementation holds; the arithmetic in between stays fp64. */
+static int g_round_bf16 = 0;
+#pragma omp threadprivate(g_round_bf16)
+
+static void store_round(double* a, size_t n)
+{
+    if (!g_round_bf16) return;
+    for (size_t i = 0; i < n; ++i) a[i] = to_bf16(a[i]);
+}
+
 static bnode* bfwd(const modules* m, const int32_t* prog, int32_t* pos, const float* feat)
 {
     size_t n = (size_t)m->H * m->W * m->C, w3 = (size_t)m->C * 9 * m->C;
@@ -693,15 +718,18 @@ static bnode* bfwd(const modules* m, const int32_t* prog, int32_t* pos, const fl
         nd->b = bfwd(m, prog, pos, feat);
         nd->u = (double*)malloc(n * sizeof(double));
         join1x1(m, nd->t, nd->a->y, nd->b->y, nd->u);
+        store_round(nd->u, n);
     } else {
         nd->u = nd->a->y;
     }
     nd->mid = (double*)malloc(n * sizeof(double));
     conv3x3(nd->u, m->w3a + nd->t * w3, m->b3a ? m->b3a + (size_t)nd->t * m->C : NULL, nd->mid, m->C, m->H, m->W);
     relu_inplace(nd->mid, n);
+    store_round(nd->mid, n);
     conv3x3(nd->mid, m->w3b + nd->t * w3, m->b3b ? m->b3b + (size_t)nd->t * m->C : NULL, nd->y, m->C, m->H, m->W);
     for (size_t i = 0; i < n; ++i) nd->y[i] += nd->u[i];
     relu_inplace(nd->y, n);
+    store_round(nd->y, n);
     return nd;
 }
 
@@ -785,12 +813,13 @@ static void bbwd(const modules* m, const grads* gr, const bnode* nd, const doubl
 }
 
 /* Programs must be well formed.  dout: float [B,H,W,C].  Outputs (double, overwritten): dfeats [B,H,W,C] and the
- * parameter gradients in the shapes of the parameters; dw1/db1 may be NULL if no function is binary. */
+ * parameter gradients in the shapes of the parameters; dw1/db1 may be NULL if no function is binary; roots
+ * (may be NULL) receives the root maps of the forward evaluation the gradients belong to. */
 int oracle_iep_backward(const int32_t* prog, const int32_t* prog_off, int32_t B, const uint8_t* arity,
                         int32_t n_types, int32_t C, int32_t H, int32_t W, const float* feats,
                         const float* w1, const float* b1, const float* w3a, const float* b3a,
-                        const float* w3b, const float* b3b, const float* dout, double* dfeats,
-                        double* dw1, double* db1, double* dw3a, double* db3a, double* dw3b, double* db3b)
+                        const float* w3b, const float* b3b, const float* dout, int32_t round_bf16, double* dfeats,
+                        double* dw1, double* db1, double* dw3a, double* db3a, double* dw3b, double* db3b, double* roots)
 {
     if (!prog || !prog_off || B <= 0 || !feats || !dout || !dfeats || !w3a || !w3b || !dw3a || !db3a || !dw3b || !db3b)
         return ORC_E_INVAL;
@@ -803,6 +832,7 @@ int oracle_iep_backward(const int32_t* prog, const int32_t* prog_off, int32_t B,
     if (db1) memset(db1, 0, sizeof(double) * sb);
 #pragma omp parallel
     {
+        g_round_bf16 = round_bf16;
         grads gr;                                   /* this thread's sums, added to the result at the end */
         gr.dw3a = (double*)calloc(s3, sizeof(double)); gr.dw3b = (double*)calloc(s3, sizeof(double));
         gr.db3a = (double*)calloc(sb, sizeof(double)); gr.db3b = (double*)calloc(sb, sizeof(double));
@@ -811,6 +841,7 @@ int oracle_iep_backward(const int32_t* prog, const int32_t* prog_off, int32_t B,
         for (int32_t i = 0; i < B; ++i) {
             int32_t pos = prog_off[i];
             bnode* root = bfwd(&m, prog, &pos, feats + (size_t)i * n);
+            if (roots) memcpy(roots + (size_t)i * n, root->y, n * sizeof(double));
             double* dy = (double*)malloc(n * sizeof(double));
             for (size_t e = 0; e < n; ++e) dy[e] = (double)dout[(size_t)i * n + e];
             bbwd(&m, &gr, root, dy, dfeats + (size_t)i * n);

@@ -20,13 +20,14 @@ DYNB_SCHED_IMPROVED, DYNB_SCHED_STANDARD, DYNB_SCHED_NAIVE, DYNB_SCHED_DEPTH = 0
 DYNB_PLAN_THROUGHPUT = 8
 DYNB_PLAN_BALANCE = 4
 DYNB_PLAN_PERSISTENT = 16
+DYNB_PLAN_KEEP = 32
 ERRORS = {-1: "DYNB_E_INVAL", -2: "DYNB_E_MALFORMED", -3: "DYNB_E_NOMEM", -4: "DYNB_E_WORKSPACE",
           -5: "DYNB_E_UNSUPPORTED", -6: "DYNB_E_HIP"}
 
 EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_plan_view", "dynbatch_plan_free",
            "dynbatch_plan_device_bytes", "dynbatch_plan_upload", "dynbatch_workspace_bytes",
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
-           "dynbatch_classify_workspace_bytes", "dynbatch_classify",
+           "dynbatch_classify_workspace_bytes", "dynbatch_classify", "dynbatch_backward_workspace_bytes", "dynbatch_backward",
            "dynbatch_execute", "dynbatch_execute_check", "dynb_set_spin_limit", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
            "dynb_timing_enable", "dynb_probe_mfma_bf16", "dynb_probe_copy",
            "dynb_timing_read"]
@@ -57,6 +58,10 @@ class _Shape(ct.Structure):
 
 class _Weights(ct.Structure):
     _fields_ = [(n, ct.c_void_p) for n in ("w1", "b1", "w3a", "b3a", "w3b", "b3b", "packed")]
+
+
+class _Grads(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("dfeats", "dw1", "db1", "dw3a", "db3a", "dw3b", "db3b")]
 
 
 class _HeadShape(ct.Structure):
@@ -98,6 +103,10 @@ def _load():
     L.dynbatch_workspace_bytes.restype = ct.c_size_t
     L.dynbatch_execute.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p,
                                    ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynbatch_backward_workspace_bytes.argtypes = [ct.c_void_p, ct.POINTER(_Shape)]
+    L.dynbatch_backward_workspace_bytes.restype = ct.c_size_t
+    L.dynbatch_backward.argtypes = [ct.c_void_p, ct.POINTER(_Shape), ct.POINTER(_Weights), ct.c_void_p, ct.c_void_p, ct.c_void_p,
+                                    ct.c_void_p, ct.POINTER(_Grads), ct.c_void_p, ct.c_size_t, ct.c_void_p]
     L.dynbatch_classify_workspace_bytes.argtypes = [ct.POINTER(_HeadShape), ct.c_int32]
     L.dynbatch_classify_workspace_bytes.restype = ct.c_size_t
     L.dynbatch_classify.argtypes = [ct.POINTER(_HeadShape), ct.POINTER(_HeadWeights), ct.c_void_p, ct.c_int32, ct.c_void_p,
@@ -307,6 +316,34 @@ def dynbatch_execute_check(plan: Plan, feats, workspace, stream=None) -> None:
 
 def dynb_set_spin_limit(polls: int) -> int:
     return int(lib.dynb_set_spin_limit(int(polls)))
+
+
+# ------------------------------------------------------------------------------------------ backward pass
+def dynbatch_backward(plan: Plan, weights: dict, feats, out, forward_workspace, dout, workspace=None, stream=None) -> dict:
+    """Backward pass of an executed DYNB_PLAN_KEEP plan.  dout: device float32 [B,H,W,C].  Returns a dict of device
+    float32 tensors dfeats, dw1, db1, dw3a, db3a, dw3b, db3b in the shapes of feats and of the weights."""
+    import torch
+    shape = _shape_of(feats)
+    assert dout.is_cuda and dout.is_contiguous() and dout.dtype == torch.float32 and dout.shape == feats.shape
+    f32 = lambda t: torch.empty(t.shape, dtype=torch.float32, device=feats.device)
+    C = shape.C
+    n_types = weights["w3a"].shape[0]
+    g = dict(dfeats=f32(feats), dw3a=f32(weights["w3a"]), dw3b=f32(weights["w3b"]),
+             db3a=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
+             db3b=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
+             dw1=torch.empty((n_types, C, 2 * C), dtype=torch.float32, device=feats.device),
+             db1=torch.empty((n_types, C), dtype=torch.float32, device=feats.device))
+    if workspace is None:
+        n = int(lib.dynbatch_backward_workspace_bytes(plan.handle, ct.byref(shape)))
+        if n == 0:
+            _check(lib.dynbatch_backward(plan.handle, ct.byref(shape), None, None, None, None, None, None, None, 0, None))
+        workspace = _scratch(n, feats.device, stream)
+    gs = _Grads(*[g[k].data_ptr() for k in ("dfeats", "dw1", "db1", "dw3a", "db3a", "dw3b", "db3b")])
+    w = _weights_struct(weights)
+    _check(lib.dynbatch_backward(plan.handle, ct.byref(shape), ct.byref(w), _ptr(feats), _ptr(out), _ptr(forward_workspace),
+                                 _ptr(dout), ct.byref(gs), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream(stream)))
+    return g
 
 
 # ------------------------------------------------------------------------------------------ classifier head

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdynbatch.so")
-SOURCES = ["planner.cpp", "timing.cpp", "iep_exec.hip", "moe.hip", "head.hip", "probe.hip"]
+SOURCES = ["planner.cpp", "timing.cpp", "iep_exec.hip", "iep_backward.hip", "moe.hip", "head.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

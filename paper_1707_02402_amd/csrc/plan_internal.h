@@ -41,9 +41,24 @@ struct dynb_plan {
     // DYNB_PLAN_PERSISTENT: units of work in the order workgroups claim them: 4 * item + part, part 0 = the
     // whole node, 1 / 2 = its upper / lower half.  Every unit of a node's arguments precedes the node's units.
     std::vector<int32_t> tickets;
+    // DYNB_PLAN_KEEP: where the backward pass sends the gradient of an item's arguments, and the SCENE leaves.
+    // grad_dst0/1[item] >= 0: item that evaluates the argument; -1 - l: SCENE leaf number l (leaves are numbered
+    // example by example, in node order); unused entries are 0.
+    bool keep = false;
+    bool shared_nodes = false;           // built by dynbatch_plan_dag: a node may have several consumers
+    std::vector<int32_t> grad_dst0, grad_dst1;
+    std::vector<int32_t> leaf_first;     // [B+1] leaves of example e are leaf_first[e] .. leaf_first[e+1]
+    std::vector<int32_t> root_item;      // [B] item that evaluates the example's root, -1 if the root is a SCENE leaf
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };
+
+// Device buffer of an uploaded plan: items | ids of single-SCENE examples | arity table | tickets, each part
+// padded to 256 bytes.
+inline size_t dynb_align256(size_t v) { return (v + 255) & ~size_t(255); }
+inline size_t dynb_plan_items_bytes(const dynb_plan* p) { return dynb_align256(p->items.size() * sizeof(dynb_item)); }
+inline size_t dynb_plan_leaf_bytes(const dynb_plan* p) { return dynb_align256(p->leaf_roots.size() * sizeof(int32_t)); }
+inline size_t dynb_plan_arity_offset(const dynb_plan* p) { return dynb_plan_items_bytes(p) + dynb_plan_leaf_bytes(p); }
 
 namespace dynb {
 void set_error(const std::string& msg);

@@ -257,8 +257,9 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         // A shared node lives until its last consumer has been issued (use counts).
         // One dependency-driven launch per batch has no label boundary after which a slot could be reused:
         // every result keeps a slot of its own.
-        const bool pingpong = improved && !balance && !shared && !p->persistent;
-        const bool recycle = ((improved && balance) || by_depth || shared) && !p->persistent;
+        const bool own_slots = p->persistent || p->keep;
+        const bool pingpong = improved && !balance && !shared && !own_slots;
+        const bool recycle = ((improved && balance) || by_depth || shared) && !own_slots;
         std::vector<int32_t> uses;
         if (recycle) {
             uses.assign(N, 0);
@@ -311,6 +312,28 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         p->n_slots = pingpong ? 2 * maxw : running;
         for (const auto& l : p->launches) p->max_launch = std::max(p->max_launch, l.count);
     }
+    // 3b. routes of the backward pass: the gradient with respect to an argument goes to the item that evaluated
+    // it, or to a numbered SCENE leaf (summed per example afterwards, in leaf order)
+    if (p->keep) {
+        std::vector<int32_t> item_of(N, -1), leaf_of(N, -1);
+        for (size_t i = 0; i < p->item_node.size(); ++i) item_of[p->item_node[i]] = int32_t(i);
+        p->leaf_first.assign(size_t(B) + 1, 0);
+        int32_t n_leaf = 0;
+        for (int32_t n = 0; n < N; ++n) {                   // node ids ascend example by example
+            if (arity[p->type[n]] == 0) leaf_of[n] = n_leaf++;
+            p->leaf_first[example[n] + 1] = n_leaf;
+        }
+        for (int32_t e = 0; e < B; ++e) p->leaf_first[e + 1] = std::max(p->leaf_first[e + 1], p->leaf_first[e]);
+        auto route = [&](int32_t c) -> int32_t { return c < 0 ? 0 : (item_of[c] >= 0 ? item_of[c] : -1 - leaf_of[c]); };
+        p->grad_dst0.resize(p->items.size()); p->grad_dst1.resize(p->items.size());
+        for (size_t i = 0; i < p->items.size(); ++i) {
+            const int32_t n = p->item_node[i];
+            p->grad_dst0[i] = route(p->child0[n]);
+            p->grad_dst1[i] = route(p->child1[n]);
+        }
+        p->root_item.resize(B);
+        for (int32_t e = 0; e < B; ++e) p->root_item[e] = item_of[p->root[e]];
+    }
     // 4. units of work of the dependency-driven launch, in claim order = execution order of the items
     // (arguments always come earlier in it).  Groups that leave half of the chip idle are run with two
     // workgroups per node (upper and lower half of the map), like the per-label executor does.
@@ -336,7 +359,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
     if (out) *out = nullptr;
     if (!prog || !prog_off || !arity || !out) return fail(DYNB_E_INVAL, "dynbatch_plan: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT | DYNB_PLAN_KEEP)) return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan: unknown flag bits");
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
     // one dependency-driven launch per batch sizes its units of work by the balanced launch groups
     const bool persistent = (flags & DYNB_PLAN_PERSISTENT) != 0 && mode != DYNB_SCHED_NAIVE;
@@ -355,6 +378,7 @@ extern "C" int dynbatch_plan(const int32_t* prog, const int32_t* prog_off, int32
         p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
         p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
         p->persistent = persistent;
+        p->keep = (flags & DYNB_PLAN_KEEP) != 0;
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(prog, prog + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);
@@ -475,7 +499,7 @@ extern "C" int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const
     if (!type || !arg0 || !arg1 || !node_off || !root || !arity || !out)
         return fail(DYNB_E_INVAL, "dynbatch_plan_dag: NULL argument");
     if (B <= 0 || n_types <= 0) return fail(DYNB_E_INVAL, "dynbatch_plan_dag: B and n_types must be positive");
-    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT))
+    if (flags & ~uint32_t(DYNB_SCHED_MASK | DYNB_PLAN_BALANCE | DYNB_PLAN_THROUGHPUT | DYNB_PLAN_PERSISTENT | DYNB_PLAN_KEEP))
         return fail(DYNB_E_UNSUPPORTED, "dynbatch_plan_dag: unknown flag bits");
     const int32_t mode = int32_t(flags & DYNB_SCHED_MASK);
     if (mode != DYNB_SCHED_IMPROVED && mode != DYNB_SCHED_DEPTH)
@@ -494,6 +518,8 @@ extern "C" int dynbatch_plan_dag(const int32_t* type, const int32_t* arg0, const
         p->B = B; p->N = N; p->n_types = n_types; p->mode = mode;
         p->throughput = (flags & DYNB_PLAN_THROUGHPUT) != 0;
         p->persistent = (flags & DYNB_PLAN_PERSISTENT) != 0;
+        p->keep = (flags & DYNB_PLAN_KEEP) != 0;
+        p->shared_nodes = true;
         p->arity.assign(arity, arity + n_types);
         p->level.resize(N); p->type.assign(type, type + N);
         p->child0.resize(N); p->child1.resize(N); p->root.resize(B);

@@ -7,10 +7,15 @@ import pytest
 from workloads import iep
 
 
-def torch_tree_grads(w, dout):
-    """The programs of w from torch layers (conv2d on NCHW, cat, relu), differentiated by autograd in fp64."""
+def torch_tree_grads(w, dout, round_bf16=False):
+    """The programs of w from torch layers (conv2d on NCHW, cat, relu), differentiated by autograd in fp64.
+    round_bf16: stored activations pass through torch's own bfloat16 conversion (identity in the backward pass)."""
     import torch
     import torch.nn.functional as F
+
+    def st(x):
+        return x + (x.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64) - x.detach()) if round_bf16 else x
+
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).double().requires_grad_(True)
     feats = t(w.feats)
     P = dict(w1=t(w.w1), b1=t(w.b1), w3a=t(w.w3a), b3a=t(w.b3a), w3b=t(w.w3b), b3b=t(w.b3b))
@@ -25,11 +30,11 @@ def torch_tree_grads(w, dout):
         a, pos = ev(i, pos)
         if w.arity[ty] == 2:
             b, pos = ev(i, pos)
-            u = F.relu(F.conv2d(torch.cat([a, b], 1), P["w1"][ty][:, :, None, None], P["b1"][ty]))
+            u = st(F.relu(F.conv2d(torch.cat([a, b], 1), P["w1"][ty][:, :, None, None], P["b1"][ty])))
         else:
             u = a
-        m = F.relu(conv3(u, P["w3a"][ty], P["b3a"][ty]))
-        return F.relu(u + conv3(m, P["w3b"][ty], P["b3b"][ty])), pos
+        m = st(F.relu(conv3(u, P["w3a"][ty], P["b3a"][ty])))
+        return st(F.relu(u + conv3(m, P["w3b"][ty], P["b3b"][ty]))), pos
 
     loss = 0
     for i in range(w.B):
@@ -49,6 +54,25 @@ def test_against_torch_autograd(oracle, seed, B, C, H, W):
     dout = np.random.default_rng(seed).standard_normal(w.feats.shape).astype(np.float32)
     g = oracle.iep_backward_workload(w, dout)
     ref = torch_tree_grads(w, dout)
+    for mine, theirs in ((g.dfeats, ref["feats"]), (g.dw1, ref["w1"]), (g.db1, ref["b1"]), (g.dw3a, ref["w3a"]),
+                         (g.db3a, ref["b3a"]), (g.dw3b, ref["w3b"]), (g.db3b, ref["b3b"])):
+        scale = max(1.0, np.abs(theirs).max())
+        assert np.abs(mine - theirs).max() < 1e-11 * scale
+
+
+@pytest.mark.parametrize("seed,B,C,H,W", [(11, 4, 5, 3, 4), (12, 5, 8, 2, 2)])
+def test_bf16_storage_mode_against_torch_with_its_own_bfloat16_conversion(oracle, seed, B, C, H, W):
+    """round_bf16: the forward evaluation rounds u, mid and y to bfloat16 (checked against torch's conversion, so a
+    wrong rounding rule or a missed rounding point shows in the root maps), the gradients follow the rounded values."""
+    w = iep.small_mixed(seed=seed, B=B, C=C, H=H, W=W, dtype="bf16", min_len=1, max_len=8)
+    dout = np.random.default_rng(seed).standard_normal(w.feats.shape).astype(np.float32)
+    g = oracle.iep_backward_workload(w, dout, round_bf16=True)
+    plain = oracle.iep_backward_workload(w, dout)
+    assert np.abs(plain.roots - oracle.iep_forward_workload(w)).max() == 0          # the unrounded mode is the forward oracle
+    from workloads.rng import round_bf16
+    assert (g.roots == round_bf16(g.roots.astype(np.float32))).all()                  # root maps are bfloat16 values
+    assert 0 < np.abs(g.roots - plain.roots).max() < 2e-2 * np.abs(plain.roots).max()
+    ref = torch_tree_grads(w, dout, round_bf16=True)
     for mine, theirs in ((g.dfeats, ref["feats"]), (g.dw1, ref["w1"]), (g.db1, ref["b1"]), (g.dw3a, ref["w3a"]),
                          (g.db3a, ref["b3a"]), (g.dw3b, ref["w3b"]), (g.db3b, ref["b3b"])):
         scale = max(1.0, np.abs(theirs).max())

@@ -153,7 +153,7 @@ def test_error_codes(dyn):
     assert e.value.name == "DYNB_E_UNSUPPORTED"
     dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=dyn.DYNB_PLAN_THROUGHPUT | dyn.DYNB_PLAN_BALANCE)
     with pytest.raises(dyn.DynbError) as e:
-        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=32)
+        dyn.dynbatch_plan(ok, np.array([0, 2], np.int32), ar, flags=64)
     assert e.value.name == "DYNB_E_UNSUPPORTED"
     with pytest.raises(dyn.DynbError) as e:
         dyn.dynbatch_plan(ok, np.array([1, 2], np.int32), ar)
