@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--skip-schedules", action="store_true", help="skip the side-by-side timing of the schedules")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-peak", action="store_true")
+    ap.add_argument("--skip-extras", action="store_true", help="skip the classifier head and the backward pass")
     ap.add_argument("--moe-config", choices=["config3", "config4"], default="config4")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -278,6 +279,38 @@ def main():
         naive = {"kind": "same kernels, one launch per node, example by example", "ms_per_step": round(naive_ms, 3),
                  "module_evals_per_sec": round(n_evals / naive_ms * 1e3, 1), "speedup_batched": round(naive_ms / one_ms, 2),
                  "speedup_note": "against one batched step at a time on one stream"}
+
+    # ------------------------------------------------------------------ classifier head and backward pass (config 2)
+    extras = {}
+    if not args.skip_extras:
+        head = iep.make_head(iep.config2.__defaults__[0], w.C, w.H, w.W, 32, 256, 28, w.dtype)
+        hd = U.head_dev(head, w.dtype)
+        hws = torch.empty(dyn.dynbatch_classify_workspace_bytes(w.C, w.H, w.W, dyn.DYNB_BF16, 32, 256, 28, w.B), dtype=torch.uint8, device="cuda")
+        probs = torch.empty((w.B, 28), dtype=torch.float32, device="cuda")
+        head_ms = gpu_ms(lambda: dyn.dynbatch_classify(ref_out, hd, probs=probs, workspace=hws), K)
+        head_flops = 2.0 * w.B * (w.H * w.W * w.C * 32 + w.H * w.W * 32 * 256 + 256 * 28)
+        extras["classifier_head"] = {"shape": "conv1x1 128->32, fc 6272->256, fc 256->28, softmax, on the %d root maps" % w.B,
+                                     "ms": round(head_ms, 4), "tflops": round(head_flops / head_ms / 1e9, 2),
+                                     "share_of_a_step": round(head_ms / one_ms, 4)}
+        kplan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, base_flags | dyn.DYNB_PLAN_KEEP)
+        dyn.dynbatch_plan_upload(kplan)
+        kws = torch.empty(dyn.dynbatch_workspace_bytes(kplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+        kout = dyn.dynbatch_execute(kplan, weights, L0["feats"], workspace=kws)
+        assert torch.equal(kout, ref_out)
+        dout = torch.randn(kout.shape, dtype=torch.float32, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
+        wfull = dict(weights)
+        t0 = time.perf_counter()
+        dyn.dynbatch_backward(kplan, wfull, L0["feats"], kout, kws, dout)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dyn.dynbatch_backward(kplan, wfull, L0["feats"], kout, kws, dout)
+        torch.cuda.synchronize()
+        bwd_ms = (time.perf_counter() - t0) * 1e3
+        extras["backward"] = {"ms_per_step": round(bwd_ms, 2), "forward_ms_per_step": round(one_ms, 4),
+                              "ratio_to_forward": round(bwd_ms / one_ms, 1),
+                              "flops": 2.0 * flops_step, "tflops": round(2.0 * flops_step / bwd_ms / 1e9, 2),
+                              "kind": "plain FMA kernels (one thread per output element), parameter gradients pool by pool"}
+        del kws, kout, dout, kplan
 
     # ------------------------------------------------------------------ mixture of experts
     moe_res, moe_roof = None, []
@@ -497,7 +530,7 @@ def main():
                      "frac_of_measured_peak": None if peak is None else round(achieved_tflops / peak["mfma_bf16_tflops"], 4),
                      "configuration": "the headline's: one batch at a time on one stream; useful flops of a step / duration of its "
                                       "module-kernel launches (one HIP event pair around them on that stream)"},
-        "measured_peak": peak, "in_flight": fly,
+        "measured_peak": peak, "in_flight": fly, "classifier_head": extras.get("classifier_head"), "backward": extras.get("backward"),
         "rooflines_other": moe_roof, "schedules": sched_cmp, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
         "paper_context": "paper reports ratios only: >14x cell execution (IEP, GTX 1080 Ti), up to 1000x (MoE, 11 GB card)",
     }

@@ -140,107 +140,121 @@ __global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict_
     }
 }
 
-// acc[t][nt] += W * X over one 3x3 convolution (9 taps) or, CENTER_ONLY, over 128 channels of the
-// centre tap (one half of the 1x1 convolution).  Software pipelined by hand: the activation
-// fragments live in a ring of four register sets (one per step), the LDS reads that fill the set of
-// the step after next are interleaved one by one with the MFMAs of the current step, and the weight
-// fragments of all 8 steps
-// of a tap sit in registers: each is re-fetched from global memory one step after its last use,
-// i.e. 7 steps (> 1800 clocks) ahead of its next use.  Scheduler fences keep that order.
-// TAIL: the wave's last pixel-tile slot is shared by the four waves of a node; this wave multiplies
-// only its first channel tile (wrow[0]) of it, into acc[MTW-1][0].
-template <int MTW, bool CENTER_ONLY, int RW = 8, bool TAIL = false>
-__device__ __forceinline__ void kloop_mfma(f32x16 (&acc)[MTW][2], const uint32_t (&xaddr)[MTW], int mcount,
-                                           const bf16_t* (&wrow)[2])
+// ---- K loop -----------------------------------------------------------------------------------------
+// acc[t][nt] += W * X over one 3x3 convolution (9 taps x 8 steps of 16 input channels) or, CENTER_ONLY, over the
+// 8 steps of the centre tap (one half of the 1x1 convolution).  Software pipelined by hand:
+//   * activation fragments live in XS register sets; the LDS reads that fill the set of the step XS/2 ahead are
+//     interleaved one by one with the MFMAs of the current step, so LDS traffic is spread evenly under them;
+//   * weight fragments live in a ring of RW steps (the caller's registers); the slot of the previous step is
+//     refilled from global memory right after the first pixel tile of the current step, RW - 1 steps ahead of its
+//     use (issuing the load directly behind the MFMAs that still read the slot would stall the wave);
+//   * scheduler fences keep that order (the compiler would otherwise sink every load to its use).
+// The ring is filled by ring_fill, a call of its own so that the caller can issue it long before the loop; the
+// last chunk refills the ring with the first fragments of the NEXT loop (wnext), which then starts full.
+// Measured on this chip: a workgroup receives about 27 bytes per clock of weight fragments whatever the
+// look-ahead, so a loop is only MFMA-bound if every fragment is fetched once per workgroup: each wave owns one
+// channel tile (32 output channels) and all pixel tiles of its node (NT = 1); with two nodes per workgroup a
+// wave owns two channel tiles of one node (NT = 2).
+template <int NT, int RW>
+__device__ __forceinline__ void ring_fill(bf16x8 (&wf)[RW][NT], const bf16_t* (&wrow)[NT])
 {
-    // wrow[nt] points at this lane's 8 values of the first fragment of channel tile nt in the packed
-    // weights; fragment (tap, j) follows at (tap*8 + j) * 512 elements
-    constexpr int NTAP = CENTER_ONLY ? 1 : 9;
-    static_assert(RW == 8 || RW == 4, "weight ring of 4 or 8 steps");
-    bf16x8 x[4][MTW], wf[RW][2];
-    auto tap_off = [](int tap) -> uint32_t {
-        return CENTER_ONLY ? uint32_t(mf::CENTER) : uint32_t((tap / 3) * mf::ROW_BYTES + (tap % 3) * mf::PIX_BYTES);
-    };
-    auto load_w = [&](bf16x8 (&w)[2], int off) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) w[nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + off);
-    };
-    // One K-step: the MFMAs of pixel tile t read xc[t]; the LDS read that fills xn[t] for the step
-    // after next is issued right before them, so LDS traffic is spread evenly under the MFMAs.
-    // The weight slot used by the previous step is refilled after the first pixel tile: issuing that
-    // load directly behind the MFMAs that still read the slot would stall the wave until they retire.
-    auto step = [&](const bf16x8 (&xc)[MTW], bf16x8 (&xn)[MTW], uint32_t noff, const bf16x8 (&w)[2],
-                    bf16x8 (&wrefill)[2], int refill_off) {
-#pragma unroll
-        for (int t = 0; t < MTW; ++t) {
-            if (t < mcount) {
-                xn[t] = lds_read_frag(xaddr[t] + noff);
-                if (TAIL && t == MTW - 1) {
-                    acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[0], xc[t], acc[t][0], 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[nt], xc[t], acc[t][nt], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (t == 0) {
-                load_w(wrefill, refill_off);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    };
-    // The prologue issues its loads in exactly the order the loop body does (fences again), so that
-    // the wait counts the compiler derives for the loop entry and for the back edge agree and stay
-    // as loose as the ring allows.  Slot 7 is filled by the first step of the loop.
 #pragma unroll
     for (int j = 0; j < RW - 1; ++j) {
-        load_w(wf[j], j * mf::FRAG);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wf[j][nt] = *reinterpret_cast<const bf16x8*>(wrow[nt] + j * mf::FRAG);
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+template <int MTW, int NT, int RW, int XS, bool CENTER_ONLY>
+__device__ __forceinline__ void kloop(f32x16 (&acc)[MTW][NT], const uint32_t (&xaddr)[MTW], bf16x8 (&wf)[RW][NT],
+                                      const bf16_t* (&wrow)[NT], const bf16_t* (&wnext)[NT])
+{
+    constexpr int NSTEP = CENTER_ONLY ? 8 : 72;
+    constexpr int NCHUNK = NSTEP / RW, XA = XS / 2;
+    static_assert(NSTEP % RW == 0 && RW % 8 == 0 && RW % XS == 0 && (XS == 2 || XS == 4), "ring shapes");
+    static_assert(RW == 8 || RW == 24, "a chunk is one tap or one kernel row");
+    // byte offset of step j (0 .. RW) of a chunk from the chunk's first tap: taps advance by a pixel, steps by 16 bytes
+    auto in_chunk = [](int j) -> uint32_t { return uint32_t((j / 8) * mf::PIX_BYTES + (j % 8) * 16); };
+    auto chunk_base = [](int c) -> uint32_t {
+        if (CENTER_ONLY) return uint32_t(mf::CENTER);
+        if (RW == 24) return uint32_t(c) * mf::ROW_BYTES;
+        return uint32_t(c / 3) * mf::ROW_BYTES + uint32_t(c % 3) * mf::PIX_BYTES;
+    };
+    bf16x8 x[XS][MTW];
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
+    for (int jj = 0; jj < XA; ++jj)
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            if (t < mcount) x[jj][t] = lds_read_frag(xaddr[t] + tap_off(0) + jj * 16);
+            x[jj][t] = lds_read_frag(xaddr[t] + chunk_base(0) + in_chunk(jj));
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll 1
-    for (int tap = 0; tap < NTAP; ++tap) {
-        const int ntap = tap + 1 < NTAP ? tap + 1 : tap;      // the last prefetches re-read valid data
-        const uint32_t xo = tap_off(tap), nxo = tap_off(ntap);
-        const int wo = tap * 8 * mf::FRAG, nwo = ntap * 8 * mf::FRAG;
+    for (int c = 0; c < NCHUNK; ++c) {
+        const bool last = c + 1 >= NCHUNK;
+        uint32_t xa[MTW], xn[MTW];                      // this chunk's and the next chunk's activations
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            step(x[j & 3], x[(j + 2) & 3], j + 2 < 8 ? xo + (j + 2) * 16 : nxo + (j + 2 - 8) * 16, wf[j % RW],
-                 wf[(j + RW - 1) % RW], j + RW - 1 < 8 ? wo + (j + RW - 1) * mf::FRAG : nwo + (j + RW - 1 - 8) * mf::FRAG);
+        for (int t = 0; t < MTW; ++t) {
+            xa[t] = xaddr[t] + chunk_base(c);
+            xn[t] = xaddr[t] + chunk_base(last ? c : c + 1);        // after the last chunk: re-read valid data
+        }
+        const bf16_t* cur[NT];                          // fragment RW - 1 of this chunk
+        const bf16_t* nxt[NT];                          // fragments 0 .. RW - 2 of the next chunk / the next loop
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            cur[nt] = wrow[nt] + (c * RW + RW - 1) * mf::FRAG;
+            nxt[nt] = last ? wnext[nt] : wrow[nt] + (c + 1) * RW * mf::FRAG;
+        }
+#pragma unroll
+        for (int j = 0; j < RW; ++j) {
+            const int ja = j + XA;                      // the step whose activations are fetched now
+#pragma unroll
+            for (int t = 0; t < MTW; ++t) {
+                x[ja % XS][t] = lds_read_frag(ja >= RW ? xn[t] + in_chunk(ja - RW) : xa[t] + in_chunk(ja));
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][nt], x[j % XS][t], acc[t][nt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t == 0) {                           // refill the slot of the previous step
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        wf[(j + RW - 1) % RW][nt] = j == 0 ? *reinterpret_cast<const bf16x8*>(cur[nt])
+                                                           : *reinterpret_cast<const bf16x8*>(nxt[nt] + (j - 1) * mf::FRAG);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
     }
 }
 
 // WM selects how a node is spread over waves and workgroups.
-//   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles
-//           each): best throughput per CU, used for the widest launch groups.
-//   WM = 2: one node per workgroup, shared by 4 waves (64 channels x 3 pixel tiles, plus 32 channels
-//           of the seventh pixel tile: 7 MFMA tiles per wave).
-//   WM = 3: half a node per workgroup: output rows 0..6 or 7..13.  The workgroup convolves an 8-row
-//           window (rows 0..7 or 6..13: the second conv needs one row of the first conv's output
-//           beyond its own rows), i.e. 112 pixels = 4 pixel tiles, 2 per wave.  Two CUs share a node,
-//           which halves the latency of narrow launch groups at the price of 8/7 of the MFMA work.
-//   WM = 4: the layout of WM = 2 inside at most 256 registers (weight ring of 4 steps), so that two
-//           workgroups share a CU and one's staging, swap and epilogue run under the other's MFMAs.
+//   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles each): most
+//           MFMAs per operand byte, used for the widest launch groups.
+//   WM = 2: one node per workgroup: wave w owns channel tile w (32 channels) and all 7 pixel tiles.
+//   WM = 3: half a node per workgroup: output rows 0..6 or 7..13.  The workgroup convolves an 8-row window (rows
+//           0..7 or 6..13: the second conv needs one row of the first conv's output beyond its own rows), i.e. 112
+//           pixels = 4 pixel tiles; wave w owns channel tile w of all four.  Two CUs share a node, which halves the
+//           latency of narrow launch groups at the price of 8/7 of the MFMA work.
+//   WM = 4: the layout of WM = 2 inside at most 256 registers (two sets of activation fragments instead of four),
+//           so that two workgroups share a CU and one's staging, swap and epilogue run under the other's MFMAs.
+// WM = 2 and 3 own a CU (up to 512 registers per lane) and, unless ALLOW_DEEP is off, keep a weight ring of 24
+// steps that is filled before the argument map is staged.
 // One workgroup's share of a launch group: position `logical` (a node, half a node or a pair of nodes,
 // depending on the layout) of the items a.items[0 .. a.count).
-template <int WMODE>
+template <int WMODE, bool ALLOW_DEEP = true>
 __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 {
     using namespace mf;
     constexpr int WM = (WMODE == 4) ? 2 : WMODE;
-    constexpr int RW = (WMODE == 4) ? 4 : 8;   // weight ring depth in K-steps
     constexpr int NPW = (WM == 1) ? 2 : 1;    // nodes per workgroup
     constexpr int WPN = 4 / NPW;              // waves per node
-    constexpr int MTW = (WM == 1) ? 7 : (WM == 2 ? 4 : 2);    // pixel tiles per wave (upper bound)
-    constexpr int NTHR = 64 * WPN;            // threads that stage one node
+    constexpr int NT = (WM == 1) ? 2 : 1;     // channel tiles per wave
     constexpr bool HALF = (WM == 3);
+    constexpr int MTW = HALF ? 4 : MT7;       // pixel tiles per wave: all of the node's (or of the half node's window)
+    constexpr int NTHR = 64 * WPN;            // threads that stage one node
+    constexpr bool DEEP = ALLOW_DEEP && (WMODE == 2 || WMODE == 3);
+    constexpr int RW = DEEP ? 24 : 8;         // weight ring depth in K-steps
+    constexpr int XS = (WMODE == 4 || WMODE == 1) ? 2 : 4;  // register sets of activation fragments (look-ahead of XS / 2 steps)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
     const int first = HALF ? (logical >> 1) : logical * NPW;
@@ -259,18 +273,20 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
     const bool binary = active && a.arity[it.type] == 2;
     const uint32_t tile = uint32_t(node_local) * TILE_BYTES;
     const int r = lane & 31, h = lane >> 5;
-    const int n0 = (wi & 1) * 64;             // first output channel of this wave
-    // One node per workgroup: 7 pixel tiles x 4 channel tiles = 28 MFMA tiles for 4 waves.  Wave
-    // (pixel group pg, channel half) owns pixel tiles 3 pg .. 3 pg + 2 for its 64 channels and, in its
-    // fourth slot, one 32-channel quarter of pixel tile 6: 7 MFMA tiles per wave, the four SIMDs of
-    // the CU carry the same load.
-    constexpr bool TAIL = (WM == 2);
-    const int pg = wi >> 1;
-    const int m0 = TAIL ? pg * 3 : pg * MTW;  // first pixel tile of this wave
-    const int mcount = MTW;
-    auto tile_of = [&](int t) -> int { return (TAIL && t == MTW - 1) ? MT7 - 1 : m0 + t; };
-    // first channel of accumulator acc[t][nt], and whether this wave owns it
-    auto live = [&](int t, int nt) -> bool { return !(TAIL && t == MTW - 1 && nt == 1); };
+    const int n0 = wi * 32 * NT;              // first output channel of this wave
+
+    // packed weights of this wave's channel tiles: fragment (tap, j) of a conv follows at (tap*8 + j) * FRAG
+    const bf16_t* wrow_a[NT];
+    const bf16_t* wrow_b[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const size_t frag0 = (size_t(it.type) * 4 + (n0 >> 5) + nt) * 9 * 8;
+        wrow_a[nt] = a.w3a + frag0 * FRAG + lane * 8;
+        wrow_b[nt] = a.w3b + frag0 * FRAG + lane * 8;
+    }
+    bf16x8 ring[RW][NT];
+    if constexpr (DEEP)
+        if (!a.any_binary) ring_fill<NT, RW>(ring, wrow_a);        // first of all: they take > 2000 clocks to arrive
 
     // ---- gather: zero border once, then the argument map into the centre of the halo tile;
     // all global loads of the map are issued before the first LDS write, so one memory latency is paid
@@ -317,41 +333,27 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
     uint32_t xaddr[MTW];
 #pragma unroll
     for (int t = 0; t < MTW; ++t) {
-        const int p = wrow0 * S + min(tile_of(t) * 32 + r, NPIX - 1);
+        const int p = wrow0 * S + min(t * 32 + r, NPIX - 1);
         xaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
     }
     // this lane's 16 accumulator elements of channel tile nt are channels n0 + nt*32 + 16*h + (0..15)
     // (the packed weights carry the matching row permutation)
-    const int cbase = n0 + 16 * h;
-    // A wave's two channel tiles are numbered so that its quarter of the shared pixel tile is tile 0:
-    // waves of pixel group 1 take their channel tiles in swapped order.
-    const int ntswap = TAIL ? pg : 0;
-    auto chan = [&](int nt) -> int { return cbase + ((nt ^ ntswap) * 32); };
-    f32x16 acc[MTW][2];
+    auto chan = [&](int nt) -> int { return n0 + nt * 32 + 16 * h; };
+    f32x16 acc[MTW][NT];
 
-    constexpr int NFULL = (WM == 2) ? MTW - 1 : MTW;          // slots that hold both channel tiles
     auto init_bias = [&](const float* bias) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
                 if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan(nt) + b * 4);
 #pragma unroll
-                for (int t = 0; t < NFULL; ++t) {
+                for (int t = 0; t < MTW; ++t) {
                     acc[t][nt][4 * b + 0] = v.x; acc[t][nt][4 * b + 1] = v.y;
                     acc[t][nt][4 * b + 2] = v.z; acc[t][nt][4 * b + 3] = v.w;
                 }
             }
-        if (NFULL < MTW) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan(0) + b * 4);
-                acc[MTW - 1][0][4 * b + 0] = v.x; acc[MTW - 1][0][4 * b + 1] = v.y;
-                acc[MTW - 1][0][4 * b + 2] = v.z; acc[MTW - 1][0][4 * b + 3] = v.w;
-            }
-        }
     };
     // byte address of this lane's centre pixel of tile t (channel 0)
     auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
@@ -378,37 +380,43 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
         uint32_t uaddr[MTW];
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            const int p = urow0 * S + min(tile_of(t) * 32 + r, UPIX - 1);
+            const int p = urow0 * S + min(t * 32 + r, UPIX - 1);
             uaddr[t] = tile + uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
         }
-        const bf16_t* w1row[2];
+        const bf16_t* w1row[NT];                          // first half of the 1x1 weights (argument 0), then the second
+        const bf16_t* w1row2[NT];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-            w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 2 * 8) * FRAG + lane * 8;
+        for (int nt = 0; nt < NT; ++nt) {
+            w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
+            w1row2[nt] = w1row[nt] + 8 * FRAG;
+        }
+        // one channel tile per wave: the second half's fragments are fetched under the first half's loop and wait in
+        // the ring while the second argument is staged; with two channel tiles the registers do not allow that
+        constexpr bool CARRY = (NT == 1);
+        bf16x8 ring1[8][NT];
         if (binary) {
+            ring_fill<NT, 8>(ring1, w1row);
             init_bias(a.b1);
-            kloop_mfma<MTW, true, RW, TAIL>(acc, uaddr, mcount, w1row);
+            kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row, CARRY ? w1row2 : w1row);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
         __syncthreads();
         if (binary) {
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) w1row[nt] += 8 * FRAG;
-            kloop_mfma<MTW, true, RW, TAIL>(acc, uaddr, mcount, w1row);
+            if (!CARRY) ring_fill<NT, 8>(ring1, w1row2);
+            kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row2, w1row2);
         }
         __syncthreads();
         if (binary) {                                     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
 #pragma unroll
             for (int t = 0; t < MTW; ++t)
-                if (t < mcount && tile_of(t) * 32 + r < UPIX) {
+                if (t * 32 + r < UPIX) {
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
+                    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                         for (int q = 0; q < 2; ++q)
-                            if (live(t, nt))
-                                *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
-                                                          uint32_t((chan(nt) + q * 8) * 2)) = packed(t, nt, q);
+                            *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
+                                                      uint32_t((chan(nt) + q * 8) * 2)) = packed(t, nt, q);
                 }
         }
         __syncthreads();
@@ -416,13 +424,10 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 
     // ---- first conv3x3 + ReLU, result replaces the tile; the old centre values become the residual
     PHASE(3);
-    const bf16_t* wrow[2];
     if (active) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-            wrow[nt] = a.w3a + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 9 * 8) * FRAG + lane * 8;
+        if (!DEEP || a.any_binary) ring_fill<NT, RW>(ring, wrow_a);   // (after the 1x1 convolution, whose loops need the registers)
         init_bias(a.b3a);
-        kloop_mfma<MTW, false, RW, TAIL>(acc, xaddr, mcount, wrow);
+        kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_a, wrow_b);   // leaves the ring filled for the second conv
     }
     PHASE(4);
     __syncthreads();
@@ -452,23 +457,15 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
             acc[t][nt][8 * q + 7] = __uint_as_float(res.w & 0xffff0000u) + bhi.w;
         };
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 f32x4 blo, bhi;
                 bias8(chan(nt) + q * 8, blo, bhi);
 #pragma unroll
-                for (int t = 0; t < NFULL; ++t)
-                    if (t < mcount && tile_of(t) * 32 + r < NPIX) swap8(t, nt, q, blo, bhi);
+                for (int t = 0; t < MTW; ++t)
+                    if (t * 32 + r < NPIX) swap8(t, nt, q, blo, bhi);
             }
-        if (TAIL && tile_of(MTW - 1) * 32 + r < NPIX) {
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                f32x4 blo, bhi;
-                bias8(chan(0) + q * 8, blo, bhi);
-                swap8(MTW - 1, 0, q, blo, bhi);
-            }
-        }
     }
     PHASE(6);
     __syncthreads();
@@ -476,23 +473,19 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 
     // ---- second conv3x3 on top of (residual + bias), ReLU, scatter
     if (active) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-            wrow[nt] = a.w3b + ((size_t(it.type) * 4 + (n0 >> 5) + (nt ^ ntswap)) * 9 * 8) * FRAG + lane * 8;
-        kloop_mfma<MTW, false, RW, TAIL>(acc, xaddr, mcount, wrow);
+        kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_b, wrow_b);
         PHASE(8);
         bf16_t* dst = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
-            const int pl = tile_of(t) * 32 + r;
+            const int pl = t * 32 + r;
             const int p = wrow0 * S + pl;
-            if (t < mcount && pl < NPIX && p >= orow0 * S && p < orow1 * S) {
+            if (pl < NPIX && p >= orow0 * S && p < orow1 * S) {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
-                        if (live(t, nt))
-                            *reinterpret_cast<u32x4*>(dst + size_t(p) * C + chan(nt) + q * 8) = packed(t, nt, q);
+                        *reinterpret_cast<u32x4*>(dst + size_t(p) * C + chan(nt) + q * 8) = packed(t, nt, q);
             }
         }
     }
@@ -576,8 +569,8 @@ __global__ __launch_bounds__(256, 1) void k_module_persist(MfArgs a, PersistArgs
         b.count = 1;
         b.any_binary = (a.arity[b.items[0].type] == 2);
         const int part = t & 3;
-        if (part == 0) module_body<2>(b, 0);
-        else module_body<3>(b, part - 1);
+        if (part == 0) module_body<2, false>(b, 0);          // both layouts in one kernel: the shallow weight ring fits
+        else module_body<3, false>(b, part - 1);
         // Publish: every wave waits until its stores of the result have reached the L2 (all waves of a
         // workgroup sit behind the same one), then one thread writes that L2's dirty lines back to memory,
         // where every CU can see them, and raises the flag (the agent-scope release does both).
