@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-peak", action="store_true")
     ap.add_argument("--skip-extras", action="store_true", help="skip the classifier head and the backward pass")
+    ap.add_argument("--wide-nodes", type=int, default=4096, help="nodes of the single wide launch group (0 = skip)")
     ap.add_argument("--moe-config", choices=["config3", "config4"], default="config4")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -279,6 +280,29 @@ def main():
         naive = {"kind": "same kernels, one launch per node, example by example", "ms_per_step": round(naive_ms, 3),
                  "module_evals_per_sec": round(n_evals / naive_ms * 1e3, 1), "speedup_batched": round(naive_ms / one_ms, 2),
                  "speedup_note": "against one batched step at a time on one stream"}
+
+    # ------------------------------------------------------------------ one wide launch group (the module kernel at full width)
+    wide = None
+    if args.wide_nodes > 0:
+        nw = args.wide_nodes
+        n_un = int((w.arity == 1).sum())
+        wprog = np.empty(2 * nw, np.int32)
+        wprog[0::2] = 1 + np.arange(nw) % n_un                    # one one-argument module per program, functions in turn
+        wprog[1::2] = 0
+        woff = (2 * np.arange(nw + 1)).astype(np.int32)
+        wfeats = L0["feats"].repeat((nw + w.B - 1) // w.B, 1, 1, 1)[:nw].contiguous()
+        wout = torch.empty_like(wfeats)
+        wide = {"nodes": nw, "programs": "one one-argument module per program, the %d one-argument functions in turn" % n_un}
+        for name, fl_ in (("throughput layout (two workgroups per CU)", dyn.DYNB_PLAN_THROUGHPUT), ("latency layouts", 0)):
+            wplan = dyn.dynbatch_plan(wprog, woff, w.arity, fl_)
+            dyn.dynbatch_plan_upload(wplan)
+            wws = torch.empty(dyn.dynbatch_workspace_bytes(wplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+            ms_ = gpu_ms(lambda: dyn.dynbatch_execute(wplan, weights, wfeats, wout, wws), K)
+            tf = nw * FLOP_UNARY / ms_ / 1e9
+            wide[name] = {"ms": round(ms_, 4), "tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                          "frac_of_measured_peak": None if peak is None else round(tf / peak["mfma_bf16_tflops"], 4)}
+            del wws, wplan
+        del wfeats, wout
 
     # ------------------------------------------------------------------ classifier head and backward pass (config 2)
     extras = {}
@@ -530,7 +554,7 @@ def main():
                      "frac_of_measured_peak": None if peak is None else round(achieved_tflops / peak["mfma_bf16_tflops"], 4),
                      "configuration": "the headline's: one batch at a time on one stream; useful flops of a step / duration of its "
                                       "module-kernel launches (one HIP event pair around them on that stream)"},
-        "measured_peak": peak, "in_flight": fly, "classifier_head": extras.get("classifier_head"), "backward": extras.get("backward"),
+        "measured_peak": peak, "in_flight": fly, "wide_launch": wide, "classifier_head": extras.get("classifier_head"), "backward": extras.get("backward"),
         "rooflines_other": moe_roof, "schedules": sched_cmp, "moe": moe_res, "naive_gpu": naive, "cpu_baseline": cpu,
         "paper_context": "paper reports ratios only: >14x cell execution (IEP, GTX 1080 Ti), up to 1000x (MoE, 11 GB card)",
     }

@@ -3,7 +3,7 @@
 //
 // Two kernel families with the same semantics:
 //   * k_module_mfma  — bf16, C = 128, 14 x 14: one fused kernel per launch group.  A workgroup
-//                      owns one or two nodes; the node's input map is gathered straight into an
+//                      owns a node or half a node; the node's input map is gathered straight into an
 //                      LDS halo tile, conv1x1 (binary functions), conv3x3, ReLU, conv3x3, residual
 //                      add and ReLU all run from that tile on MFMA, and the result is scattered to
 //                      the node's slot (or to the output tensor for a root).
@@ -154,7 +154,7 @@ __global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict_
 // Measured on this chip: a workgroup receives about 27 bytes per clock of weight fragments whatever the
 // look-ahead, so a loop is only MFMA-bound if every fragment is fetched once per workgroup: each wave owns one
 // channel tile (32 output channels) and all pixel tiles of its node (NT = 1); with two nodes per workgroup a
-// wave owns two channel tiles of one node (NT = 2).
+// wave would own NT = 2 channel tiles of one node.
 template <int NT, int RW>
 __device__ __forceinline__ void ring_fill(bf16x8 (&wf)[RW][NT], const bf16_t* (&wrow)[NT])
 {
@@ -227,9 +227,7 @@ __device__ __forceinline__ void kloop(f32x16 (&acc)[MTW][NT], const uint32_t (&x
     }
 }
 
-// WM selects how a node is spread over waves and workgroups.
-//   WM = 1: two nodes per workgroup, a node is shared by 2 waves (64 channels x all 7 pixel tiles each): most
-//           MFMAs per operand byte, used for the widest launch groups.
+// WM selects how a node is spread over workgroups.
 //   WM = 2: one node per workgroup: wave w owns channel tile w (32 channels) and all 7 pixel tiles.
 //   WM = 3: half a node per workgroup: output rows 0..6 or 7..13.  The workgroup convolves an 8-row window (rows
 //           0..7 or 6..13: the second conv needs one row of the first conv's output beyond its own rows), i.e. 112
@@ -245,16 +243,17 @@ template <int WMODE, bool ALLOW_DEEP = true>
 __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 {
     using namespace mf;
+    static_assert(WMODE == 2 || WMODE == 3 || WMODE == 4, "layouts");
     constexpr int WM = (WMODE == 4) ? 2 : WMODE;
-    constexpr int NPW = (WM == 1) ? 2 : 1;    // nodes per workgroup
-    constexpr int WPN = 4 / NPW;              // waves per node
-    constexpr int NT = (WM == 1) ? 2 : 1;     // channel tiles per wave
+    constexpr int NPW = 1;                    // nodes per workgroup
+    constexpr int WPN = 4;                    // waves per node
+    constexpr int NT = 1;                     // channel tiles per wave
     constexpr bool HALF = (WM == 3);
     constexpr int MTW = HALF ? 4 : MT7;       // pixel tiles per wave: all of the node's (or of the half node's window)
     constexpr int NTHR = 64 * WPN;            // threads that stage one node
     constexpr bool DEEP = ALLOW_DEEP && (WMODE == 2 || WMODE == 3);
     constexpr int RW = DEEP ? 24 : 8;         // weight ring depth in K-steps
-    constexpr int XS = (WMODE == 4 || WMODE == 1) ? 2 : 4;  // register sets of activation fragments (look-ahead of XS / 2 steps)
+    constexpr int XS = (WMODE == 4) ? 2 : 4;  // register sets of activation fragments (look-ahead of XS / 2 steps)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
     const int first = HALF ? (logical >> 1) : logical * NPW;
@@ -285,26 +284,26 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
         wrow_b[nt] = a.w3b + frag0 * FRAG + lane * 8;
     }
     bf16x8 ring[RW][NT];
-    if constexpr (DEEP)
-        if (!a.any_binary) ring_fill<NT, RW>(ring, wrow_a);        // first of all: they take > 2000 clocks to arrive
 
     // ---- gather: zero border once, then the argument map into the centre of the halo tile;
     // all global loads of the map are issued before the first LDS write, so one memory latency is paid
     const int tl = tid % NTHR;
-    auto stage = [&](const bf16_t* src) {
-        // rows of the argument map that the window's 3x3 taps can touch
-        const int srow0 = wrow0 > 0 ? wrow0 - 1 : 0;
-        const int srow1 = wrow0 + wrows + 1 < S ? wrow0 + wrows + 1 : S;
-        constexpr int MAXPIECES = (HALF ? 9 : S) * S * 16;
-        constexpr int NIT = (MAXPIECES + NTHR - 1) / NTHR;
-        const int c_lo = srow0 * S * 16, c_hi = srow1 * S * 16;
+    // rows of the argument map that the window's 3x3 taps can touch
+    const int srow0 = wrow0 > 0 ? wrow0 - 1 : 0;
+    const int srow1 = wrow0 + wrows + 1 < S ? wrow0 + wrows + 1 : S;
+    constexpr int MAXPIECES = (HALF ? 9 : S) * S * 16;
+    constexpr int NIT = (MAXPIECES + NTHR - 1) / NTHR;
+    const int c_lo = srow0 * S * 16, c_hi = srow1 * S * 16;
+    u32x4 tmp[NIT];
+    auto stage_load = [&](const bf16_t* src) {
         const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
-        u32x4 tmp[NIT];
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = c_lo + tl + i * NTHR;
             if (c < c_hi) tmp[i] = s4[c];
         }
+    };
+    auto stage_store = [&]() {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = c_lo + tl + i * NTHR;
@@ -315,6 +314,13 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
             }
         }
     };
+    auto stage = [&](const bf16_t* src) { stage_load(src); stage_store(); };
+    // Loads return in the order they were issued: the argument map (needed first) goes ahead of the weight ring,
+    // whose fragments then arrive while the map is written to the tile.
+    if (active) stage_load(it.src0 >= 0 ? a.slots + size_t(it.src0) * (P * C) : a.feats + size_t(-1 - it.src0) * (P * C));
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DEEP)
+        if (!a.any_binary) ring_fill<NT, RW>(ring, wrow_a);
     if (active) {
         for (int c = tl; c < 60 * 16; c += NTHR) {
             const int q = c >> 4, part = c & 15;
@@ -325,7 +331,7 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
             *reinterpret_cast<u32x4*>(lds_raw + tile + uint32_t(row * ROW_BYTES + col * PIX_BYTES + part * 16)) =
                 u32x4{0u, 0u, 0u, 0u};
         }
-        stage(it.src0 >= 0 ? a.slots + size_t(it.src0) * (P * C) : a.feats + size_t(-1 - it.src0) * (P * C));
+        stage_store();
     }
 
     // per-lane LDS addresses: top-left tap of the pixel this lane feeds to the MFMA B operand,
@@ -390,22 +396,18 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
             w1row[nt] = a.w1 + ((size_t(it.type) * 4 + (n0 >> 5) + nt) * 2 * 8) * FRAG + lane * 8;
             w1row2[nt] = w1row[nt] + 8 * FRAG;
         }
-        // one channel tile per wave: the second half's fragments are fetched under the first half's loop and wait in
-        // the ring while the second argument is staged; with two channel tiles the registers do not allow that
-        constexpr bool CARRY = (NT == 1);
+        // the second half's fragments are fetched under the first half's loop and wait in the ring while the second
+        // argument is staged
         bf16x8 ring1[8][NT];
         if (binary) {
             ring_fill<NT, 8>(ring1, w1row);
             init_bias(a.b1);
-            kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row, CARRY ? w1row2 : w1row);
+            kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row, w1row2);
         }
         __syncthreads();
         if (binary) stage(it.src1 >= 0 ? a.slots + size_t(it.src1) * (P * C) : a.feats + size_t(-1 - it.src1) * (P * C));
         __syncthreads();
-        if (binary) {
-            if (!CARRY) ring_fill<NT, 8>(ring1, w1row2);
-            kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row2, w1row2);
-        }
+        if (binary) kloop<MTW, NT, 8, XS, true>(acc, uaddr, ring1, w1row2, w1row2);
         __syncthreads();
         if (binary) {                                     // ReLU(acc) -> bf16 -> centre of the halo tile (in place)
 #pragma unroll
@@ -750,9 +752,6 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<4>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<4>)");
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
-                "hipFuncSetAttribute(k_module_mfma<1>)");
         attr_set.fetch_or(uint64_t(1) << (dev & 63));
     }
     const char* d = static_cast<const char*>(p->dev_buf);
@@ -805,23 +804,20 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         a.count = l.count;
         a.any_binary = l.any_binary;
         // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
-        // workgroup up to 256 nodes, two nodes per workgroup (highest throughput per CU) beyond that
-        // (with several batches in flight the narrow groups of different batches share the chip instead:
-        // one node per workgroup in the 256-register variant, two workgroups per CU)
-        int wm = p->throughput ? 4 : (l.count <= 128) ? 3 : (l.count <= 256) ? 2 : 1;
+        // workgroup up to 256 nodes; beyond that, and whenever several batches are in flight (their narrow
+        // groups share the chip), the 256-register variant with two workgroups per CU
+        int wm = (p->throughput || l.count > 256) ? 4 : (l.count <= 128) ? 3 : 2;
 #ifdef DYNB_PHASE_CLOCKS
         if (const char* f = getenv("DYNB_FORCE_WM")) wm = atoi(f);
 #endif
-        const int nwg = (wm == 1) ? (l.count + 1) / 2 : (wm == 3) ? 2 * l.count : l.count;
+        const int nwg = (wm == 3) ? 2 * l.count : l.count;
         const unsigned grid = unsigned((nwg + 7) / 8 * 8);
         if (wm == 4)
             hipLaunchKernelGGL((k_module_mfma<4>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else if (wm == 3)
             hipLaunchKernelGGL((k_module_mfma<3>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
-        else if (wm == 2)
-            hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else
-            hipLaunchKernelGGL((k_module_mfma<1>), dim3(grid), dim3(256), 2 * mf::TILE_BYTES, st, a);
+            hipLaunchKernelGGL((k_module_mfma<2>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         if (timed && !coarse) dynb::timing_mark(st, int32_t(&l - p->launches.data()), l.count);
     }
     if (coarse) dynb::timing_mark(st, 0, evals);

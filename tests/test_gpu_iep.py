@@ -59,8 +59,8 @@ def test_mfma_path_small_batch_every_element(dyn, util, oracle, flags):
         assert util.normwise(got[i], ref[i]) < TOL["bf16"], (i, util.normwise(got[i], ref[i]))
 
 
-def test_mfma_path_wide_level_uses_two_nodes_per_workgroup(dyn, util, oracle):
-    """More than 256 nodes in one launch group selects the two-node kernel; sampled examples vs oracle."""
+def test_mfma_path_launch_group_wider_than_the_chip(dyn, util, oracle):
+    """More than 256 nodes in one launch group selects the layout with two workgroups per CU; sampled examples vs oracle."""
     w = iep.small_mixed(seed=5, B=701, C=128, H=14, W=14, dtype="bf16", min_len=2, max_len=4)
     v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity))
     assert v.max_launch_nodes > 512 and v.max_launch_nodes % 2 == 1
