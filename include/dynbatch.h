@@ -292,8 +292,10 @@ size_t dynbatch_backward_workspace_bytes(const dynb_plan* plan, const dynb_shape
  *   dout               device [B][H][W][C] fp32
  *   grads              host struct of device pointers
  *   workspace          device, >= dynbatch_backward_workspace_bytes, 256-byte aligned, scratch
- * Any shape and both dtypes; the kernels are plain FMA kernels (one thread per output element); every sum
- * has a fixed order, so two calls give the same bits.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small, plan
+ * Any shape and both dtypes.  bf16 with C = 128 and 14 x 14 maps (the shape of the fused forward kernels) runs on
+ * MFMAs: gradients travel between nodes as fp32 maps and enter the contractions rounded to bf16, like every other
+ * operand of that path.  Other shapes run plain FMA kernels (one thread per output element, fp32 gradients
+ * throughout).  Every sum has a fixed order, so two calls give the same bits.  Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small, plan
  * not uploaded), DYNB_E_UNSUPPORTED (plan without DYNB_PLAN_KEEP, dependency graphs, dtype), DYNB_E_HIP. */
 int dynbatch_backward(const dynb_plan* plan, const dynb_shape* shape, const dynb_module_weights* w, const void* feats,
                       const void* out, const void* forward_workspace, const float* dout, const dynb_module_grads* grads,

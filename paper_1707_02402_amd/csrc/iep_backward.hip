@@ -14,15 +14,19 @@
 //     da0  = W1[:, :C]^T dc,  da1 = W1[:, C:]^T dc
 // The node results y come from the forward pass (a plan made with DYNB_PLAN_KEEP leaves every one of them in the
 // workspace); u of two-argument functions and mid are recomputed with the forward pass's generic kernels.
-// Generic kernels: any shape, fp32 or bf16 values and weights, fp32 gradients, one thread per output element.
+// Two kernel families with the same semantics, like the forward pass: MFMA kernels for bf16, C = 128, 14 x 14 (further
+// down), and generic kernels for any shape, fp32 or bf16 values and weights, fp32 gradients, one thread per output
+// element, which recompute u and mid with the forward pass's generic kernels.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <string>
 #include <vector>
 
 #include "device_utils.h"
 #include "iep_generic.h"
+#include "iep_mfma.h"
 #include "plan_internal.h"
 
 using dynb::fail;
@@ -240,6 +244,515 @@ __global__ void k_bwd_leaves(const float* __restrict__ gleaf, const int32_t* __r
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// MFMA path: bf16, C = 128, 14 x 14 (the shape of the fused forward kernel)
+// ------------------------------------------------------------------------------------------
+// The transposed convolutions are convolutions with the taps flipped and the channel roles exchanged, so a node's
+// backward step has the shape of its forward step and runs on the same building blocks (LDS halo tile, packed
+// weight fragments, software-pipelined K loop), one node per workgroup, wave w owning channel tile w:
+//   tile <- u (argument map; two-argument functions: the 1x1 convolution as in the forward pass)
+//   conv_a(u) + b_a            -> mid mask (16 bits per lane and pixel tile, kept in registers), mid saved
+//   tile <- g = gy * [y > 0]   (bf16)
+//   conv(g; W_b flipped^T)     -> dmid = result * [mid > 0], written into the tile in place of g
+//   conv(dmid; W_a flipped^T)  -> du = that + g (the residual path, in fp32 from the gradient map), written as fp32 to the argument's gradient map; two-argument functions:
+//                                 dc = du * [u > 0] into the tile, two 1x1 convolutions with the halves of W_1^T
+// Gradients travel between nodes as fp32 maps and enter the MFMAs as bf16 (like every other operand of this
+// path).  u (two-argument functions), mid, g, dmid and dc are saved as bf16 maps per item for the parameter
+// gradients, which one kernel sums function by function afterwards.
+struct BmArgs {
+    const dynb_item* items;       // the launch group's items
+    const int32_t* gdst0;         // routes of the group's items
+    const int32_t* gdst1;
+    const uint8_t* arity;
+    int32_t first_item;
+    int32_t count;
+    const bf16_t* feats;
+    const bf16_t* out;
+    const bf16_t* slots;
+    const bf16_t* pk3a;           // packed fragments: forward conv_a
+    const bf16_t* pk1;            //                   forward conv1x1 (two halves)
+    const bf16_t* pk3bT;          //                   conv_b, taps flipped, channels exchanged
+    const bf16_t* pk3aT;          //                   conv_a, taps flipped, channels exchanged
+    const bf16_t* pk1T;           //                   conv1x1 halves, channels exchanged
+    const float* b1;
+    const float* b3a;
+    float* gy;                    // [n_items][P*C]
+    float* gleaf;                 // [n_leaves][P*C]
+    bf16_t* sv_u;                 // [n_items][P*C] each
+    bf16_t* sv_m;
+    bf16_t* sv_g;
+    bf16_t* sv_dm;
+    bf16_t* sv_dc;
+};
+
+// a bf16 is positive iff its bits, read as int16, are positive; for the two halves of a packed pair
+__device__ __forceinline__ bool bf16_lo_positive(uint32_t w) { return int16_t(w & 0xffffu) > 0; }
+__device__ __forceinline__ bool bf16_hi_positive(uint32_t w) { return int16_t(w >> 16) > 0; }
+
+__device__ __forceinline__ float* route_mf(const BmArgs& a, int32_t r)
+{
+    return r >= 0 ? a.gy + size_t(r) * (mf::P * mf::C) : a.gleaf + size_t(-1 - r) * (mf::P * mf::C);
+}
+
+// dst[function][tile][tap][j][lane][i] = W(o, tap, k) with o = tile*32 + rho(lane % 32) (the row permutation of the
+// forward pass's packed weights), k = (lane/32)*64 + j*8 + i, where
+//   mode 0: W = src[function][o][tap][k]                 conv3x3 as given (ntap 9)
+//   mode 1: W = src[function][k][8 - tap][o]             conv3x3 transposed, taps flipped (ntap 9)
+//   mode 2: W = src[function][o][tap*128 + k]            conv1x1 over 2C inputs, half `tap` (ntap 2)
+//   mode 3: W = src[function][k][tap*128 + o]            conv1x1 transposed, half `tap` (ntap 2)
+__global__ void k_bwd_pack(const bf16_t* __restrict__ src, u32x4* __restrict__ dst, int n_types, int ntap, int mode)
+{
+    const size_t total = size_t(n_types) * 4 * ntap * 8 * 64;
+    for (size_t q = size_t(blockIdx.x) * blockDim.x + threadIdx.x; q < total; q += size_t(gridDim.x) * blockDim.x) {
+        const int lane = int(q & 63), j = int((q >> 6) & 7);
+        const size_t rest = q >> 9;
+        const int tap = int(rest % ntap), tile = int((rest / ntap) & 3);
+        const size_t type = rest / (size_t(ntap) * 4);
+        const int m = lane & 31;
+        const int o = tile * 32 + ((m >> 2) & 1) * 16 + (m >> 3) * 4 + (m & 3), k0 = (lane >> 5) * 64 + j * 8;
+        uint32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int k = k0 + i;
+            size_t e;
+            if (mode == 0) e = ((type * 128 + o) * 9 + tap) * 128 + k;
+            else if (mode == 1) e = ((type * 128 + k) * 9 + (8 - tap)) * 128 + o;
+            else if (mode == 2) e = (type * 128 + o) * 256 + tap * 128 + k;
+            else e = (type * 128 + k) * 256 + tap * 128 + o;
+            v[i] = src[e];
+        }
+        dst[q] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+    }
+}
+
+template <int RW>
+__global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
+{
+    using namespace mf;
+    constexpr int MTW = MT7, NT = 1, XS = 4, NTHR = 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= a.count) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r = lane & 31, h = lane >> 5, n0 = wave * 32;
+    const dynb_item it = a.items[logical];
+    const bool binary = a.arity[it.type] == 2;                        // uniform over the workgroup
+    const size_t item_off = size_t(a.first_item + logical) * (P * C);
+
+    const size_t frag3 = (size_t(it.type) * 4 + wave) * 9 * 8, frag1 = (size_t(it.type) * 4 + wave) * 2 * 8;
+    const bf16_t* wrow_a[NT] = {a.pk3a + frag3 * FRAG + lane * 8};
+    const bf16_t* wrow_bT[NT] = {a.pk3bT + frag3 * FRAG + lane * 8};
+    const bf16_t* wrow_aT[NT] = {a.pk3aT + frag3 * FRAG + lane * 8};
+    bf16x8 ring[RW][NT];
+
+    // ---- staging of a bf16 map into the centre of the halo tile
+    constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
+    u32x4 tmp[NIT];
+    auto stage_load = [&](const bf16_t* src) {
+        const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) tmp[i] = s4[c];
+        }
+    };
+    auto centre_addr = [&](int c) -> uint32_t {
+        const int p = c >> 4, part = c & 15;
+        return uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + part * 16);
+    };
+    auto stage_store = [&]() {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = tmp[i];
+        }
+    };
+    auto map_of = [&](int32_t s) -> const bf16_t* { return s >= 0 ? a.slots + size_t(s) * (P * C) : a.feats + size_t(-1 - s) * (P * C); };
+
+    stage_load(map_of(it.src0));
+    for (int c = tid; c < 60 * 16; c += NTHR) {                       // zero border, once: only centres are rewritten
+        const int q = c >> 4, part = c & 15;
+        int row, col;
+        if (q < 16) { row = 0; col = q; }
+        else if (q < 32) { row = HALO - 1; col = q - 16; }
+        else { row = 1 + ((q - 32) >> 1); col = ((q - 32) & 1) ? HALO - 1 : 0; }
+        *reinterpret_cast<u32x4*>(lds_raw + uint32_t(row * ROW_BYTES + col * PIX_BYTES + part * 16)) = u32x4{0u, 0u, 0u, 0u};
+    }
+    stage_store();
+
+    uint32_t xaddr[MTW];                                              // top-left tap of this lane's pixel, its 64-channel half
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) {
+        const int p = min(t * 32 + r, P - 1);
+        xaddr[t] = uint32_t((p / S) * ROW_BYTES + (p % S) * PIX_BYTES + h * 128);
+    }
+    const int chan = n0 + 16 * h;                                     // this lane's 16 accumulator elements: channels chan .. chan+15
+    f32x16 acc[MTW][NT];
+    auto init_acc = [&](const float* bias) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan + b * 4);
+#pragma unroll
+            for (int t = 0; t < MTW; ++t) {
+                acc[t][0][4 * b + 0] = v.x; acc[t][0][4 * b + 1] = v.y;
+                acc[t][0][4 * b + 2] = v.z; acc[t][0][4 * b + 3] = v.w;
+            }
+        }
+    };
+    auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
+    // acc[t][0][8q .. 8q+7] as 8 packed bf16: ReLU'd (RELU) or kept where the mask bit is set
+    auto packed_relu = [&](int t, int q) -> u32x4 {
+        u32x4 pk;
+        pk.x = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 0], acc[t][0][8 * q + 1]));
+        pk.y = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 2], acc[t][0][8 * q + 3]));
+        pk.z = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 4], acc[t][0][8 * q + 5]));
+        pk.w = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 6], acc[t][0][8 * q + 7]));
+        return pk;
+    };
+    auto packed_masked = [&](int t, int q, uint32_t bits) -> u32x4 {   // bits: the 16 mask bits of tile t
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (bits >> (8 * q + i)) & 1u ? acc[t][0][8 * q + i] : 0.f;
+        return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+    };
+    auto positive_bits = [&](int t) -> uint32_t {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bits |= (acc[t][0][i] > 0.f ? 1u : 0u) << i;
+        return bits;
+    };
+    uint32_t umask[MTW], mmask[MTW];
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) umask[t] = mmask[t] = 0;
+
+    __syncthreads();
+
+    // ---- two-argument functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the tile; saved for dW_a
+    if (binary) {
+        const bf16_t* w1row[NT] = {a.pk1 + frag1 * FRAG + lane * 8};
+        const bf16_t* w1row2[NT] = {w1row[0] + 8 * FRAG};
+        bf16x8 ring1[8][NT];
+        ring_fill<NT, 8>(ring1, w1row);
+        init_acc(a.b1);
+        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, w1row, w1row2);
+        __syncthreads();
+        stage_load(map_of(it.src1));
+        stage_store();
+        __syncthreads();
+        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, w1row2, w1row2);
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            umask[t] = positive_bits(t);
+            if (t * 32 + r < P) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const u32x4 pk = packed_relu(t, q);
+                    *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
+                    *reinterpret_cast<u32x4*>(a.sv_u + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- mid = ReLU(conv_a(u) + b_a): its mask stays in registers, the map is saved for dW_b
+    ring_fill<NT, RW>(ring, wrow_a);
+    init_acc(a.b3a);
+    kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_a, wrow_bT);   // leaves the ring filled for the next convolution
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) {
+        mmask[t] = positive_bits(t);
+        if (t * 32 + r < P) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                *reinterpret_cast<u32x4*>(a.sv_m + item_off + size_t(t * 32 + r) * C + chan + q * 8) = packed_relu(t, q);
+        }
+    }
+    __syncthreads();                                                  // every wave has read the last of u
+
+    // ---- g = gy * [y > 0] as bf16 into the tile, saved for dW_b and db_b
+    {
+        const f32x4* gy4 = reinterpret_cast<const f32x4*>(a.gy + item_off);
+        const u32x4* y4 = reinterpret_cast<const u32x4*>(it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C));
+        u32x4* sg4 = reinterpret_cast<u32x4*>(a.sv_g + item_off);
+        f32x4 glo[NIT], ghi[NIT];
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) { glo[i] = gy4[2 * c]; ghi[i] = gy4[2 * c + 1]; tmp[i] = y4[c]; }
+        }
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) {
+                auto on_lo = [](uint32_t w) { return bf16_lo_positive(w); };
+                auto on_hi = [](uint32_t w) { return bf16_hi_positive(w); };
+                const u32x4 yv = tmp[i];
+                u32x4 pk;
+                pk.x = pack_bf16x2(on_lo(yv.x) ? glo[i].x : 0.f, on_hi(yv.x) ? glo[i].y : 0.f);
+                pk.y = pack_bf16x2(on_lo(yv.y) ? glo[i].z : 0.f, on_hi(yv.y) ? glo[i].w : 0.f);
+                pk.z = pack_bf16x2(on_lo(yv.z) ? ghi[i].x : 0.f, on_hi(yv.z) ? ghi[i].y : 0.f);
+                pk.w = pack_bf16x2(on_lo(yv.w) ? ghi[i].z : 0.f, on_hi(yv.w) ? ghi[i].w : 0.f);
+                *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = pk;
+                sg4[c] = pk;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- dmid = conv(g; W_b flipped, transposed) * [mid > 0], written into the tile in place of g
+    init_acc(nullptr);
+    kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_bT, wrow_aT);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < MTW; ++t)
+        if (t * 32 + r < P) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const u32x4 pk = packed_masked(t, q, mmask[t]);
+                *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
+                *reinterpret_cast<u32x4*>(a.sv_dm + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
+            }
+        }
+    __syncthreads();
+
+    // ---- du = g + conv(dmid; W_a flipped, transposed).  The residual term is added in fp32 from the gradient map
+    // itself, not from its bf16 copy in the tile: down a chain of modules the convolution's share is small against
+    // the residual's and would vanish below the bfloat16 quantum of the latter at every level.
+    init_acc(nullptr);
+    kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_aT, wrow_aT);
+    {
+        const float* gyp = a.gy + item_off;
+        const bf16_t* yp = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
+#pragma unroll
+        for (int t = 0; t < MTW; ++t)
+            if (t * 32 + r < P) {
+                const size_t e = size_t(t * 32 + r) * C + chan;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const u32x4 yv = *reinterpret_cast<const u32x4*>(yp + e + q * 8);
+                    const f32x4 g0 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8), g1 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8 + 4);
+                    acc[t][0][8 * q + 0] += bf16_lo_positive(yv.x) ? g0.x : 0.f;
+                    acc[t][0][8 * q + 1] += bf16_hi_positive(yv.x) ? g0.y : 0.f;
+                    acc[t][0][8 * q + 2] += bf16_lo_positive(yv.y) ? g0.z : 0.f;
+                    acc[t][0][8 * q + 3] += bf16_hi_positive(yv.y) ? g0.w : 0.f;
+                    acc[t][0][8 * q + 4] += bf16_lo_positive(yv.z) ? g1.x : 0.f;
+                    acc[t][0][8 * q + 5] += bf16_hi_positive(yv.z) ? g1.y : 0.f;
+                    acc[t][0][8 * q + 6] += bf16_lo_positive(yv.w) ? g1.z : 0.f;
+                    acc[t][0][8 * q + 7] += bf16_hi_positive(yv.w) ? g1.w : 0.f;
+                }
+            }
+    }
+    auto store_grad = [&](float* dst) {                               // the accumulators as an fp32 map
+#pragma unroll
+        for (int t = 0; t < MTW; ++t)
+            if (t * 32 + r < P) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    *reinterpret_cast<f32x4*>(dst + size_t(t * 32 + r) * C + chan + 4 * b) =
+                        f32x4{acc[t][0][4 * b], acc[t][0][4 * b + 1], acc[t][0][4 * b + 2], acc[t][0][4 * b + 3]};
+            }
+    };
+    if (!binary) {
+        store_grad(route_mf(a, a.gdst0[logical]));
+        return;
+    }
+    // ---- two-argument functions: dc = du * [u > 0] into the tile, then da0 = dc W_1[:, :C], da1 = dc W_1[:, C:]
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < MTW; ++t)
+        if (t * 32 + r < P) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const u32x4 pk = packed_masked(t, q, umask[t]);
+                *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
+                *reinterpret_cast<u32x4*>(a.sv_dc + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
+            }
+        }
+    __syncthreads();
+    {
+        const bf16_t* t1row[NT] = {a.pk1T + frag1 * FRAG + lane * 8};
+        const bf16_t* t1row2[NT] = {t1row[0] + 8 * FRAG};
+        bf16x8 ring1[8][NT];
+        ring_fill<NT, 8>(ring1, t1row);
+        init_acc(nullptr);
+        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row, t1row2);
+        store_grad(route_mf(a, a.gdst0[logical]));
+        init_acc(nullptr);
+        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row2, t1row2);
+        store_grad(route_mf(a, a.gdst1[logical]));
+    }
+}
+
+// Parameter gradients of every function, one workgroup per (function, part):
+//   MODE 0: conv_b, part = kernel row kh:  dW_b[co][kh][kw][ci] = sum_items sum_p g[p][co]    mid[p + (kh-1, kw-1)][ci]
+//   MODE 1: conv_a, part = kernel row kh:  dW_a[co][kh][kw][ci] = sum_items sum_p dmid[p][co] u[p + (kh-1, kw-1)][ci]
+//   MODE 2: conv1x1, part = argument:      dW_1[co][part*C + ci] = sum_items sum_p dc[p][co]  arg_part[p][ci]
+// and with part 0 the bias gradient, the sum of g / dmid / dc over items and pixels.
+// The contraction runs over pixels, the dimension in which neither map is contiguous.  Both maps of an item are
+// copied into LDS halo tiles (pixel-major like the forward pass's tile) and the MFMA operands are read from
+// there two bytes at a time: lane (m, hk) of an operand fragment holds channel m of the 8 pixels x = 8 hk .. 8 hk + 7
+// of image row y, one K step per image row (x = 14, 15 are zeros).  For a kernel row the three taps' fragments of the
+// input map are the same 10 pixels shifted by one, so they are read once.  D[ci][co] accumulates in registers over
+// all items of the function, in item order; nothing is atomic.  The bias gradient is the same contraction with
+// a fragment of ones in place of the input map.
+struct WgArgs {
+    const dynb_item* items;       // all items of the plan
+    const uint8_t* arity;
+    const int32_t* fn_first;
+    const int32_t* fn_items;
+    const bf16_t* feats;
+    const bf16_t* slots;
+    const bf16_t* sv_u;
+    const bf16_t* sv_m;
+    const bf16_t* sv_g;
+    const bf16_t* sv_dm;
+    const bf16_t* sv_dc;
+    float* dw;                    // the mode's weight gradient
+    float* db;                    // the mode's bias gradient
+};
+
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void k_bwd_wgrad_mfma(WgArgs a)
+{
+    using namespace mf;
+    constexpr int NPART = MODE == 2 ? 2 : 3, NTAP = MODE == 2 ? 1 : 3, NV = MODE == 2 ? 8 : 10, NTHR = 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int t = blockIdx.x / NPART, part = blockIdx.x % NPART;
+    const int ar = a.arity[t];
+    if (ar == 0 || (MODE == 2 && ar != 2)) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int m = lane & 31, hk = lane >> 5, wi = wave & 1, wj = wave >> 1;
+    constexpr uint32_t TILE_G = TILE_BYTES;                            // the gradient map's tile follows the input map's
+
+    for (int c = tid; c < 2 * TILE_BYTES / 16; c += NTHR) reinterpret_cast<u32x4*>(lds_raw)[c] = u32x4{0u, 0u, 0u, 0u};
+
+    f32x16 acc[NTAP][2][2], accb[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+        for (int k = 0; k < NTAP; ++k)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int cj = 0; cj < 2; ++cj) acc[k][ct][cj][i] = 0.f;
+        accb[0][i] = 0.f; accb[1][i] = 0.f;
+    }
+    constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
+    u32x4 tin[NIT], tg[NIT];
+    auto load = [&](int idx) {
+        const int32_t item = a.fn_items[idx];
+        const dynb_item it = a.items[item];
+        const size_t off = size_t(item) * (P * C);
+        const bf16_t* G = (MODE == 0 ? a.sv_g : MODE == 1 ? a.sv_dm : a.sv_dc) + off;
+        const bf16_t* IN;
+        if (MODE == 0) IN = a.sv_m + off;
+        else if (MODE == 1 && ar == 2) IN = a.sv_u + off;
+        else {
+            const int32_t s = (MODE == 2 && part == 1) ? it.src1 : it.src0;
+            IN = s >= 0 ? a.slots + size_t(s) * (P * C) : a.feats + size_t(-1 - s) * (P * C);
+        }
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) { tin[i] = reinterpret_cast<const u32x4*>(IN)[c]; tg[i] = reinterpret_cast<const u32x4*>(G)[c]; }
+        }
+    };
+    auto store = [&]() {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) {
+                const int p = c >> 4, piece = c & 15;
+                const uint32_t addr = uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + piece * 16);
+                *reinterpret_cast<u32x4*>(lds_raw + addr) = tin[i];
+                *reinterpret_cast<u32x4*>(lds_raw + TILE_G + addr) = tg[i];
+            }
+        }
+    };
+    auto rd16 = [&](uint32_t addr) -> uint32_t { return *reinterpret_cast<const uint16_t*>(lds_raw + addr); };
+    auto frag_of = [](const uint32_t* v) -> bf16x8 {
+        const u32x4 w = {v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        return __builtin_bit_cast(bf16x8, w);
+    };
+    const u32x4 ones_w = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_w);
+    // tile row / first tile column of this lane's 8 pixels of image row y:
+    //   gradient map and conv1x1 input: row y + 1, column 1 + 8 hk;  conv3x3 input for kernel row kh: row y + kh, column 8 hk
+    const uint32_t g_lane = TILE_G + uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wj * 64 + m) * 2);
+    const uint32_t in_lane = MODE == 2 ? uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wi * 64 + m) * 2)
+                                       : uint32_t(part * ROW_BYTES + (8 * hk) * PIX_BYTES + (wi * 64 + m) * 2);
+
+    const int n_begin = a.fn_first[t], n_end = a.fn_first[t + 1];
+    if (n_begin < n_end) load(n_begin);
+    for (int idx = n_begin; idx < n_end; ++idx) {
+        __syncthreads();                                              // the previous item's fragments have been read
+        store();
+        __syncthreads();
+        if (idx + 1 < n_end) load(idx + 1);                           // arrives under this item's MFMAs
+#pragma unroll 2
+        for (int y = 0; y < S; ++y) {
+            bf16x8 gf[2], inf[2][NTAP];
+#pragma unroll
+            for (int cj = 0; cj < 2; ++cj) {
+                uint32_t v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    // pixels x = 14, 15 do not exist: the last two values of the upper lane half are zeros
+                    const uint32_t raw = rd16(g_lane + uint32_t(y * ROW_BYTES + cj * 64 + (i < 6 ? i : (hk ? 0 : i)) * PIX_BYTES));
+                    v[i] = (i >= 6 && hk) ? 0u : raw;
+                }
+                gf[cj] = frag_of(v);
+            }
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                uint32_t v[NV];
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    // the upper lane half's pixels end at tile column 15 (conv3x3) / image column 13 (conv1x1); what
+                    // lies beyond only ever meets the zeros of the gradient fragment, but must be a finite number
+                    const int lim = MODE == 2 ? 6 : 8;
+                    const uint32_t raw = rd16(in_lane + uint32_t(y * ROW_BYTES + ct * 64 + (i < lim ? i : (hk ? 0 : i)) * PIX_BYTES));
+                    v[i] = (i >= lim && hk) ? 0u : raw;
+                }
+#pragma unroll
+                for (int k = 0; k < NTAP; ++k) inf[ct][k] = frag_of(v + k);
+            }
+#pragma unroll
+            for (int k = 0; k < NTAP; ++k)
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                    for (int cj = 0; cj < 2; ++cj)
+                        acc[k][ct][cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(inf[ct][k], gf[cj], acc[k][ct][cj], 0, 0, 0);
+            if (part == 0 && wi == 0) {
+#pragma unroll
+                for (int cj = 0; cj < 2; ++cj) accb[cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, gf[cj], accb[cj], 0, 0, 0);
+            }
+        }
+    }
+    // D[ci][co]: this lane holds co = wj*64 + cj*32 + m and ci = wi*64 + ct*32 + 8 b + 4 hk + (0..3) in elements 4 b .. 4 b + 3
+#pragma unroll
+    for (int cj = 0; cj < 2; ++cj) {
+        const int co = wj * 64 + cj * 32 + m;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int k = 0; k < NTAP; ++k)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int ci = wi * 64 + ct * 32 + 8 * b + 4 * hk;
+                    float* dst = MODE == 2 ? a.dw + (size_t(t) * C + co) * (2 * C) + part * C + ci
+                                           : a.dw + ((size_t(t) * C + co) * 9 + part * 3 + k) * C + ci;
+                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[k][ct][cj][4 * b], acc[k][ct][cj][4 * b + 1], acc[k][ct][cj][4 * b + 2], acc[k][ct][cj][4 * b + 3]};
+                }
+        if (part == 0 && wi == 0 && hk == 0) a.db[size_t(t) * C + co] = accb[cj][0];
+    }
+}
+
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 size_t elt_bytes(int dtype) { return dtype == DYNB_BF16 ? 2 : 4; }
 
@@ -365,6 +878,146 @@ int run_backward(const dynb_plan* p, const dynb_shape* s, const dynb_module_weig
     return DYNB_OK;
 }
 
+#ifdef DYNB_BWD_FORCE_GENERIC          // development aid: the generic kernels at every shape
+bool fast_shape(const dynb_shape*) { return false; }
+#else
+bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 128 && s->H == 14 && s->W == 14; }
+#endif
+
+// workspace of the MFMA path
+struct BmLayout {
+    size_t gy, gleaf, sv_u, sv_m, sv_g, sv_dm, sv_dc, pk3a, pk1, pk3bT, pk3aT, pk1T;
+    size_t t_gdst0, t_gdst1, t_leaf_first, t_root_item, t_fn_first, t_fn_items, total;
+};
+
+BmLayout bm_layout(const dynb_plan* p)
+{
+    BmLayout L;
+    const size_t chw = size_t(mf::P) * mf::C, n_items = p->items.size(), nt = size_t(p->n_types);
+    const size_t n_leaf = p->leaf_first.empty() ? 0 : size_t(p->leaf_first.back());
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(std::max<size_t>(bytes, 4)); return at; };
+    L.gy = take(n_items * chw * 4);
+    L.gleaf = take(n_leaf * chw * 4);
+    L.sv_u = take(p->has_binary ? n_items * chw * 2 : 0);
+    L.sv_m = take(n_items * chw * 2);
+    L.sv_g = take(n_items * chw * 2);
+    L.sv_dm = take(n_items * chw * 2);
+    L.sv_dc = take(p->has_binary ? n_items * chw * 2 : 0);
+    L.pk3a = take(nt * 9 * 128 * 128 * 2);
+    L.pk1 = take(nt * 2 * 128 * 128 * 2);
+    L.pk3bT = take(nt * 9 * 128 * 128 * 2);
+    L.pk3aT = take(nt * 9 * 128 * 128 * 2);
+    L.pk1T = take(nt * 2 * 128 * 128 * 2);
+    L.t_gdst0 = take(n_items * 4);
+    L.t_gdst1 = take(n_items * 4);
+    L.t_leaf_first = take((size_t(p->B) + 1) * 4);
+    L.t_root_item = take(size_t(p->B) * 4);
+    L.t_fn_first = take((nt + 1) * 4);
+    L.t_fn_items = take(n_items * 4);
+    L.total = o;
+    return L;
+}
+
+int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const void* feats, const void* out, const void* fwd_ws,
+                      const float* dout, const dynb_module_grads* g, char* ws, hipStream_t st)
+{
+    static std::atomic<uint64_t> attr_set{0};                 // one bit per device
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+    if (!(attr_set.load() >> (dev & 63) & 1)) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<8>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_bwd_node_mfma)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<0>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_bwd_wgrad_mfma<0>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<1>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_bwd_wgrad_mfma<1>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_bwd_wgrad_mfma<2>)");
+        attr_set.fetch_or(uint64_t(1) << (dev & 63));
+    }
+    const BmLayout L = bm_layout(p);
+    const size_t chw = size_t(mf::P) * mf::C;
+    const int C = mf::C, B = p->B, nt = p->n_types;
+    auto table = [&](size_t at, const std::vector<int32_t>& v) -> hipError_t {
+        return v.empty() ? hipSuccess : hipMemcpyAsync(ws + at, v.data(), v.size() * 4, hipMemcpyHostToDevice, st);
+    };
+    HIP_TRY(table(L.t_gdst0, p->grad_dst0), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_gdst1, p->grad_dst1), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_leaf_first, p->leaf_first), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_root_item, p->root_item), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_fn_first, p->fn_first), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_fn_items, p->fn_items), "dynbatch_backward(tables)");
+    const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(ws + L.t_leaf_first);
+    const int32_t* d_root_item = reinterpret_cast<const int32_t*>(ws + L.t_root_item);
+
+    // gradients of functions that no item uses stay zero
+    auto fill = [&](float* ptr, size_t n) {
+        if (ptr && n) hipLaunchKernelGGL(k_bwd_fill, dim3(unsigned(std::min<size_t>((n + 255) / 256, 4096))), dim3(256), 0, st, ptr, n, 0.f);
+    };
+    fill(g->dw3a, size_t(nt) * C * 9 * C); fill(g->dw3b, size_t(nt) * C * 9 * C); fill(g->db3a, size_t(nt) * C); fill(g->db3b, size_t(nt) * C);
+    fill(g->dw1, size_t(nt) * C * 2 * C); fill(g->db1, size_t(nt) * C);
+
+    // weights in fragment order, as given and transposed
+    auto pack = [&](const void* src, size_t at, int ntap, int mode) {
+        const size_t pieces = size_t(nt) * 4 * ntap * 512;
+        hipLaunchKernelGGL(k_bwd_pack, dim3(unsigned(std::min<size_t>((pieces + 255) / 256, 4096))), dim3(256), 0, st,
+                           static_cast<const bf16_t*>(src), reinterpret_cast<u32x4*>(ws + at), nt, ntap, mode);
+    };
+    pack(w->w3a, L.pk3a, 9, 0);
+    pack(w->w3b, L.pk3bT, 9, 1);
+    pack(w->w3a, L.pk3aT, 9, 1);
+    if (p->has_binary) { pack(w->w1, L.pk1, 2, 2); pack(w->w1, L.pk1T, 2, 3); }
+
+    float* gy = reinterpret_cast<float*>(ws + L.gy);
+    const unsigned bx_map = unsigned(std::min<size_t>((chw + 255) / 256, 64));
+    for (int e0 = 0; e0 < B; e0 += 32768)
+        hipLaunchKernelGGL(k_bwd_seed, dim3(bx_map, unsigned(std::min(32768, B - e0))), dim3(256), 0, st, dout + size_t(e0) * chw,
+                           d_root_item + e0, gy, chw);
+
+    const char* d = static_cast<const char*>(p->dev_buf);
+    const dynb_item* d_items = reinterpret_cast<const dynb_item*>(d);
+    const uint8_t* d_arity = reinterpret_cast<const uint8_t*>(d + dynb_plan_arity_offset(p));
+    BmArgs a;
+    a.arity = d_arity;
+    a.feats = static_cast<const bf16_t*>(feats); a.out = static_cast<const bf16_t*>(out); a.slots = static_cast<const bf16_t*>(fwd_ws);
+    a.pk3a = reinterpret_cast<const bf16_t*>(ws + L.pk3a); a.pk1 = reinterpret_cast<const bf16_t*>(ws + L.pk1);
+    a.pk3bT = reinterpret_cast<const bf16_t*>(ws + L.pk3bT); a.pk3aT = reinterpret_cast<const bf16_t*>(ws + L.pk3aT);
+    a.pk1T = reinterpret_cast<const bf16_t*>(ws + L.pk1T);
+    a.b1 = w->b1; a.b3a = w->b3a;
+    a.gy = gy; a.gleaf = reinterpret_cast<float*>(ws + L.gleaf);
+    a.sv_u = reinterpret_cast<bf16_t*>(ws + L.sv_u); a.sv_m = reinterpret_cast<bf16_t*>(ws + L.sv_m);
+    a.sv_g = reinterpret_cast<bf16_t*>(ws + L.sv_g); a.sv_dm = reinterpret_cast<bf16_t*>(ws + L.sv_dm);
+    a.sv_dc = reinterpret_cast<bf16_t*>(ws + L.sv_dc);
+    for (size_t li = p->launches.size(); li-- > 0;) {
+        const dynb_launch& l = p->launches[li];
+        a.items = d_items + l.start; a.first_item = l.start; a.count = l.count;
+        a.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + l.start;
+        a.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + l.start;
+        const unsigned grid = unsigned((l.count + 7) / 8 * 8);
+        hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+    }
+    WgArgs q;
+    q.items = d_items; q.arity = d_arity;
+    q.fn_first = reinterpret_cast<const int32_t*>(ws + L.t_fn_first);
+    q.fn_items = reinterpret_cast<const int32_t*>(ws + L.t_fn_items);
+    q.feats = a.feats; q.slots = a.slots;
+    q.sv_u = a.sv_u; q.sv_m = a.sv_m; q.sv_g = a.sv_g; q.sv_dm = a.sv_dm; q.sv_dc = a.sv_dc;
+    q.dw = g->dw3b; q.db = g->db3b;
+    hipLaunchKernelGGL((k_bwd_wgrad_mfma<0>), dim3(unsigned(nt) * 3), dim3(256), 2 * mf::TILE_BYTES, st, q);
+    q.dw = g->dw3a; q.db = g->db3a;
+    hipLaunchKernelGGL((k_bwd_wgrad_mfma<1>), dim3(unsigned(nt) * 3), dim3(256), 2 * mf::TILE_BYTES, st, q);
+    if (p->has_binary) {
+        q.dw = g->dw1; q.db = g->db1;
+        hipLaunchKernelGGL((k_bwd_wgrad_mfma<2>), dim3(unsigned(nt) * 2), dim3(256), 2 * mf::TILE_BYTES, st, q);
+    }
+    for (int e0 = 0; e0 < B; e0 += 32768)
+        hipLaunchKernelGGL(k_bwd_leaves, dim3(bx_map, unsigned(std::min(32768, B - e0))), dim3(256), 0, st, a.gleaf, d_leaf_first + e0,
+                           d_root_item + e0, dout + size_t(e0) * chw, g->dfeats + size_t(e0) * chw, chw);
+    HIP_TRY(hipGetLastError(), "dynbatch_backward(mfma kernels)");
+    return DYNB_OK;
+}
+
 int check_backward(const dynb_plan* p, const dynb_shape* s, const char* who)
 {
     if (!p || !s) return fail(DYNB_E_INVAL, std::string(who) + ": NULL argument");
@@ -382,6 +1035,7 @@ int check_backward(const dynb_plan* p, const dynb_shape* s, const char* who)
 extern "C" size_t dynbatch_backward_workspace_bytes(const dynb_plan* p, const dynb_shape* s)
 {
     if (check_backward(p, s, "dynbatch_backward_workspace_bytes") != DYNB_OK) return 0;
+    if (fast_shape(s)) return std::max<size_t>(bm_layout(p).total, 256);
     return std::max<size_t>(bwd_layout(p, s).total, 256);
 }
 
@@ -399,10 +1053,12 @@ extern "C" int dynbatch_backward(const dynb_plan* p, const dynb_shape* s, const 
     if (p->has_binary && (!w->w1 || !grads->dw1 || !grads->db1))
         return fail(DYNB_E_INVAL, "dynbatch_backward: two-argument functions need w1, dw1 and db1");
     if (!p->dev_buf) return fail(DYNB_E_WORKSPACE, "dynbatch_backward: plan not uploaded");
-    if (workspace_bytes < bwd_layout(p, s).total) return fail(DYNB_E_WORKSPACE, "dynbatch_backward: workspace too small");
+    if (workspace_bytes < (fast_shape(s) ? bm_layout(p).total : bwd_layout(p, s).total))
+        return fail(DYNB_E_WORKSPACE, "dynbatch_backward: workspace too small");
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(DYNB_E_INVAL, "dynbatch_backward: workspace not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
+    if (fast_shape(s)) return run_backward_mfma(p, w, feats, out, forward_workspace, dout, grads, ws, st);
     if (s->dtype == DYNB_BF16) return run_backward<bf16_t>(p, s, w, feats, out, forward_workspace, dout, grads, ws, st);
     return run_backward<float>(p, s, w, feats, out, forward_workspace, dout, grads, ws, st);
 }

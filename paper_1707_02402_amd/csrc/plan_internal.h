@@ -49,6 +49,8 @@ struct dynb_plan {
     std::vector<int32_t> grad_dst0, grad_dst1;
     std::vector<int32_t> leaf_first;     // [B+1] leaves of example e are leaf_first[e] .. leaf_first[e+1]
     std::vector<int32_t> root_item;      // [B] item that evaluates the example's root, -1 if the root is a SCENE leaf
+    std::vector<int32_t> fn_first;       // [n_types+1] the items of function t are fn_items[fn_first[t] .. fn_first[t+1])
+    std::vector<int32_t> fn_items;       // item indices grouped by function, ascending inside a function
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };

@@ -333,6 +333,14 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         }
         p->root_item.resize(B);
         for (int32_t e = 0; e < B; ++e) p->root_item[e] = item_of[p->root[e]];
+        // the items of every function in execution order (counting sort): a function's parameter gradients are
+        // summed over this list
+        p->fn_first.assign(size_t(p->n_types) + 1, 0);
+        for (const dynb_item& it : p->items) ++p->fn_first[size_t(it.type) + 1];
+        for (int32_t t = 0; t < p->n_types; ++t) p->fn_first[t + 1] += p->fn_first[t];
+        p->fn_items.resize(p->items.size());
+        std::vector<int32_t> at(p->fn_first.begin(), p->fn_first.end() - 1);
+        for (size_t i = 0; i < p->items.size(); ++i) p->fn_items[at[p->items[i].type]++] = int32_t(i);
     }
     // 4. units of work of the dependency-driven launch, in claim order = execution order of the items
     // (arguments always come earlier in it).  Groups that leave half of the chip idle are run with two

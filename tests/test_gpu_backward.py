@@ -11,6 +11,11 @@ stored activations of every module to the neighbouring bfloat16.  Such a differe
 rounding points, and the gradient of a ReLU network is not continuous in its activations (the oracle's own gradients
 with and without bf16 storage differ by 8 % in the Frobenius norm on this workload): deep programs at C = 128 are
 therefore compared in the relative Frobenius norm of every gradient tensor with a bar of 5e-2 (observed 2-4e-2).
+At the shape of the fused kernels (bf16, C = 128, 14 x 14) the backward pass runs on MFMAs, whose operands are bf16:
+the gradient maps g, dmid and dc are rounded to bfloat16 (relative error up to 2^-9, independent from element to
+element) before they are multiplied.  A sum of n such products then deviates by about 2^-9 / sqrt(3) of its own
+typical size whatever n is, i.e. ~1e-3; with two or three such stages in a row a single module is off by 2-3e-3
+of the tensor maximum (observed), against a bar of 1e-2.
 """
 import numpy as np
 import pytest
@@ -122,7 +127,7 @@ def test_bf16_deep_programs_at_a_small_channel_count(dyn, util, oracle):
 
 def test_bf16_single_modules(dyn, util, oracle):
     """One module per program (a one-argument or a two-argument function on SCENE leaves): no upstream activation
-    can differ, so the bf16 backward pass must agree with the oracle's bf16-storage mode tightly."""
+    can differ, so only the bf16 rounding of the gradient operands separates the two sides."""
     arity = np.array([0, 1, 1, 2, 2], np.uint8)
     progs = [np.array(p, np.int32) for p in ([1, 0], [3, 0, 0], [2, 0], [4, 0, 0], [1, 0], [3, 0, 0])]
     off = np.concatenate([[0], np.cumsum([len(p) for p in progs])]).astype(np.int32)
@@ -134,7 +139,75 @@ def test_bf16_single_modules(dyn, util, oracle):
     ref = oracle.iep_backward_workload(w, dout, round_bf16=True)
     got, out = run_backward(dyn, util, w, dout)
     for name in NAMES:
-        assert maxnorm(got[name], getattr(ref, name)) < 1e-3, (name, maxnorm(got[name], getattr(ref, name)))
+        assert maxnorm(got[name], getattr(ref, name)) < 1e-2, (name, maxnorm(got[name], getattr(ref, name)))
+        assert frob(got[name], getattr(ref, name)) < 5e-3, (name, frob(got[name], getattr(ref, name)))
+    again, _ = run_backward(dyn, util, w, dout)
+    for name in NAMES:
+        assert (again[name] == got[name]).all(), name                     # no atomics: same bits
+
+
+def _sampled(w, seed):
+    """dout that is zero outside a sample of the examples, and the sample as a workload of its own.  The backward
+    pass is linear in dout and examples are independent, so every parameter gradient of the full batch equals that
+    of the sample alone, which the oracle computes program by program."""
+    sample = np.arange(3, w.B, 11)                                          # 23 of 256 programs
+    sub = w.subset(sample)
+    dsub = np.random.default_rng(seed).standard_normal(sub.feats.shape).astype(np.float32)
+    dout = np.zeros(w.feats.shape, np.float32)
+    dout[sample] = dsub
+    return sample, sub, dsub, dout
+
+
+def test_config2_full_batch_with_every_unit_active(dyn, util, oracle):
+    """The benchmark's programs, shapes and launch configuration (256 programs, 27 labels, balanced launch groups,
+    MFMA kernels) with non-negative weights, biases and feature maps: every ReLU is active, the network is linear,
+    and nothing but rounding separates the two sides at any depth.  This pins the routing of the gradients through
+    4066 nodes, the sums over all nodes of a function and every launch shape; the masks are pinned by the tests above."""
+    import dataclasses
+    from workloads.rng import round_bf16, stream
+    w = iep.config2()
+    g = stream(4242, 1)
+    C = w.C
+    pos = lambda shape, mean: round_bf16((g.random(shape, dtype=np.float32) * 2 * mean).astype(np.float32))
+    binary = (w.arity == 2)[:, None, None]
+    w = dataclasses.replace(
+        w, feats=pos(w.feats.shape, 0.5),
+        w1=pos(w.w1.shape, 0.5 / (2 * C)) * binary, b1=pos(w.b1.shape, 0.05) * binary[:, :, 0],
+        w3a=pos(w.w3a.shape, 0.3 / (9 * C)), b3a=pos(w.b3a.shape, 0.05),
+        w3b=pos(w.w3b.shape, 0.3 / (9 * C)), b3b=pos(w.b3b.shape, 0.05))
+    sample, sub, dsub, dout = _sampled(w, 6)
+    ref = oracle.iep_backward_workload(sub, dsub, round_bf16=True)
+    got, out = run_backward(dyn, util, w, dout, dyn.DYNB_PLAN_BALANCE)
+    assert (out > 0).all()
+    assert util.normwise(out[sample], ref.roots) < 2e-2
+    errs = {name: maxnorm(got[name][sample] if name == "dfeats" else got[name], getattr(ref, name)) for name in NAMES}
+    print("max-norm errors, all units active", errs)
+    for name in NAMES:
+        assert errs[name] < 1e-2, (name, errs[name])                        # observed 1e-4 (dfeats) .. 2e-3
+    rest = np.setdiff1d(np.arange(w.B), sample)
+    assert (got["dfeats"][rest] == 0).all()
+
+
+def test_config2_full_batch_against_the_oracle_on_sampled_examples(dyn, util, oracle):
+    """The benchmark's configuration as bench.py runs it.  Programs of up to 30 modules amplify what the module
+    docstring describes: a stored activation that rounds to the neighbouring bfloat16 flips a ReLU decision somewhere
+    downstream, and the oracle's own gradients with fp64 and with bf16 storage differ by 15-30 % in the Frobenius norm
+    on these programs (the forward results by 1 %).  The kernels are held to that spread: no gradient tensor may be
+    further from the bf16-storage oracle than 1.25 times the distance between the oracle's two modes (+ 0.02), and short
+    programs must be close."""
+    w = iep.config2()
+    sample, sub, dsub, dout = _sampled(w, 5)
+    ref = oracle.iep_backward_workload(sub, dsub, round_bf16=True)
+    plain = oracle.iep_backward_workload(sub, dsub)
+    got, out = run_backward(dyn, util, w, dout, dyn.DYNB_PLAN_BALANCE)
+    assert util.normwise(out[sample], ref.roots) < 2e-2
+    for name in NAMES:
+        err = frob(got[name][sample] if name == "dfeats" else got[name], getattr(ref, name))
+        spread = frob(getattr(plain, name), getattr(ref, name))
+        print(name, "kernels vs bf16-storage oracle", round(err, 4), "fp64 oracle vs bf16-storage oracle", round(spread, 4))
+        assert err < 1.25 * spread + 0.02, (name, err, spread)
+    rest = np.setdiff1d(np.arange(w.B), sample)
+    assert (got["dfeats"][rest] == 0).all()
 
 
 def test_closed_form_identity_kernels(dyn, util):
