@@ -322,18 +322,21 @@ def main():
         kout = dyn.dynbatch_execute(kplan, weights, L0["feats"], workspace=kws)
         assert torch.equal(kout, ref_out)
         dout = torch.randn(kout.shape, dtype=torch.float32, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
-        wfull = dict(weights)
-        t0 = time.perf_counter()
-        dyn.dynbatch_backward(kplan, wfull, L0["feats"], kout, kws, dout)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        dyn.dynbatch_backward(kplan, wfull, L0["feats"], kout, kws, dout)
-        torch.cuda.synchronize()
-        bwd_ms = (time.perf_counter() - t0) * 1e3
-        extras["backward"] = {"ms_per_step": round(bwd_ms, 2), "forward_ms_per_step": round(one_ms, 4),
-                              "ratio_to_forward": round(bwd_ms / one_ms, 1),
-                              "flops": 2.0 * flops_step, "tflops": round(2.0 * flops_step / bwd_ms / 1e9, 2),
-                              "kind": "plain FMA kernels (one thread per output element), parameter gradients pool by pool"}
+        bws = torch.empty(dyn.dynbatch_backward_workspace_bytes(kplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+        grads = dyn.dynbatch_backward(kplan, weights, L0["feats"], kout, kws, dout, workspace=bws)
+        bwd_ms = gpu_ms(lambda: dyn.dynbatch_backward(kplan, weights, L0["feats"], kout, kws, dout, workspace=bws, grads=grads), max(K // 5, 3))
+        kfwd_ms = gpu_ms(lambda: dyn.dynbatch_execute(kplan, weights, L0["feats"], out=kout, workspace=kws), K)
+        # two transposed convolutions and two weight-gradient contractions per module: twice the forward pass's flops
+        # (the recomputation of u and mid, half a forward pass, is not counted as useful work)
+        extras["backward"] = {"ms_per_step": round(bwd_ms, 3), "forward_ms_per_step": round(kfwd_ms, 4),
+                              "ratio_to_forward": round(bwd_ms / kfwd_ms, 2),
+                              "flops": 2.0 * flops_step, "tflops": round(2.0 * flops_step / bwd_ms / 1e9, 1),
+                              "frac_of_mfma_peak": round(2.0 * flops_step / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                              "workspace_mb": round(bws.numel() / 1e6, 1),
+                              "kind": "MFMA kernels: one fused launch per label in reverse order (recomputes u and mid, both "
+                                      "transposed convolutions, fp32 gradient maps), then one launch per convolution for the "
+                                      "parameter gradients of all functions; forward = the same plan (DYNB_PLAN_KEEP: a slot per node)"}
+        del bws, grads
         del kws, kout, dout, kplan
 
     # ------------------------------------------------------------------ mixture of experts

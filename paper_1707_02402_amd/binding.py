@@ -319,20 +319,28 @@ def dynb_set_spin_limit(polls: int) -> int:
 
 
 # ------------------------------------------------------------------------------------------ backward pass
-def dynbatch_backward(plan: Plan, weights: dict, feats, out, forward_workspace, dout, workspace=None, stream=None) -> dict:
+def dynbatch_backward_workspace_bytes(plan: Plan, C: int, H: int, W: int, dtype: int) -> int:
+    return int(lib.dynbatch_backward_workspace_bytes(plan.handle, ct.byref(_Shape(C, H, W, dtype))))
+
+
+def dynbatch_backward(plan: Plan, weights: dict, feats, out, forward_workspace, dout, workspace=None, stream=None, grads=None) -> dict:
     """Backward pass of an executed DYNB_PLAN_KEEP plan.  dout: device float32 [B,H,W,C].  Returns a dict of device
-    float32 tensors dfeats, dw1, db1, dw3a, db3a, dw3b, db3b in the shapes of feats and of the weights."""
+    float32 tensors dfeats, dw1, db1, dw3a, db3a, dw3b, db3b in the shapes of feats and of the weights (`grads`: such
+    a dict from an earlier call, to be overwritten)."""
     import torch
     shape = _shape_of(feats)
     assert dout.is_cuda and dout.is_contiguous() and dout.dtype == torch.float32 and dout.shape == feats.shape
     f32 = lambda t: torch.empty(t.shape, dtype=torch.float32, device=feats.device)
     C = shape.C
     n_types = weights["w3a"].shape[0]
-    g = dict(dfeats=f32(feats), dw3a=f32(weights["w3a"]), dw3b=f32(weights["w3b"]),
-             db3a=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
-             db3b=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
-             dw1=torch.empty((n_types, C, 2 * C), dtype=torch.float32, device=feats.device),
-             db1=torch.empty((n_types, C), dtype=torch.float32, device=feats.device))
+    g = grads if grads is not None else dict(
+        dfeats=f32(feats), dw3a=f32(weights["w3a"]), dw3b=f32(weights["w3b"]),
+        db3a=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
+        db3b=torch.empty((n_types, C), dtype=torch.float32, device=feats.device),
+        dw1=torch.empty((n_types, C, 2 * C), dtype=torch.float32, device=feats.device),
+        db1=torch.empty((n_types, C), dtype=torch.float32, device=feats.device))
+    for k in ("dfeats", "dw1", "db1", "dw3a", "db3a", "dw3b", "db3b"):
+        assert g[k].is_cuda and g[k].is_contiguous() and g[k].dtype == torch.float32
     if workspace is None:
         n = int(lib.dynbatch_backward_workspace_bytes(plan.handle, ct.byref(shape)))
         if n == 0:

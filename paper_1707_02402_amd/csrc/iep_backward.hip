@@ -22,6 +22,7 @@
 #include <algorithm>
 #include <atomic>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "device_utils.h"
@@ -249,16 +250,16 @@ __global__ void k_bwd_leaves(const float* __restrict__ gleaf, const int32_t* __r
 // ------------------------------------------------------------------------------------------
 // The transposed convolutions are convolutions with the taps flipped and the channel roles exchanged, so a node's
 // backward step has the shape of its forward step and runs on the same building blocks (LDS halo tile, packed
-// weight fragments, software-pipelined K loop), one node per workgroup, wave w owning channel tile w:
-//   tile <- u (argument map; two-argument functions: the 1x1 convolution as in the forward pass)
-//   conv_a(u) + b_a            -> mid mask (16 bits per lane and pixel tile, kept in registers), mid saved
+// weight fragments, software-pipelined K loop), one node per workgroup, wave w owning channel tile w.  The forward
+// pass of a DYNB_PLAN_KEEP plan has left u (two-argument functions) and mid of every item in its workspace.
 //   tile <- g = gy * [y > 0]   (bf16)
 //   conv(g; W_b flipped^T)     -> dmid = result * [mid > 0], written into the tile in place of g
-//   conv(dmid; W_a flipped^T)  -> du = that + g (the residual path, in fp32 from the gradient map), written as fp32 to the argument's gradient map; two-argument functions:
-//                                 dc = du * [u > 0] into the tile, two 1x1 convolutions with the halves of W_1^T
+//   conv(dmid; W_a flipped^T)  -> du = that + g (the residual path, in fp32 from the gradient map), written as fp32
+//                                 to the argument's gradient map; two-argument functions: dc = du * [u > 0] into the
+//                                 tile, then two 1x1 convolutions with the halves of W_1^T
 // Gradients travel between nodes as fp32 maps and enter the MFMAs as bf16 (like every other operand of this
-// path).  u (two-argument functions), mid, g, dmid and dc are saved as bf16 maps per item for the parameter
-// gradients, which one kernel sums function by function afterwards.
+// path).  g, dmid and dc are saved as bf16 maps per item for the parameter gradients, which one kernel sums
+// function by function afterwards.
 struct BmArgs {
     const dynb_item* items;       // the launch group's items
     const int32_t* gdst0;         // routes of the group's items
@@ -269,17 +270,13 @@ struct BmArgs {
     const bf16_t* feats;
     const bf16_t* out;
     const bf16_t* slots;
-    const bf16_t* pk3a;           // packed fragments: forward conv_a
-    const bf16_t* pk1;            //                   forward conv1x1 (two halves)
-    const bf16_t* pk3bT;          //                   conv_b, taps flipped, channels exchanged
+    const bf16_t* pk3bT;          // packed fragments: conv_b, taps flipped, channels exchanged
     const bf16_t* pk3aT;          //                   conv_a, taps flipped, channels exchanged
     const bf16_t* pk1T;           //                   conv1x1 halves, channels exchanged
-    const float* b1;
-    const float* b3a;
     float* gy;                    // [n_items][P*C]
     float* gleaf;                 // [n_leaves][P*C]
-    bf16_t* sv_u;                 // [n_items][P*C] each
-    bf16_t* sv_m;
+    const bf16_t* sv_u;           // [n_items][P*C] each; u and mid: in the forward pass's workspace
+    const bf16_t* sv_m;
     bf16_t* sv_g;
     bf16_t* sv_dm;
     bf16_t* sv_dc;
@@ -341,45 +338,55 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     const size_t item_off = size_t(a.first_item + logical) * (P * C);
 
     const size_t frag3 = (size_t(it.type) * 4 + wave) * 9 * 8, frag1 = (size_t(it.type) * 4 + wave) * 2 * 8;
-    const bf16_t* wrow_a[NT] = {a.pk3a + frag3 * FRAG + lane * 8};
     const bf16_t* wrow_bT[NT] = {a.pk3bT + frag3 * FRAG + lane * 8};
     const bf16_t* wrow_aT[NT] = {a.pk3aT + frag3 * FRAG + lane * 8};
     bf16x8 ring[RW][NT];
 
-    // ---- staging of a bf16 map into the centre of the halo tile
-    constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
-    u32x4 tmp[NIT];
-    auto stage_load = [&](const bf16_t* src) {
-        const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = tid + i * NTHR;
-            if (c < P * 16) tmp[i] = s4[c];
-        }
-    };
-    auto centre_addr = [&](int c) -> uint32_t {
+    auto centre_addr = [&](int c) -> uint32_t {                       // 16-byte piece c of a map -> its place in the halo tile
         const int p = c >> 4, part = c & 15;
         return uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + part * 16);
     };
-    auto stage_store = [&]() {
+    const float* gyp = a.gy + item_off;
+    const bf16_t* yp = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
+
+    // ---- g = gy * [y > 0] as bf16 into the tile, saved for dW_b and db_b; all loads are issued before the first use
+    constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
+    {
+        const f32x4* gy4 = reinterpret_cast<const f32x4*>(gyp);
+        const u32x4* y4 = reinterpret_cast<const u32x4*>(yp);
+        u32x4* sg4 = reinterpret_cast<u32x4*>(a.sv_g + item_off);
+        f32x4 glo[NIT], ghi[NIT];
+        u32x4 yv[NIT];
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = tid + i * NTHR;
-            if (c < P * 16) *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = tmp[i];
+            if (c < P * 16) { glo[i] = gy4[2 * c]; ghi[i] = gy4[2 * c + 1]; yv[i] = y4[c]; }
         }
-    };
-    auto map_of = [&](int32_t s) -> const bf16_t* { return s >= 0 ? a.slots + size_t(s) * (P * C) : a.feats + size_t(-1 - s) * (P * C); };
-
-    stage_load(map_of(it.src0));
-    for (int c = tid; c < 60 * 16; c += NTHR) {                       // zero border, once: only centres are rewritten
-        const int q = c >> 4, part = c & 15;
-        int row, col;
-        if (q < 16) { row = 0; col = q; }
-        else if (q < 32) { row = HALO - 1; col = q - 16; }
-        else { row = 1 + ((q - 32) >> 1); col = ((q - 32) & 1) ? HALO - 1 : 0; }
-        *reinterpret_cast<u32x4*>(lds_raw + uint32_t(row * ROW_BYTES + col * PIX_BYTES + part * 16)) = u32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_sched_barrier(0);
+        ring_fill<NT, RW>(ring, wrow_bT);                             // arrives while the tile is written
+        for (int c = tid; c < 60 * 16; c += NTHR) {                   // zero border
+            const int q = c >> 4, part = c & 15;
+            int row, col;
+            if (q < 16) { row = 0; col = q; }
+            else if (q < 32) { row = HALO - 1; col = q - 16; }
+            else { row = 1 + ((q - 32) >> 1); col = ((q - 32) & 1) ? HALO - 1 : 0; }
+            *reinterpret_cast<u32x4*>(lds_raw + uint32_t(row * ROW_BYTES + col * PIX_BYTES + part * 16)) = u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) {
+                const u32x4 y = yv[i];
+                u32x4 pk;
+                pk.x = pack_bf16x2(bf16_lo_positive(y.x) ? glo[i].x : 0.f, bf16_hi_positive(y.x) ? glo[i].y : 0.f);
+                pk.y = pack_bf16x2(bf16_lo_positive(y.y) ? glo[i].z : 0.f, bf16_hi_positive(y.y) ? glo[i].w : 0.f);
+                pk.z = pack_bf16x2(bf16_lo_positive(y.z) ? ghi[i].x : 0.f, bf16_hi_positive(y.z) ? ghi[i].y : 0.f);
+                pk.w = pack_bf16x2(bf16_lo_positive(y.w) ? ghi[i].z : 0.f, bf16_hi_positive(y.w) ? ghi[i].w : 0.f);
+                *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = pk;
+                sg4[c] = pk;
+            }
+        }
     }
-    stage_store();
 
     uint32_t xaddr[MTW];                                              // top-left tap of this lane's pixel, its 64-channel half
 #pragma unroll
@@ -389,122 +396,37 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     }
     const int chan = n0 + 16 * h;                                     // this lane's 16 accumulator elements: channels chan .. chan+15
     f32x16 acc[MTW][NT];
-    auto init_acc = [&](const float* bias) {
+    auto zero_acc = [&]() {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (bias) v = *reinterpret_cast<const f32x4*>(bias + size_t(it.type) * C + chan + b * 4);
+        for (int t = 0; t < MTW; ++t)
 #pragma unroll
-            for (int t = 0; t < MTW; ++t) {
-                acc[t][0][4 * b + 0] = v.x; acc[t][0][4 * b + 1] = v.y;
-                acc[t][0][4 * b + 2] = v.z; acc[t][0][4 * b + 3] = v.w;
-            }
-        }
+            for (int i = 0; i < 16; ++i) acc[t][0][i] = 0.f;
     };
     auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
-    // acc[t][0][8q .. 8q+7] as 8 packed bf16: ReLU'd (RELU) or kept where the mask bit is set
-    auto packed_relu = [&](int t, int q) -> u32x4 {
-        u32x4 pk;
-        pk.x = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 0], acc[t][0][8 * q + 1]));
-        pk.y = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 2], acc[t][0][8 * q + 3]));
-        pk.z = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 4], acc[t][0][8 * q + 5]));
-        pk.w = relu_bf16x2(pack_bf16x2(acc[t][0][8 * q + 6], acc[t][0][8 * q + 7]));
-        return pk;
+    // the 16 mask bits [v > 0] of this lane's channels of pixel tile t of a saved bf16 map
+    auto mask_bits = [&](const bf16_t* map, int t) -> uint32_t {
+        const u32x4 lo = *reinterpret_cast<const u32x4*>(map + size_t(min(t * 32 + r, P - 1)) * C + chan);
+        const u32x4 hi = *reinterpret_cast<const u32x4*>(map + size_t(min(t * 32 + r, P - 1)) * C + chan + 8);
+        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        uint32_t bits = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bits |= (bf16_lo_positive(w[i]) ? 1u : 0u) << (2 * i) | (bf16_hi_positive(w[i]) ? 1u : 0u) << (2 * i + 1);
+        return bits;
     };
-    auto packed_masked = [&](int t, int q, uint32_t bits) -> u32x4 {   // bits: the 16 mask bits of tile t
+    // acc[t][0][8q .. 8q+7] where the mask bit is set, as 8 packed bf16
+    auto packed_masked = [&](int t, int q, uint32_t bits) -> u32x4 {
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = (bits >> (8 * q + i)) & 1u ? acc[t][0][8 * q + i] : 0.f;
         return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
     };
-    auto positive_bits = [&](int t) -> uint32_t {
-        uint32_t bits = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) bits |= (acc[t][0][i] > 0.f ? 1u : 0u) << i;
-        return bits;
-    };
-    uint32_t umask[MTW], mmask[MTW];
-#pragma unroll
-    for (int t = 0; t < MTW; ++t) umask[t] = mmask[t] = 0;
-
-    __syncthreads();
-
-    // ---- two-argument functions: u = ReLU(conv1x1(concat(arg0, arg1)) + b1), built in the tile; saved for dW_a
-    if (binary) {
-        const bf16_t* w1row[NT] = {a.pk1 + frag1 * FRAG + lane * 8};
-        const bf16_t* w1row2[NT] = {w1row[0] + 8 * FRAG};
-        bf16x8 ring1[8][NT];
-        ring_fill<NT, 8>(ring1, w1row);
-        init_acc(a.b1);
-        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, w1row, w1row2);
-        __syncthreads();
-        stage_load(map_of(it.src1));
-        stage_store();
-        __syncthreads();
-        kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, w1row2, w1row2);
-        __syncthreads();
-#pragma unroll
-        for (int t = 0; t < MTW; ++t) {
-            umask[t] = positive_bits(t);
-            if (t * 32 + r < P) {
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const u32x4 pk = packed_relu(t, q);
-                    *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
-                    *reinterpret_cast<u32x4*>(a.sv_u + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-    // ---- mid = ReLU(conv_a(u) + b_a): its mask stays in registers, the map is saved for dW_b
-    ring_fill<NT, RW>(ring, wrow_a);
-    init_acc(a.b3a);
-    kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_a, wrow_bT);   // leaves the ring filled for the next convolution
-#pragma unroll
-    for (int t = 0; t < MTW; ++t) {
-        mmask[t] = positive_bits(t);
-        if (t * 32 + r < P) {
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-                *reinterpret_cast<u32x4*>(a.sv_m + item_off + size_t(t * 32 + r) * C + chan + q * 8) = packed_relu(t, q);
-        }
-    }
-    __syncthreads();                                                  // every wave has read the last of u
-
-    // ---- g = gy * [y > 0] as bf16 into the tile, saved for dW_b and db_b
-    {
-        const f32x4* gy4 = reinterpret_cast<const f32x4*>(a.gy + item_off);
-        const u32x4* y4 = reinterpret_cast<const u32x4*>(it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C));
-        u32x4* sg4 = reinterpret_cast<u32x4*>(a.sv_g + item_off);
-        f32x4 glo[NIT], ghi[NIT];
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = tid + i * NTHR;
-            if (c < P * 16) { glo[i] = gy4[2 * c]; ghi[i] = gy4[2 * c + 1]; tmp[i] = y4[c]; }
-        }
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = tid + i * NTHR;
-            if (c < P * 16) {
-                auto on_lo = [](uint32_t w) { return bf16_lo_positive(w); };
-                auto on_hi = [](uint32_t w) { return bf16_hi_positive(w); };
-                const u32x4 yv = tmp[i];
-                u32x4 pk;
-                pk.x = pack_bf16x2(on_lo(yv.x) ? glo[i].x : 0.f, on_hi(yv.x) ? glo[i].y : 0.f);
-                pk.y = pack_bf16x2(on_lo(yv.y) ? glo[i].z : 0.f, on_hi(yv.y) ? glo[i].w : 0.f);
-                pk.z = pack_bf16x2(on_lo(yv.z) ? ghi[i].x : 0.f, on_hi(yv.z) ? ghi[i].y : 0.f);
-                pk.w = pack_bf16x2(on_lo(yv.w) ? ghi[i].z : 0.f, on_hi(yv.w) ? ghi[i].w : 0.f);
-                *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = pk;
-                sg4[c] = pk;
-            }
-        }
-    }
     __syncthreads();
 
     // ---- dmid = conv(g; W_b flipped, transposed) * [mid > 0], written into the tile in place of g
-    init_acc(nullptr);
+    uint32_t mmask[MTW];
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) mmask[t] = mask_bits(a.sv_m + item_off, t);   // (the loads return under the loop)
+    zero_acc();
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_bT, wrow_aT);
     __syncthreads();
 #pragma unroll
@@ -522,30 +444,29 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     // ---- du = g + conv(dmid; W_a flipped, transposed).  The residual term is added in fp32 from the gradient map
     // itself, not from its bf16 copy in the tile: down a chain of modules the convolution's share is small against
     // the residual's and would vanish below the bfloat16 quantum of the latter at every level.
-    init_acc(nullptr);
+    uint32_t umask[MTW];
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) umask[t] = binary ? mask_bits(a.sv_u + item_off, t) : 0u;
+    zero_acc();
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_aT, wrow_aT);
-    {
-        const float* gyp = a.gy + item_off;
-        const bf16_t* yp = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 #pragma unroll
-        for (int t = 0; t < MTW; ++t)
-            if (t * 32 + r < P) {
-                const size_t e = size_t(t * 32 + r) * C + chan;
+    for (int t = 0; t < MTW; ++t)
+        if (t * 32 + r < P) {
+            const size_t e = size_t(t * 32 + r) * C + chan;
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const u32x4 yv = *reinterpret_cast<const u32x4*>(yp + e + q * 8);
-                    const f32x4 g0 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8), g1 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8 + 4);
-                    acc[t][0][8 * q + 0] += bf16_lo_positive(yv.x) ? g0.x : 0.f;
-                    acc[t][0][8 * q + 1] += bf16_hi_positive(yv.x) ? g0.y : 0.f;
-                    acc[t][0][8 * q + 2] += bf16_lo_positive(yv.y) ? g0.z : 0.f;
-                    acc[t][0][8 * q + 3] += bf16_hi_positive(yv.y) ? g0.w : 0.f;
-                    acc[t][0][8 * q + 4] += bf16_lo_positive(yv.z) ? g1.x : 0.f;
-                    acc[t][0][8 * q + 5] += bf16_hi_positive(yv.z) ? g1.y : 0.f;
-                    acc[t][0][8 * q + 6] += bf16_lo_positive(yv.w) ? g1.z : 0.f;
-                    acc[t][0][8 * q + 7] += bf16_hi_positive(yv.w) ? g1.w : 0.f;
-                }
+            for (int q = 0; q < 2; ++q) {
+                const u32x4 yv = *reinterpret_cast<const u32x4*>(yp + e + q * 8);
+                const f32x4 g0 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8), g1 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8 + 4);
+                acc[t][0][8 * q + 0] += bf16_lo_positive(yv.x) ? g0.x : 0.f;
+                acc[t][0][8 * q + 1] += bf16_hi_positive(yv.x) ? g0.y : 0.f;
+                acc[t][0][8 * q + 2] += bf16_lo_positive(yv.y) ? g0.z : 0.f;
+                acc[t][0][8 * q + 3] += bf16_hi_positive(yv.y) ? g0.w : 0.f;
+                acc[t][0][8 * q + 4] += bf16_lo_positive(yv.z) ? g1.x : 0.f;
+                acc[t][0][8 * q + 5] += bf16_hi_positive(yv.z) ? g1.y : 0.f;
+                acc[t][0][8 * q + 6] += bf16_lo_positive(yv.w) ? g1.z : 0.f;
+                acc[t][0][8 * q + 7] += bf16_hi_positive(yv.w) ? g1.w : 0.f;
             }
-    }
+        }
     auto store_grad = [&](float* dst) {                               // the accumulators as an fp32 map
 #pragma unroll
         for (int t = 0; t < MTW; ++t)
@@ -578,31 +499,33 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
         const bf16_t* t1row2[NT] = {t1row[0] + 8 * FRAG};
         bf16x8 ring1[8][NT];
         ring_fill<NT, 8>(ring1, t1row);
-        init_acc(nullptr);
+        zero_acc();
         kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row, t1row2);
         store_grad(route_mf(a, a.gdst0[logical]));
-        init_acc(nullptr);
+        zero_acc();
         kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row2, t1row2);
         store_grad(route_mf(a, a.gdst1[logical]));
     }
 }
 
-// Parameter gradients of every function, one workgroup per (function, part):
-//   MODE 0: conv_b, part = kernel row kh:  dW_b[co][kh][kw][ci] = sum_items sum_p g[p][co]    mid[p + (kh-1, kw-1)][ci]
-//   MODE 1: conv_a, part = kernel row kh:  dW_a[co][kh][kw][ci] = sum_items sum_p dmid[p][co] u[p + (kh-1, kw-1)][ci]
-//   MODE 2: conv1x1, part = argument:      dW_1[co][part*C + ci] = sum_items sum_p dc[p][co]  arg_part[p][ci]
+// Parameter gradients.  A unit of work sums one chunk of a function's items for one (mode, part):
+//   mode 0: conv_b, part = kernel row kh:  dW_b[co][kh][kw][ci] = sum_items sum_p g[p][co]    mid[p + (kh-1, kw-1)][ci]
+//   mode 1: conv_a, part = kernel row kh:  dW_a[co][kh][kw][ci] = sum_items sum_p dmid[p][co] u[p + (kh-1, kw-1)][ci]
+//   mode 2: conv1x1, part = argument:      dW_1[co][part*C + ci] = sum_items sum_p dc[p][co]  arg_part[p][ci]
 // and with part 0 the bias gradient, the sum of g / dmid / dc over items and pixels.
 // The contraction runs over pixels, the dimension in which neither map is contiguous.  Both maps of an item are
 // copied into LDS halo tiles (pixel-major like the forward pass's tile) and the MFMA operands are read from
 // there two bytes at a time: lane (m, hk) of an operand fragment holds channel m of the 8 pixels x = 8 hk .. 8 hk + 7
 // of image row y, one K step per image row (x = 14, 15 are zeros).  For a kernel row the three taps' fragments of the
-// input map are the same 10 pixels shifted by one, so they are read once.  D[ci][co] accumulates in registers over
-// all items of the function, in item order; nothing is atomic.  The bias gradient is the same contraction with
-// a fragment of ones in place of the input map.
+// input map are the same 10 pixels shifted by one, so they are read once.  The reads of row y + 1 are issued ahead of
+// the MFMAs of row y and packed into fragments behind them.  D[ci][co] accumulates in registers over the unit's items, in item order, and is written to the
+// unit's partial result; k_bwd_wgrad_sum adds the partial results of a (function, part) in chunk order.  Nothing is
+// atomic.  The bias gradient is the same contraction with a fragment of ones in place of the input map.
 struct WgArgs {
     const dynb_item* items;       // all items of the plan
     const uint8_t* arity;
-    const int32_t* fn_first;
+    const dynb_wg_unit* units;
+    const int32_t* order;         // workgroup -> unit
     const int32_t* fn_items;
     const bf16_t* feats;
     const bf16_t* slots;
@@ -611,19 +534,18 @@ struct WgArgs {
     const bf16_t* sv_g;
     const bf16_t* sv_dm;
     const bf16_t* sv_dc;
-    float* dw;                    // the mode's weight gradient
-    float* db;                    // the mode's bias gradient
+    float* partial;               // [unit][3][C][C] weight gradient ([tap][co][ci]; conv1x1: tap 0 only), then [C] bias gradient
 };
+constexpr size_t WG_PARTIAL = size_t(3) * 128 * 128 + 128;           // floats per unit
 
 template <int MODE>
-__global__ __launch_bounds__(256, 1) void k_bwd_wgrad_mfma(WgArgs a)
+__device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit un, float* __restrict__ part_out)
 {
     using namespace mf;
-    constexpr int NPART = MODE == 2 ? 2 : 3, NTAP = MODE == 2 ? 1 : 3, NV = MODE == 2 ? 8 : 10, NTHR = 256;
+    constexpr int NTAP = MODE == 2 ? 1 : 3, NV = MODE == 2 ? 8 : 10, NTHR = 256;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const int t = blockIdx.x / NPART, part = blockIdx.x % NPART;
-    const int ar = a.arity[t];
-    if (ar == 0 || (MODE == 2 && ar != 2)) return;
+    const int part = un.part;
+    const int ar = a.arity[un.type];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int m = lane & 31, hk = lane >> 5, wi = wave & 1, wj = wave >> 1;
     constexpr uint32_t TILE_G = TILE_BYTES;                            // the gradient map's tile follows the input map's
@@ -685,55 +607,103 @@ __global__ __launch_bounds__(256, 1) void k_bwd_wgrad_mfma(WgArgs a)
     const uint32_t g_lane = TILE_G + uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wj * 64 + m) * 2);
     const uint32_t in_lane = MODE == 2 ? uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wi * 64 + m) * 2)
                                        : uint32_t(part * ROW_BYTES + (8 * hk) * PIX_BYTES + (wi * 64 + m) * 2);
-
-    const int n_begin = a.fn_first[t], n_end = a.fn_first[t + 1];
-    if (n_begin < n_end) load(n_begin);
-    for (int idx = n_begin; idx < n_end; ++idx) {
-        __syncthreads();                                              // the previous item's fragments have been read
-        store();
-        __syncthreads();
-        if (idx + 1 < n_end) load(idx + 1);                           // arrives under this item's MFMAs
-#pragma unroll 2
-        for (int y = 0; y < S; ++y) {
-            bf16x8 gf[2], inf[2][NTAP];
+    struct Raw { uint32_t g[2][8]; uint32_t in[2][NV]; };              // one row's 16-bit values as they come from LDS
+    struct Row { bf16x8 gf[2]; bf16x8 inf[2][NTAP]; };                 // ... and packed into operand fragments
+    // The upper lane half's last pixels do not exist (x = 14, 15) or lie beyond the tile (conv3x3 input, tile columns
+    // 16, 17): those lanes read their first pixel again and the value is replaced by zero when the fragment is packed.
+    // The gradient fragment is zero there, so what the input fragment holds only has to be a finite number.
+    constexpr int GLIM = 6, ILIM = MODE == 2 ? 6 : 8;
+    const uint32_t g_off6 = hk ? 0u : 6u * PIX_BYTES, g_off7 = hk ? 0u : 7u * PIX_BYTES;
+    const uint32_t in_offa = hk ? 0u : uint32_t(ILIM) * PIX_BYTES, in_offb = hk ? 0u : uint32_t(ILIM + 1) * PIX_BYTES;
+    auto issue_row = [&](int y, Raw& rw) {
+        const uint32_t gb = g_lane + uint32_t(y * ROW_BYTES), ib = in_lane + uint32_t(y * ROW_BYTES);
+        const uint32_t g6 = gb + g_off6, g7 = gb + g_off7, ia = ib + in_offa, ibb = ib + in_offb;
 #pragma unroll
-            for (int cj = 0; cj < 2; ++cj) {
-                uint32_t v[8];
+        for (int cj = 0; cj < 2; ++cj) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    // pixels x = 14, 15 do not exist: the last two values of the upper lane half are zeros
-                    const uint32_t raw = rd16(g_lane + uint32_t(y * ROW_BYTES + cj * 64 + (i < 6 ? i : (hk ? 0 : i)) * PIX_BYTES));
-                    v[i] = (i >= 6 && hk) ? 0u : raw;
-                }
-                gf[cj] = frag_of(v);
-            }
+            for (int i = 0; i < GLIM; ++i) rw.g[cj][i] = rd16(gb + uint32_t(cj * 64 + i * PIX_BYTES));
+            rw.g[cj][6] = rd16(g6 + uint32_t(cj * 64));
+            rw.g[cj][7] = rd16(g7 + uint32_t(cj * 64));
+        }
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                uint32_t v[NV];
+        for (int ct = 0; ct < 2; ++ct) {
 #pragma unroll
-                for (int i = 0; i < NV; ++i) {
-                    // the upper lane half's pixels end at tile column 15 (conv3x3) / image column 13 (conv1x1); what
-                    // lies beyond only ever meets the zeros of the gradient fragment, but must be a finite number
-                    const int lim = MODE == 2 ? 6 : 8;
-                    const uint32_t raw = rd16(in_lane + uint32_t(y * ROW_BYTES + ct * 64 + (i < lim ? i : (hk ? 0 : i)) * PIX_BYTES));
-                    v[i] = (i >= lim && hk) ? 0u : raw;
-                }
+            for (int i = 0; i < ILIM; ++i) rw.in[ct][i] = rd16(ib + uint32_t(ct * 64 + i * PIX_BYTES));
+            rw.in[ct][ILIM] = rd16(ia + uint32_t(ct * 64));
+            rw.in[ct][ILIM + 1] = rd16(ibb + uint32_t(ct * 64));
+        }
+    };
+    auto pack_row = [&](const Raw& rw, Row& row) {
 #pragma unroll
-                for (int k = 0; k < NTAP; ++k) inf[ct][k] = frag_of(v + k);
-            }
+        for (int cj = 0; cj < 2; ++cj) {
+            uint32_t v[8];
 #pragma unroll
-            for (int k = 0; k < NTAP; ++k)
+            for (int i = 0; i < 8; ++i) v[i] = (i >= GLIM && hk) ? 0u : rw.g[cj][i];
+            row.gf[cj] = frag_of(v);
+        }
 #pragma unroll
-                for (int ct = 0; ct < 2; ++ct)
+        for (int ct = 0; ct < 2; ++ct) {
+            uint32_t v[NV];
 #pragma unroll
-                    for (int cj = 0; cj < 2; ++cj)
-                        acc[k][ct][cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(inf[ct][k], gf[cj], acc[k][ct][cj], 0, 0, 0);
-            if (part == 0 && wi == 0) {
+            for (int i = 0; i < NV; ++i) v[i] = (i >= ILIM && hk) ? 0u : rw.in[ct][i];
 #pragma unroll
-                for (int cj = 0; cj < 2; ++cj) accb[cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, gf[cj], accb[cj], 0, 0, 0);
+            for (int k = 0; k < NTAP; ++k) row.inf[ct][k] = frag_of(v + k);
+        }
+    };
+    const bool with_bias = part == 0 && wi == 0;                      // uniform over the wave
+    auto mfma_row = [&](const Row& rw, auto WB) {
+#pragma unroll
+        for (int k = 0; k < NTAP; ++k)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int cj = 0; cj < 2; ++cj)
+                    acc[k][ct][cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rw.inf[ct][k], rw.gf[cj], acc[k][ct][cj], 0, 0, 0);
+        if constexpr (decltype(WB)::value) {
+#pragma unroll
+            for (int cj = 0; cj < 2; ++cj) accb[cj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, rw.gf[cj], accb[cj], 0, 0, 0);
+        }
+    };
+    // One step of the row pipeline: the LDS reads of the row after next are issued first, then the MFMAs of row `cur`
+    // run with the packing of row `nxt` (whose reads were issued a step earlier) spread between them: a wave issues one
+    // instruction at a time, and only what it issues while an MFMA executes is free.
+    auto step = [&](int y_issue, Raw& raw_issue, const Raw& raw_pack, Row& nxt, const Row& cur, auto WB) {
+        issue_row(y_issue, raw_issue);
+        mfma_row(cur, WB);
+        pack_row(raw_pack, nxt);
+        constexpr int NMF = NTAP * 4 + (decltype(WB)::value ? 2 : 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * 8 + 2 * NV, 0);          // all reads
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                        // their addresses were computed before
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, MODE == 2 ? 12 : 8, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto items = [&](auto WB) {
+        load(un.begin);
+        for (int idx = un.begin; idx < un.end; ++idx) {
+            __syncthreads();                                          // the previous item's fragments have been read
+            store();
+            __syncthreads();
+            if (idx + 1 < un.end) load(idx + 1);                      // arrives under this item's MFMAs
+            Raw r0, r1;
+            Row ra, rb;
+            issue_row(0, r0);
+            issue_row(1, r1);
+            pack_row(r0, ra);
+            __builtin_amdgcn_sched_barrier(0);
+            // rows y and y + 1 per trip: r1 holds row y + 1 on entry, ra row y
+#pragma unroll 1
+            for (int y = 0; y < S; y += 2) {
+                step(y + 2 < S ? y + 2 : y, r0, r1, rb, ra, WB);      // reads row y+2, MFMAs row y, packs row y+1
+                step(y + 3 < S ? y + 3 : y, r1, r0, ra, rb, WB);      // reads row y+3, MFMAs row y+1, packs row y+2
             }
         }
-    }
+    };
+    if (with_bias) items(std::true_type{});
+    else items(std::false_type{});
     // D[ci][co]: this lane holds co = wj*64 + cj*32 + m and ci = wi*64 + ct*32 + 8 b + 4 hk + (0..3) in elements 4 b .. 4 b + 3
 #pragma unroll
     for (int cj = 0; cj < 2; ++cj) {
@@ -745,11 +715,51 @@ __global__ __launch_bounds__(256, 1) void k_bwd_wgrad_mfma(WgArgs a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const int ci = wi * 64 + ct * 32 + 8 * b + 4 * hk;
-                    float* dst = MODE == 2 ? a.dw + (size_t(t) * C + co) * (2 * C) + part * C + ci
-                                           : a.dw + ((size_t(t) * C + co) * 9 + part * 3 + k) * C + ci;
-                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[k][ct][cj][4 * b], acc[k][ct][cj][4 * b + 1], acc[k][ct][cj][4 * b + 2], acc[k][ct][cj][4 * b + 3]};
+                    *reinterpret_cast<f32x4*>(part_out + (size_t(k) * C + co) * C + ci) =
+                        f32x4{acc[k][ct][cj][4 * b], acc[k][ct][cj][4 * b + 1], acc[k][ct][cj][4 * b + 2], acc[k][ct][cj][4 * b + 3]};
                 }
-        if (part == 0 && wi == 0 && hk == 0) a.db[size_t(t) * C + co] = accb[cj][0];
+        if (with_bias && hk == 0) part_out[size_t(3) * C * C + co] = accb[cj][0];
+    }
+}
+
+__global__ __launch_bounds__(256, 1) void k_bwd_wgrad_mfma(WgArgs a)
+{
+    const int32_t u = a.order[blockIdx.x];
+    const dynb_wg_unit un = a.units[u];
+    float* out = a.partial + size_t(u) * WG_PARTIAL;
+    if (un.mode == 0) wgrad_unit<0>(a, un, out);
+    else if (un.mode == 1) wgrad_unit<1>(a, un, out);
+    else wgrad_unit<2>(a, un, out);
+}
+
+// dW / db of one (mode, function, part) = its units' partial results added in chunk order
+struct WsArgs {
+    const dynb_wg_group* groups;
+    const float* partial;
+    float* dw3a; float* db3a; float* dw3b; float* db3b; float* dw1; float* db1;
+};
+
+__global__ void k_bwd_wgrad_sum(WsArgs a)
+{
+    constexpr int C = 128;
+    const dynb_wg_group g = a.groups[blockIdx.y];
+    const int ntap = g.mode == 2 ? 1 : 3;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;              // float4 index inside [tap][co][ci]
+    if (e < ntap * C * C / 4) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < g.n_units; ++c) {
+            const f32x4 v = reinterpret_cast<const f32x4*>(a.partial + size_t(g.first_unit + c) * WG_PARTIAL)[e];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        const int ci = (e * 4) % C, co = (e * 4 / C) % C, k = e * 4 / (C * C);
+        float* dst = g.mode == 2 ? a.dw1 + (size_t(g.type) * C + co) * (2 * C) + g.part * C + ci
+                                 : (g.mode == 0 ? a.dw3b : a.dw3a) + ((size_t(g.type) * C + co) * 9 + g.part * 3 + k) * C + ci;
+        *reinterpret_cast<f32x4*>(dst) = s;
+    }
+    if (g.part == 0 && blockIdx.x == 0 && threadIdx.x < C) {
+        float s = 0.f;
+        for (int c = 0; c < g.n_units; ++c) s += a.partial[size_t(g.first_unit + c) * WG_PARTIAL + size_t(3) * C * C + threadIdx.x];
+        (g.mode == 2 ? a.db1 : g.mode == 0 ? a.db3b : a.db3a)[size_t(g.type) * C + threadIdx.x] = s;
     }
 }
 
@@ -886,8 +896,8 @@ bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 1
 
 // workspace of the MFMA path
 struct BmLayout {
-    size_t gy, gleaf, sv_u, sv_m, sv_g, sv_dm, sv_dc, pk3a, pk1, pk3bT, pk3aT, pk1T;
-    size_t t_gdst0, t_gdst1, t_leaf_first, t_root_item, t_fn_first, t_fn_items, total;
+    size_t gy, gleaf, sv_g, sv_dm, sv_dc, pk3bT, pk3aT, pk1T;
+    size_t partial, t_gdst0, t_gdst1, t_leaf_first, t_root_item, t_fn_items, t_units, t_groups, t_order, total;
 };
 
 BmLayout bm_layout(const dynb_plan* p)
@@ -899,13 +909,9 @@ BmLayout bm_layout(const dynb_plan* p)
     auto take = [&](size_t bytes) { size_t at = o; o += align256(std::max<size_t>(bytes, 4)); return at; };
     L.gy = take(n_items * chw * 4);
     L.gleaf = take(n_leaf * chw * 4);
-    L.sv_u = take(p->has_binary ? n_items * chw * 2 : 0);
-    L.sv_m = take(n_items * chw * 2);
     L.sv_g = take(n_items * chw * 2);
     L.sv_dm = take(n_items * chw * 2);
     L.sv_dc = take(p->has_binary ? n_items * chw * 2 : 0);
-    L.pk3a = take(nt * 9 * 128 * 128 * 2);
-    L.pk1 = take(nt * 2 * 128 * 128 * 2);
     L.pk3bT = take(nt * 9 * 128 * 128 * 2);
     L.pk3aT = take(nt * 9 * 128 * 128 * 2);
     L.pk1T = take(nt * 2 * 128 * 128 * 2);
@@ -913,8 +919,11 @@ BmLayout bm_layout(const dynb_plan* p)
     L.t_gdst1 = take(n_items * 4);
     L.t_leaf_first = take((size_t(p->B) + 1) * 4);
     L.t_root_item = take(size_t(p->B) * 4);
-    L.t_fn_first = take((nt + 1) * 4);
     L.t_fn_items = take(n_items * 4);
+    L.partial = take(p->wg_units.size() * WG_PARTIAL * 4);
+    L.t_units = take(p->wg_units.size() * sizeof(dynb_wg_unit));
+    L.t_groups = take(p->wg_groups.size() * sizeof(dynb_wg_group));
+    L.t_order = take(p->wg_order.size() * 4);
     L.total = o;
     return L;
 }
@@ -926,18 +935,14 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
     if (!(attr_set.load() >> (dev & 63) & 1)) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<8>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<24>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_bwd_node_mfma)");
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<0>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
-                "hipFuncSetAttribute(k_bwd_wgrad_mfma<0>)");
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<1>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
-                "hipFuncSetAttribute(k_bwd_wgrad_mfma<1>)");
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
-                "hipFuncSetAttribute(k_bwd_wgrad_mfma<2>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_bwd_wgrad_mfma)");
         attr_set.fetch_or(uint64_t(1) << (dev & 63));
     }
     const BmLayout L = bm_layout(p);
-    const size_t chw = size_t(mf::P) * mf::C;
+    const size_t chw = size_t(mf::P) * mf::C, n_items_all = p->items.size();
     const int C = mf::C, B = p->B, nt = p->n_types;
     auto table = [&](size_t at, const std::vector<int32_t>& v) -> hipError_t {
         return v.empty() ? hipSuccess : hipMemcpyAsync(ws + at, v.data(), v.size() * 4, hipMemcpyHostToDevice, st);
@@ -946,8 +951,14 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     HIP_TRY(table(L.t_gdst1, p->grad_dst1), "dynbatch_backward(tables)");
     HIP_TRY(table(L.t_leaf_first, p->leaf_first), "dynbatch_backward(tables)");
     HIP_TRY(table(L.t_root_item, p->root_item), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_fn_first, p->fn_first), "dynbatch_backward(tables)");
     HIP_TRY(table(L.t_fn_items, p->fn_items), "dynbatch_backward(tables)");
+    HIP_TRY(table(L.t_order, p->wg_order), "dynbatch_backward(tables)");
+    if (!p->wg_units.empty())
+        HIP_TRY(hipMemcpyAsync(ws + L.t_units, p->wg_units.data(), p->wg_units.size() * sizeof(dynb_wg_unit), hipMemcpyHostToDevice, st),
+                "dynbatch_backward(tables)");
+    if (!p->wg_groups.empty())
+        HIP_TRY(hipMemcpyAsync(ws + L.t_groups, p->wg_groups.data(), p->wg_groups.size() * sizeof(dynb_wg_group), hipMemcpyHostToDevice, st),
+                "dynbatch_backward(tables)");
     const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(ws + L.t_leaf_first);
     const int32_t* d_root_item = reinterpret_cast<const int32_t*>(ws + L.t_root_item);
 
@@ -964,10 +975,9 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
         hipLaunchKernelGGL(k_bwd_pack, dim3(unsigned(std::min<size_t>((pieces + 255) / 256, 4096))), dim3(256), 0, st,
                            static_cast<const bf16_t*>(src), reinterpret_cast<u32x4*>(ws + at), nt, ntap, mode);
     };
-    pack(w->w3a, L.pk3a, 9, 0);
     pack(w->w3b, L.pk3bT, 9, 1);
     pack(w->w3a, L.pk3aT, 9, 1);
-    if (p->has_binary) { pack(w->w1, L.pk1, 2, 2); pack(w->w1, L.pk1T, 2, 3); }
+    if (p->has_binary) pack(w->w1, L.pk1T, 2, 3);
 
     float* gy = reinterpret_cast<float*>(ws + L.gy);
     const unsigned bx_map = unsigned(std::min<size_t>((chw + 255) / 256, 64));
@@ -981,12 +991,12 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     BmArgs a;
     a.arity = d_arity;
     a.feats = static_cast<const bf16_t*>(feats); a.out = static_cast<const bf16_t*>(out); a.slots = static_cast<const bf16_t*>(fwd_ws);
-    a.pk3a = reinterpret_cast<const bf16_t*>(ws + L.pk3a); a.pk1 = reinterpret_cast<const bf16_t*>(ws + L.pk1);
     a.pk3bT = reinterpret_cast<const bf16_t*>(ws + L.pk3bT); a.pk3aT = reinterpret_cast<const bf16_t*>(ws + L.pk3aT);
     a.pk1T = reinterpret_cast<const bf16_t*>(ws + L.pk1T);
-    a.b1 = w->b1; a.b3a = w->b3a;
     a.gy = gy; a.gleaf = reinterpret_cast<float*>(ws + L.gleaf);
-    a.sv_u = reinterpret_cast<bf16_t*>(ws + L.sv_u); a.sv_m = reinterpret_cast<bf16_t*>(ws + L.sv_m);
+    // u and mid of every item: where the forward pass of a DYNB_PLAN_KEEP plan put them
+    a.sv_m = reinterpret_cast<const bf16_t*>(static_cast<const char*>(fwd_ws) + dynb_fast_keep_offset(p));
+    a.sv_u = a.sv_m + n_items_all * chw;
     a.sv_g = reinterpret_cast<bf16_t*>(ws + L.sv_g); a.sv_dm = reinterpret_cast<bf16_t*>(ws + L.sv_dm);
     a.sv_dc = reinterpret_cast<bf16_t*>(ws + L.sv_dc);
     for (size_t li = p->launches.size(); li-- > 0;) {
@@ -995,21 +1005,24 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
         a.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + l.start;
         a.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + l.start;
         const unsigned grid = unsigned((l.count + 7) / 8 * 8);
-        hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        hipLaunchKernelGGL((k_bwd_node_mfma<24>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
     }
-    WgArgs q;
-    q.items = d_items; q.arity = d_arity;
-    q.fn_first = reinterpret_cast<const int32_t*>(ws + L.t_fn_first);
-    q.fn_items = reinterpret_cast<const int32_t*>(ws + L.t_fn_items);
-    q.feats = a.feats; q.slots = a.slots;
-    q.sv_u = a.sv_u; q.sv_m = a.sv_m; q.sv_g = a.sv_g; q.sv_dm = a.sv_dm; q.sv_dc = a.sv_dc;
-    q.dw = g->dw3b; q.db = g->db3b;
-    hipLaunchKernelGGL((k_bwd_wgrad_mfma<0>), dim3(unsigned(nt) * 3), dim3(256), 2 * mf::TILE_BYTES, st, q);
-    q.dw = g->dw3a; q.db = g->db3a;
-    hipLaunchKernelGGL((k_bwd_wgrad_mfma<1>), dim3(unsigned(nt) * 3), dim3(256), 2 * mf::TILE_BYTES, st, q);
-    if (p->has_binary) {
-        q.dw = g->dw1; q.db = g->db1;
-        hipLaunchKernelGGL((k_bwd_wgrad_mfma<2>), dim3(unsigned(nt) * 2), dim3(256), 2 * mf::TILE_BYTES, st, q);
+    if (!p->wg_units.empty()) {
+        WgArgs q;
+        q.items = d_items; q.arity = d_arity;
+        q.units = reinterpret_cast<const dynb_wg_unit*>(ws + L.t_units);
+        q.order = reinterpret_cast<const int32_t*>(ws + L.t_order);
+        q.fn_items = reinterpret_cast<const int32_t*>(ws + L.t_fn_items);
+        q.feats = a.feats; q.slots = a.slots;
+        q.sv_u = a.sv_u; q.sv_m = a.sv_m; q.sv_g = a.sv_g; q.sv_dm = a.sv_dm; q.sv_dc = a.sv_dc;
+        q.partial = reinterpret_cast<float*>(ws + L.partial);
+        hipLaunchKernelGGL(k_bwd_wgrad_mfma, dim3(unsigned(p->wg_units.size())), dim3(256), 2 * mf::TILE_BYTES, st, q);
+        WsArgs r;
+        r.groups = reinterpret_cast<const dynb_wg_group*>(ws + L.t_groups);
+        r.partial = q.partial;
+        r.dw3a = g->dw3a; r.db3a = g->db3a; r.dw3b = g->dw3b; r.db3b = g->db3b; r.dw1 = g->dw1; r.db1 = g->db1;
+        // functions without items have groups without units: the sum writes their zeros
+        hipLaunchKernelGGL(k_bwd_wgrad_sum, dim3(3 * 128 * 128 / 4 / 256, unsigned(p->wg_groups.size())), dim3(256), 0, st, r);
     }
     for (int e0 = 0; e0 < B; e0 += 32768)
         hipLaunchKernelGGL(k_bwd_leaves, dim3(bx_map, unsigned(std::min(32768, B - e0))), dim3(256), 0, st, a.gleaf, d_leaf_first + e0,

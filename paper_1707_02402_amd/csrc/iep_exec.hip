@@ -76,6 +76,10 @@ struct MfArgs {
     const float* b3a;
     const bf16_t* w3b;
     const float* b3b;
+    // plans that keep what the backward pass needs: u of two-argument functions and mid, one map per item
+    int32_t first_item;       // index of items[0] in the plan
+    bf16_t* keep_u;           // [n_items][P*C]
+    bf16_t* keep_m;
 };
 
 
@@ -110,7 +114,8 @@ __global__ void k_pack_weights(const u32x4* __restrict__ src, u32x4* __restrict_
 // steps that is filled before the argument map is staged.
 // One workgroup's share of a launch group: position `logical` (a node, half a node or a pair of nodes,
 // depending on the layout) of the items a.items[0 .. a.count).
-template <int WMODE, bool ALLOW_DEEP = true>
+// KEEP: u (two-argument functions) and mid are also written to a.keep_u / a.keep_m, as they enter the LDS tile.
+template <int WMODE, bool ALLOW_DEEP = true, bool KEEP = false>
 __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 {
     using namespace mf;
@@ -287,9 +292,15 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                        for (int q = 0; q < 2; ++q)
+                        for (int q = 0; q < 2; ++q) {
+                            const u32x4 pk = packed(t, nt, q);
                             *reinterpret_cast<u32x4*>(lds_raw + uaddr[t] - uint32_t(h * 128) + CENTER +
-                                                      uint32_t((chan(nt) + q * 8) * 2)) = packed(t, nt, q);
+                                                      uint32_t((chan(nt) + q * 8) * 2)) = pk;
+                            // (half-node layouts: the two windows overlap; both write the same values there)
+                            if constexpr (KEEP)
+                                *reinterpret_cast<u32x4*>(a.keep_u + (size_t(a.first_item + first + node_local) * P + urow0 * S + t * 32 + r) * C +
+                                                          chan(nt) + q * 8) = pk;
+                        }
                 }
         }
         __syncthreads();
@@ -319,7 +330,11 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
         auto swap8 = [&](int t, int nt, int q, const f32x4& blo, const f32x4& bhi) {
             const uint32_t addr = centre(t) + uint32_t((chan(nt) + q * 8) * 2);
             const u32x4 res = *reinterpret_cast<const u32x4*>(lds_raw + addr);
-            *reinterpret_cast<u32x4*>(lds_raw + addr) = packed(t, nt, q);
+            const u32x4 pk = packed(t, nt, q);
+            *reinterpret_cast<u32x4*>(lds_raw + addr) = pk;
+            if constexpr (KEEP)
+                *reinterpret_cast<u32x4*>(a.keep_m + (size_t(a.first_item + first + node_local) * P + wrow0 * S + t * 32 + r) * C +
+                                          chan(nt) + q * 8) = pk;
             acc[t][nt][8 * q + 0] = __uint_as_float(res.x << 16) + blo.x;
             acc[t][nt][8 * q + 1] = __uint_as_float(res.x & 0xffff0000u) + blo.y;
             acc[t][nt][8 * q + 2] = __uint_as_float(res.y << 16) + blo.z;
@@ -365,14 +380,14 @@ __device__ __forceinline__ void module_body(const MfArgs& a, const int logical)
     PHASE(9);
 }
 
-template <int WMODE>
+template <int WMODE, bool KEEP = false>
 __global__ __launch_bounds__(256, WMODE == 4 ? 2 : 1) void k_module_mfma(MfArgs a)
 {
     // Workgroup -> position in the launch group.  Consecutive workgroup ids land on different
     // XCDs; give every XCD one contiguous run of items (items are sorted by function id) so that
     // a function's weights stay in as few L2s as possible.
     const int per_xcd = gridDim.x >> 3;
-    module_body<WMODE>(a, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3));
+    module_body<WMODE, true, KEEP>(a, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3));
 }
 
 // ---- one dependency-driven launch per batch ---------------------------------------------------------
@@ -466,8 +481,7 @@ bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 1
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
-// packed copies of w3a, w3b (9 taps each) and w1 (2 halves), 128 x 128 bf16 per tap and function
-size_t packed_weight_bytes(int n_types) { return size_t(n_types) * (9 + 9 + 2) * 128 * 128 * 2; }
+size_t packed_weight_bytes(int n_types) { return dynb_fast_packed_weight_bytes(n_types); }
 
 }  // namespace
 
@@ -493,12 +507,12 @@ extern "C" size_t dynbatch_plan_device_bytes(const dynb_plan* p)
 
 // Workspace tail of the dependency-driven launch: ready[n_slots] | counter | status (after the slots and,
 // without prepared weights, the packed weights)
-static size_t persist_sync_bytes(const dynb_plan* p) { return p->persistent ? align256((size_t(p->n_slots) + 2) * sizeof(int32_t)) : 0; }
+static size_t persist_sync_bytes(const dynb_plan* p) { return dynb_fast_sync_bytes(p); }
 
 // offset of that tail: behind the slots and the room for packed weights
 static size_t persist_sync_offset(const dynb_plan* p)
 {
-    return align256(size_t(p->n_slots) * mf::P * mf::C * 2) + align256(packed_weight_bytes(p->n_types));
+    return dynb_fast_sync_offset(p);
 }
 
 static std::atomic<int32_t> g_spin_limit{1 << 22};
@@ -541,6 +555,7 @@ extern "C" size_t dynbatch_workspace_bytes(const dynb_plan* p, const dynb_shape*
     size_t bytes = align256(n * map);
     if (fast_shape(s)) bytes += align256(packed_weight_bytes(p->n_types));    // weights in MFMA fragment order
     if (fast_shape(s)) bytes += persist_sync_bytes(p);                        // ready flags, ticket counter, status
+    if (fast_shape(s)) bytes += dynb_fast_keep_bytes(p);                      // u and mid of every item for the backward pass
     return std::max<size_t>(bytes, 256);
 }
 
@@ -623,6 +638,15 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<4>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_module_mfma<4>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<2, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<2, keep>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<3, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<3, keep>)");
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_module_mfma<4, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+                "hipFuncSetAttribute(k_module_mfma<4, keep>)");
         attr_set.fetch_or(uint64_t(1) << (dev & 63));
     }
     const char* d = static_cast<const char*>(p->dev_buf);
@@ -643,6 +667,12 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
     a.w1 = pk1; a.b1 = w->b1;
     a.w3a = pk3a; a.b3a = w->b3a;
     a.w3b = pk3b; a.b3b = w->b3b;
+    a.first_item = 0;
+    a.keep_u = a.keep_m = nullptr;
+    if (p->keep) {
+        a.keep_m = reinterpret_cast<bf16_t*>(ws + dynb_fast_keep_offset(p));
+        a.keep_u = a.keep_m + p->items.size() * size_t(mf::P) * mf::C;
+    }
     const bool timed = dynb::timing_on(), coarse = dynb::timing_coarse();
     if (p->persistent) {
         // one launch for the whole batch: clear the ready flags, the ticket counter and the status word with a
@@ -657,21 +687,26 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
         const size_t nsync = size_t(p->n_slots) + 2;
         hipLaunchKernelGGL(k_fill_i32, dim3(unsigned(std::min<size_t>((nsync + 255) / 256, 256))), dim3(256), 0, st, q.ready, nsync, 0);
         if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
-        a.items = reinterpret_cast<const dynb_item*>(d);
-        a.count = int32_t(p->items.size());
-        a.any_binary = 0;
-        const int resident = cu_count[dev & 63];              // one workgroup per CU (73 KB of LDS, all registers)
-        const unsigned grid = unsigned(std::min<int>(q.n_tickets, resident));
-        hipLaunchKernelGGL(k_module_persist, dim3(grid), dim3(256), mf::TILE_BYTES, st, a, q);
-        if (timed) dynb::timing_mark(st, 0, a.count);
-        HIP_TRY(hipGetLastError(), "dynbatch_execute(dependency-driven kernel)");
-        return DYNB_OK;
+        // a plan that also keeps u and mid for the backward pass runs one launch per label (below); its status
+        // word stays clear
+        if (!p->keep) {
+            a.items = reinterpret_cast<const dynb_item*>(d);
+            a.count = int32_t(p->items.size());
+            a.any_binary = 0;
+            const int resident = cu_count[dev & 63];          // one workgroup per CU (73 KB of LDS, all registers)
+            const unsigned grid = unsigned(std::min<int>(q.n_tickets, resident));
+            hipLaunchKernelGGL(k_module_persist, dim3(grid), dim3(256), mf::TILE_BYTES, st, a, q);
+            if (timed) dynb::timing_mark(st, 0, a.count);
+            HIP_TRY(hipGetLastError(), "dynbatch_execute(dependency-driven kernel)");
+            return DYNB_OK;
+        }
     }
-    if (timed) dynb::timing_mark(st, dynb::ST_SETUP, 0);
+    if (timed && !p->persistent) dynb::timing_mark(st, dynb::ST_SETUP, 0);
     int32_t evals = 0;
     for (const dynb_launch& l : p->launches) {
         evals += l.count;
         a.items = reinterpret_cast<const dynb_item*>(d) + l.start;
+        a.first_item = l.start;
         a.count = l.count;
         a.any_binary = l.any_binary;
         // half a node per workgroup while that still fits the chip's 256 CUs in one round, one node per
@@ -683,7 +718,14 @@ static int run_mfma(const dynb_plan* p, const dynb_module_weights* w, const void
 #endif
         const int nwg = (wm == 3) ? 2 * l.count : l.count;
         const unsigned grid = unsigned((nwg + 7) / 8 * 8);
-        if (wm == 4)
+        if (p->keep) {
+            if (wm == 4)
+                hipLaunchKernelGGL((k_module_mfma<4, true>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+            else if (wm == 3)
+                hipLaunchKernelGGL((k_module_mfma<3, true>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+            else
+                hipLaunchKernelGGL((k_module_mfma<2, true>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        } else if (wm == 4)
             hipLaunchKernelGGL((k_module_mfma<4>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
         else if (wm == 3)
             hipLaunchKernelGGL((k_module_mfma<3>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);

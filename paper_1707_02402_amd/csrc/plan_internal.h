@@ -24,6 +24,11 @@ struct dynb_launch {
     int32_t any_binary;  // some item of the group is a two-argument function (the kernels take the conv1x1 path)
 };
 
+// mode 0: second conv3x3 (part = kernel row), 1: first conv3x3 (part = kernel row), 2: conv1x1 (part = argument)
+constexpr int DYNB_WG_CHUNK = 16;
+struct dynb_wg_unit { int32_t mode, type, part, begin, end, pad0, pad1, pad2; };     // items fn_items[begin .. end)
+struct dynb_wg_group { int32_t mode, type, part, first_unit, n_units, pad0, pad1, pad2; };
+
 struct dynb_plan {
     int32_t B = 0, N = 0, D = 0, n_types = 0, mode = 0;
     std::vector<uint8_t> arity;
@@ -51,6 +56,11 @@ struct dynb_plan {
     std::vector<int32_t> root_item;      // [B] item that evaluates the example's root, -1 if the root is a SCENE leaf
     std::vector<int32_t> fn_first;       // [n_types+1] the items of function t are fn_items[fn_first[t] .. fn_first[t+1])
     std::vector<int32_t> fn_items;       // item indices grouped by function, ascending inside a function
+    // Work list of the parameter-gradient kernel: a function's items are cut into chunks of at most DYNB_WG_CHUNK so that
+    // the units fill the chip evenly; a unit sums one chunk for one (convolution, kernel row or argument).
+    std::vector<dynb_wg_unit> wg_units;  // grouped: the chunks of one (mode, function, part) are consecutive
+    std::vector<dynb_wg_group> wg_groups;
+    std::vector<int32_t> wg_order;       // unit indices, longest chunks first: the order in which workgroups take them
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };
@@ -61,6 +71,20 @@ inline size_t dynb_align256(size_t v) { return (v + 255) & ~size_t(255); }
 inline size_t dynb_plan_items_bytes(const dynb_plan* p) { return dynb_align256(p->items.size() * sizeof(dynb_item)); }
 inline size_t dynb_plan_leaf_bytes(const dynb_plan* p) { return dynb_align256(p->leaf_roots.size() * sizeof(int32_t)); }
 inline size_t dynb_plan_arity_offset(const dynb_plan* p) { return dynb_plan_items_bytes(p) + dynb_plan_leaf_bytes(p); }
+
+// Workspace of dynbatch_execute on the fused kernels' shape (bf16, C = 128, 14 x 14), in this order:
+//   slots | module weights in fragment order (w3a, w3b: 9 taps, w1: 2 halves; 128 x 128 bf16 per tap and function)
+//   | DYNB_PLAN_PERSISTENT: ready[n_slots], ticket counter, status word
+//   | DYNB_PLAN_KEEP: mid of every item, then u of every item (written for two-argument functions), for the backward pass
+inline size_t dynb_fast_map_bytes() { return size_t(14) * 14 * 128 * 2; }
+inline size_t dynb_fast_packed_weight_bytes(int n_types) { return size_t(n_types) * (9 + 9 + 2) * 128 * 128 * 2; }
+inline size_t dynb_fast_sync_offset(const dynb_plan* p)
+{
+    return dynb_align256(size_t(p->n_slots) * dynb_fast_map_bytes()) + dynb_align256(dynb_fast_packed_weight_bytes(p->n_types));
+}
+inline size_t dynb_fast_sync_bytes(const dynb_plan* p) { return p->persistent ? dynb_align256((size_t(p->n_slots) + 2) * sizeof(int32_t)) : 0; }
+inline size_t dynb_fast_keep_offset(const dynb_plan* p) { return dynb_fast_sync_offset(p) + dynb_fast_sync_bytes(p); }
+inline size_t dynb_fast_keep_bytes(const dynb_plan* p) { return p->keep ? dynb_align256(2 * p->items.size() * dynb_fast_map_bytes()) : 0; }
 
 namespace dynb {
 void set_error(const std::string& msg);

@@ -341,6 +341,43 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         p->fn_items.resize(p->items.size());
         std::vector<int32_t> at(p->fn_first.begin(), p->fn_first.end() - 1);
         for (size_t i = 0; i < p->items.size(); ++i) p->fn_items[at[p->items[i].type]++] = int32_t(i);
+        // units of the parameter-gradient kernel
+        for (int32_t mode = 0; mode < 3; ++mode)
+            for (int32_t t = 0; t < p->n_types; ++t) {
+                if (arity[t] == 0 || (mode == 2 && arity[t] != 2)) continue;
+                const int32_t lo = p->fn_first[t], hi = p->fn_first[t + 1];
+                for (int32_t part = 0; part < (mode == 2 ? 2 : 3); ++part) {
+                    dynb_wg_group g{mode, t, part, int32_t(p->wg_units.size()), 0, 0, 0, 0};
+                    for (int32_t b = lo; b < hi; b += DYNB_WG_CHUNK) {
+                        p->wg_units.push_back(dynb_wg_unit{mode, t, part, b, std::min(hi, b + DYNB_WG_CHUNK), 0, 0, 0});
+                        ++g.n_units;
+                    }
+                    p->wg_groups.push_back(g);                     // a function without items has no units: its gradient is zero
+                }
+            }
+        // Order in which workgroups take the units: chunks with the most items first (a short tail), and the parts of
+        // one chunk (its kernel rows / arguments read the same maps) 8 workgroups apart: consecutive workgroups go
+        // to the chip's 8 dies in turn, so those parts run on one die at the same time and share its L2.
+        struct Chunk { int32_t first_group, n_parts, chunk, work; };
+        std::vector<Chunk> chunks;
+        for (size_t gi = 0; gi < p->wg_groups.size();) {
+            const dynb_wg_group& g0 = p->wg_groups[gi];
+            const int32_t n_parts = g0.mode == 2 ? 2 : 3;
+            for (int32_t c = 0; c < g0.n_units; ++c) {
+                const dynb_wg_unit& u = p->wg_units[g0.first_unit + c];
+                chunks.push_back(Chunk{int32_t(gi), n_parts, c, (u.end - u.begin) * (g0.mode == 2 ? 1 : 3)});
+            }
+            gi += size_t(n_parts);
+        }
+        std::stable_sort(chunks.begin(), chunks.end(), [](const Chunk& a, const Chunk& b) {
+            return a.n_parts != b.n_parts ? a.n_parts > b.n_parts : a.work > b.work;
+        });
+        p->wg_order.clear();
+        for (size_t b0 = 0; b0 < chunks.size(); b0 += 8)
+            for (int32_t part = 0; part < 3; ++part)
+                for (size_t x = b0; x < std::min(chunks.size(), b0 + 8); ++x)
+                    if (part < chunks[x].n_parts)
+                        p->wg_order.push_back(p->wg_groups[size_t(chunks[x].first_group) + part].first_unit + chunks[x].chunk);
     }
     // 4. units of work of the dependency-driven launch, in claim order = execution order of the items
     // (arguments always come earlier in it).  Groups that leave half of the chip idle are run with two
