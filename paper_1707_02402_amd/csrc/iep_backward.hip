@@ -423,9 +423,12 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     __syncthreads();
 
     // ---- dmid = conv(g; W_b flipped, transposed) * [mid > 0], written into the tile in place of g
-    uint32_t mmask[MTW];
+    uint32_t mmask[MTW], ymask[MTW];
 #pragma unroll
-    for (int t = 0; t < MTW; ++t) mmask[t] = mask_bits(a.sv_m + item_off, t);   // (the loads return under the loop)
+    for (int t = 0; t < MTW; ++t) {                                   // (the loads return under the loop)
+        mmask[t] = mask_bits(a.sv_m + item_off, t);
+        ymask[t] = mask_bits(yp, t);
+    }
     zero_acc();
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_bT, wrow_aT);
     __syncthreads();
@@ -447,24 +450,35 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     uint32_t umask[MTW];
 #pragma unroll
     for (int t = 0; t < MTW; ++t) umask[t] = binary ? mask_bits(a.sv_u + item_off, t) : 0u;
+    // (this lane's part of gy for the first pixel tiles is requested before the loop and arrives under it; the
+    // registers do not hold more)
+    constexpr int NPRE = 3;
+    f32x4 rg[NPRE][4];
+    auto gy_at = [&](int t, int b) -> f32x4 {
+        return *reinterpret_cast<const f32x4*>(gyp + size_t(min(t * 32 + r, P - 1)) * C + chan + 4 * b);
+    };
+#pragma unroll
+    for (int t = 0; t < NPRE; ++t)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) rg[t][b] = gy_at(t, b);
     zero_acc();
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_aT, wrow_aT);
+    f32x4 rl[MTW - NPRE][4];
+#pragma unroll
+    for (int t = NPRE; t < MTW; ++t)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) rl[t - NPRE][b] = gy_at(t, b);
 #pragma unroll
     for (int t = 0; t < MTW; ++t)
         if (t * 32 + r < P) {
-            const size_t e = size_t(t * 32 + r) * C + chan;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const u32x4 yv = *reinterpret_cast<const u32x4*>(yp + e + q * 8);
-                const f32x4 g0 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8), g1 = *reinterpret_cast<const f32x4*>(gyp + e + q * 8 + 4);
-                acc[t][0][8 * q + 0] += bf16_lo_positive(yv.x) ? g0.x : 0.f;
-                acc[t][0][8 * q + 1] += bf16_hi_positive(yv.x) ? g0.y : 0.f;
-                acc[t][0][8 * q + 2] += bf16_lo_positive(yv.y) ? g0.z : 0.f;
-                acc[t][0][8 * q + 3] += bf16_hi_positive(yv.y) ? g0.w : 0.f;
-                acc[t][0][8 * q + 4] += bf16_lo_positive(yv.z) ? g1.x : 0.f;
-                acc[t][0][8 * q + 5] += bf16_hi_positive(yv.z) ? g1.y : 0.f;
-                acc[t][0][8 * q + 6] += bf16_lo_positive(yv.w) ? g1.z : 0.f;
-                acc[t][0][8 * q + 7] += bf16_hi_positive(yv.w) ? g1.w : 0.f;
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t bits = ymask[t] >> (4 * b);
+                const f32x4 v = t < NPRE ? rg[t < NPRE ? t : 0][b] : rl[t < NPRE ? 0 : t - NPRE][b];
+                acc[t][0][4 * b + 0] += bits & 1u ? v.x : 0.f;
+                acc[t][0][4 * b + 1] += bits & 2u ? v.y : 0.f;
+                acc[t][0][4 * b + 2] += bits & 4u ? v.z : 0.f;
+                acc[t][0][4 * b + 3] += bits & 8u ? v.w : 0.f;
             }
         }
     auto store_grad = [&](float* dst) {                               // the accumulators as an fp32 map
@@ -596,8 +610,9 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
         }
     };
     auto rd16 = [&](uint32_t addr) -> uint32_t { return *reinterpret_cast<const uint16_t*>(lds_raw + addr); };
-    auto frag_of = [](const uint32_t* v) -> bf16x8 {
-        const u32x4 w = {v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+    auto frag_of = [](const uint32_t* v) -> bf16x8 {                   // eight zero-extended 16-bit values -> 8 bf16, one v_perm per pair
+        auto pair = [](uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x05040100u); };
+        const u32x4 w = {pair(v[0], v[1]), pair(v[2], v[3]), pair(v[4], v[5]), pair(v[6], v[7])};
         return __builtin_bit_cast(bf16x8, w);
     };
     const u32x4 ones_w = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
@@ -610,19 +625,20 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
     struct Raw { uint32_t g[2][8]; uint32_t in[2][NV]; };              // one row's 16-bit values as they come from LDS
     struct Row { bf16x8 gf[2]; bf16x8 inf[2][NTAP]; };                 // ... and packed into operand fragments
     // The upper lane half's last pixels do not exist (x = 14, 15) or lie beyond the tile (conv3x3 input, tile columns
-    // 16, 17): those lanes read their first pixel again and the value is replaced by zero when the fragment is packed.
-    // The gradient fragment is zero there, so what the input fragment holds only has to be a finite number.
-    constexpr int GLIM = 6, ILIM = MODE == 2 ? 6 : 8;
-    const uint32_t g_off6 = hk ? 0u : 6u * PIX_BYTES, g_off7 = hk ? 0u : 7u * PIX_BYTES;
-    const uint32_t in_offa = hk ? 0u : uint32_t(ILIM) * PIX_BYTES, in_offb = hk ? 0u : uint32_t(ILIM + 1) * PIX_BYTES;
+    // 16, 17).  Tile column 15 is the zero border: the gradient map's x = 14 is that column already, and the lanes
+    // whose pixel would lie beyond it read column 15 again, so every such value is a zero without any select.
+    constexpr int ILIM = MODE == 2 ? 7 : 8;                            // first index of an input value beyond column 15
+    const uint32_t g_off7 = (hk ? 6u : 7u) * PIX_BYTES;
+    const uint32_t in_offa = (hk ? uint32_t(ILIM - 1) : uint32_t(ILIM)) * PIX_BYTES;
+    const uint32_t in_offb = (hk ? uint32_t(ILIM - 1) : uint32_t(ILIM + 1)) * PIX_BYTES;
+    const uint32_t g_lane7 = g_lane + g_off7, in_lanea = in_lane + in_offa, in_laneb = in_lane + in_offb;
     auto issue_row = [&](int y, Raw& rw) {
-        const uint32_t gb = g_lane + uint32_t(y * ROW_BYTES), ib = in_lane + uint32_t(y * ROW_BYTES);
-        const uint32_t g6 = gb + g_off6, g7 = gb + g_off7, ia = ib + in_offa, ibb = ib + in_offb;
+        const uint32_t yo = uint32_t(y * ROW_BYTES);
+        const uint32_t gb = g_lane + yo, g7 = g_lane7 + yo, ib = in_lane + yo, ia = in_lanea + yo, ibb = in_laneb + yo;
 #pragma unroll
         for (int cj = 0; cj < 2; ++cj) {
 #pragma unroll
-            for (int i = 0; i < GLIM; ++i) rw.g[cj][i] = rd16(gb + uint32_t(cj * 64 + i * PIX_BYTES));
-            rw.g[cj][6] = rd16(g6 + uint32_t(cj * 64));
+            for (int i = 0; i < 7; ++i) rw.g[cj][i] = rd16(gb + uint32_t(cj * 64 + i * PIX_BYTES));
             rw.g[cj][7] = rd16(g7 + uint32_t(cj * 64));
         }
 #pragma unroll
@@ -630,25 +646,16 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
 #pragma unroll
             for (int i = 0; i < ILIM; ++i) rw.in[ct][i] = rd16(ib + uint32_t(ct * 64 + i * PIX_BYTES));
             rw.in[ct][ILIM] = rd16(ia + uint32_t(ct * 64));
-            rw.in[ct][ILIM + 1] = rd16(ibb + uint32_t(ct * 64));
+            if (ILIM + 1 < NV) rw.in[ct][ILIM + 1 < NV ? ILIM + 1 : 0] = rd16(ibb + uint32_t(ct * 64));
         }
     };
     auto pack_row = [&](const Raw& rw, Row& row) {
 #pragma unroll
-        for (int cj = 0; cj < 2; ++cj) {
-            uint32_t v[8];
+        for (int cj = 0; cj < 2; ++cj) row.gf[cj] = frag_of(rw.g[cj]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = (i >= GLIM && hk) ? 0u : rw.g[cj][i];
-            row.gf[cj] = frag_of(v);
-        }
+        for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-            uint32_t v[NV];
-#pragma unroll
-            for (int i = 0; i < NV; ++i) v[i] = (i >= ILIM && hk) ? 0u : rw.in[ct][i];
-#pragma unroll
-            for (int k = 0; k < NTAP; ++k) row.inf[ct][k] = frag_of(v + k);
-        }
+            for (int k = 0; k < NTAP; ++k) row.inf[ct][k] = frag_of(rw.in[ct] + k);
     };
     const bool with_bias = part == 0 && wi == 0;                      // uniform over the wave
     auto mfma_row = [&](const Row& rw, auto WB) {
@@ -673,11 +680,11 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
         pack_row(raw_pack, nxt);
         constexpr int NMF = NTAP * 4 + (decltype(WB)::value ? 2 : 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * 8 + 2 * NV, 0);          // all reads
-        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                        // their addresses were computed before
+        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                        // (their addresses)
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, MODE == 2 ? 12 : 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, MODE == 2 ? 8 : 4, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -935,7 +942,7 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
     if (!(attr_set.load() >> (dev & 63) & 1)) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<24>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<8>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_bwd_node_mfma)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_bwd_wgrad_mfma)");
@@ -1005,7 +1012,7 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
         a.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + l.start;
         a.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + l.start;
         const unsigned grid = unsigned((l.count + 7) / 8 * 8);
-        hipLaunchKernelGGL((k_bwd_node_mfma<24>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
     }
     if (!p->wg_units.empty()) {
         WgArgs q;
