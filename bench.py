@@ -82,11 +82,18 @@ def main():
     K, Wm, NW = args.steps, args.warmup, max(1, args.windows)
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
 
-    def gpu_ms(fn, reps):
-        """Mean GPU time of fn() over reps calls, from one HIP event pair on the current stream."""
+    def gpu_ms(fn, reps, warm_ms=0.0):
+        """Mean GPU time of fn() over reps calls, from one HIP event pair on the current stream.  warm_ms: keep the
+        GPU busy with fn() for about that long first (after an idle spell the card takes some 20 ms of load to reach
+        the clock it then holds; a single warm-up call measures the ramp)."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         fn()
         torch.cuda.synchronize()
+        t_w = time.perf_counter()
+        while (time.perf_counter() - t_w) * 1e3 < warm_ms:
+            for _ in range(4):
+                fn()
+            torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
             fn()
@@ -293,15 +300,17 @@ def main():
         wfeats = L0["feats"].repeat((nw + w.B - 1) // w.B, 1, 1, 1)[:nw].contiguous()
         wout = torch.empty_like(wfeats)
         wide = {"nodes": nw, "programs": "one one-argument module per program, the %d one-argument functions in turn" % n_un}
-        for name, fl_ in (("throughput layout (two workgroups per CU)", dyn.DYNB_PLAN_THROUGHPUT), ("latency layouts", 0)):
-            wplan = dyn.dynbatch_plan(wprog, woff, w.arity, fl_)
-            dyn.dynbatch_plan_upload(wplan)
-            wws = torch.empty(dyn.dynbatch_workspace_bytes(wplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
-            ms_ = gpu_ms(lambda: dyn.dynbatch_execute(wplan, weights, wfeats, wout, wws), K)
-            tf = nw * FLOP_UNARY / ms_ / 1e9
-            wide[name] = {"ms": round(ms_, 4), "tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
-                          "frac_of_measured_peak": None if peak is None else round(tf / peak["mfma_bf16_tflops"], 4)}
-            del wws, wplan
+        # (a launch group wider than the chip runs the two-workgroups-per-CU layout whatever the plan's flags)
+        wplan = dyn.dynbatch_plan(wprog, woff, w.arity, 0)
+        dyn.dynbatch_plan_upload(wplan)
+        wws = torch.empty(dyn.dynbatch_workspace_bytes(wplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+        ms_ = gpu_ms(lambda: dyn.dynbatch_execute(wplan, weights, wfeats, wout, wws), K, warm_ms=40.0)
+        tf = nw * FLOP_UNARY / ms_ / 1e9
+        wide.update({"kernel": "k_module_mfma<4> (two workgroups per CU)", "ms": round(ms_, 4), "tflops": round(tf, 1),
+                     "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                     "frac_of_measured_peak": None if peak is None else round(tf / peak["mfma_bf16_tflops"], 4),
+                     "warm_up": "40 ms of the same launches before the timed ones"})
+        del wws, wplan
         del wfeats, wout
 
     # ------------------------------------------------------------------ classifier head and backward pass (config 2)
@@ -324,7 +333,7 @@ def main():
         dout = torch.randn(kout.shape, dtype=torch.float32, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
         bws = torch.empty(dyn.dynbatch_backward_workspace_bytes(kplan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
         grads = dyn.dynbatch_backward(kplan, weights, L0["feats"], kout, kws, dout, workspace=bws)
-        bwd_ms = gpu_ms(lambda: dyn.dynbatch_backward(kplan, weights, L0["feats"], kout, kws, dout, workspace=bws, grads=grads), max(K // 5, 3))
+        bwd_ms = gpu_ms(lambda: dyn.dynbatch_backward(kplan, weights, L0["feats"], kout, kws, dout, workspace=bws, grads=grads), max(K // 5, 3), warm_ms=20.0)
         kfwd_ms = gpu_ms(lambda: dyn.dynbatch_execute(kplan, weights, L0["feats"], out=kout, workspace=kws), K)
         # two transposed convolutions and two weight-gradient contractions per module: twice the forward pass's flops
         # (the recomputation of u and mid, half a forward pass, is not counted as useful work)
@@ -333,9 +342,10 @@ def main():
                               "flops": 2.0 * flops_step, "tflops": round(2.0 * flops_step / bwd_ms / 1e9, 1),
                               "frac_of_mfma_peak": round(2.0 * flops_step / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
                               "workspace_mb": round(bws.numel() / 1e6, 1),
-                              "kind": "MFMA kernels: one fused launch per label in reverse order (recomputes u and mid, both "
-                                      "transposed convolutions, fp32 gradient maps), then one launch per convolution for the "
-                                      "parameter gradients of all functions; forward = the same plan (DYNB_PLAN_KEEP: a slot per node)"}
+                              "kind": "MFMA kernels: one fused launch per label in reverse order (both transposed convolutions, "
+                                      "fp32 gradient maps), then one launch for the parameter gradients of all functions and one that "
+                                      "sums their partial results; forward = the same plan (DYNB_PLAN_KEEP: a slot per node, u and mid "
+                                      "of every node saved)"}
         del bws, grads
         del kws, kout, dout, kplan
 
