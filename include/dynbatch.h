@@ -140,6 +140,20 @@ typedef struct {
     int32_t n_tickets;           /* DYNB_PLAN_PERSISTENT: units of work of the single launch, else 0 */
     const int32_t* tickets;      /* [n_tickets] in claim order: 4 * item + part; part 0 = the whole
                                     node, 1 / 2 = its upper / lower half                         */
+    /* DYNB_PLAN_KEEP: what the backward pass works from (NULL / 0 otherwise).                     */
+    const int32_t* grad_dst0;    /* [n_compute_nodes] where the gradient of an item's first argument goes:
+                                    >= 0 the item that evaluates the argument, -1 - l the SCENE leaf number l
+                                    (leaves are numbered example by example in node order)         */
+    const int32_t* grad_dst1;    /* [n_compute_nodes] same for the second argument (0 if there is none) */
+    const int32_t* fn_first;     /* [n_types + 1] the items of function t are fn_items[fn_first[t] ..
+                                    fn_first[t+1]), ascending                                      */
+    const int32_t* fn_items;     /* [n_compute_nodes]                                             */
+    int32_t n_types;
+    int32_t n_wg_units;          /* units of work of the parameter-gradient kernel                */
+    const int32_t* wg_units;     /* [n_wg_units][8]: mode (0 second conv3x3, 1 first conv3x3, 2 conv1x1),
+                                    function, part (kernel row, or argument for mode 2), begin, end (a chunk
+                                    fn_items[begin .. end) of at most 16 items), 3 unused            */
+    const int32_t* wg_order;     /* [n_wg_units] unit taken by every workgroup of that kernel     */
 } dynb_plan_view;
 
 /* Builds the plan for a minibatch of programs (Background / Visual Reasoning Programs: the fixed

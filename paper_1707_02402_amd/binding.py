@@ -49,7 +49,9 @@ class _PlanView(ct.Structure):
                [(n, I32P) for n in ("node_level", "node_type", "child0", "child1", "root", "bucket_level",
                                     "bucket_type", "bucket_start", "bucket_count", "members", "in0", "in1", "out",
                                     "node_launch", "item_node")] + \
-               [("n_tickets", ct.c_int32), ("tickets", I32P)]
+               [("n_tickets", ct.c_int32), ("tickets", I32P)] + \
+               [(n, I32P) for n in ("grad_dst0", "grad_dst1", "fn_first", "fn_items")] + \
+               [("n_types", ct.c_int32), ("n_wg_units", ct.c_int32), ("wg_units", I32P), ("wg_order", I32P)]
 
 
 class _Shape(ct.Structure):
@@ -225,7 +227,14 @@ def dynbatch_plan_view(plan: Plan) -> SimpleNamespace:
         bucket_type=arr(v.bucket_type, nb), bucket_start=arr(v.bucket_start, nb),
         bucket_count=arr(v.bucket_count, nb), members=arr(v.members, N), in0=arr(v.in0, N), in1=arr(v.in1, N),
         out=arr(v.out, N), node_launch=arr(v.node_launch, N), item_node=arr(v.item_node, v.n_compute_nodes),
-        n_tickets=v.n_tickets, tickets=arr(v.tickets, v.n_tickets))
+        n_tickets=v.n_tickets, tickets=arr(v.tickets, v.n_tickets),
+        grad_dst0=arr(v.grad_dst0, v.n_compute_nodes if v.grad_dst0 else 0),
+        grad_dst1=arr(v.grad_dst1, v.n_compute_nodes if v.grad_dst1 else 0),
+        fn_first=arr(v.fn_first, v.n_types + 1 if v.fn_first else 0),
+        fn_items=arr(v.fn_items, v.n_compute_nodes if v.fn_items else 0),
+        n_types=v.n_types, n_wg_units=v.n_wg_units,
+        wg_units=arr(v.wg_units, 8 * v.n_wg_units if v.wg_units else 0).reshape(-1, 8),
+        wg_order=arr(v.wg_order, v.n_wg_units if v.wg_order else 0))
 
 
 def dynbatch_plan_device_bytes(plan: Plan) -> int:

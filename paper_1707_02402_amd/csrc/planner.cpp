@@ -628,6 +628,15 @@ extern "C" int dynbatch_plan_view(const dynb_plan* p, dynb_plan_view* v)
     v->item_node = p->item_node.data();
     v->n_tickets = int32_t(p->tickets.size());
     v->tickets = p->tickets.data();
+    v->grad_dst0 = p->keep ? p->grad_dst0.data() : nullptr;
+    v->grad_dst1 = p->keep ? p->grad_dst1.data() : nullptr;
+    v->fn_first = p->keep ? p->fn_first.data() : nullptr;
+    v->fn_items = p->keep ? p->fn_items.data() : nullptr;
+    v->n_types = p->n_types;
+    v->n_wg_units = int32_t(p->wg_units.size());
+    static_assert(sizeof(dynb_wg_unit) == 8 * sizeof(int32_t), "a unit is eight integers");
+    v->wg_units = p->wg_units.empty() ? nullptr : reinterpret_cast<const int32_t*>(p->wg_units.data());
+    v->wg_order = p->wg_order.empty() ? nullptr : p->wg_order.data();
     return DYNB_OK;
 }
 

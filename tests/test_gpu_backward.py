@@ -210,6 +210,26 @@ def test_config2_full_batch_against_the_oracle_on_sampled_examples(dyn, util, or
     assert (got["dfeats"][rest] == 0).all()
 
 
+def test_keep_plans_with_the_persistent_flag(dyn, util):
+    """A plan that keeps u and mid for the backward pass runs one launch per label even if one dependency-driven
+    launch was asked for; its status word reads "no wait expired" and its backward pass gives the same bits."""
+    import torch
+    w = iep.small_mixed(seed=23, B=5, C=128, H=14, W=14, dtype="bf16", min_len=1, max_len=6)
+    dout = np.random.default_rng(1).standard_normal(w.feats.shape).astype(np.float32)
+    ref, out0 = run_backward(dyn, util, w, dout, dyn.DYNB_PLAN_BALANCE)
+    got, out1 = run_backward(dyn, util, w, dout, dyn.DYNB_PLAN_PERSISTENT)
+    assert (out0 == out1).all()
+    for name in NAMES:
+        assert (got[name] == ref[name]).all(), name
+    plan = dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_PLAN_PERSISTENT | dyn.DYNB_PLAN_KEEP)
+    dyn.dynbatch_plan_upload(plan)
+    feats = util.to_dev(w.feats, w.dtype)
+    ws = torch.empty(dyn.dynbatch_workspace_bytes(plan, w.C, w.H, w.W, dyn.DYNB_BF16), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xff)
+    dyn.dynbatch_execute(plan, util.iep_weights_dev(w), feats, workspace=ws)
+    dyn.dynbatch_execute_check(plan, feats, ws)
+
+
 def test_closed_form_identity_kernels(dyn, util):
     """Chains of n doubling modules on positive maps: dL/dx = 2^n dout, exactly."""
     C, H, W = 8, 4, 4

@@ -262,3 +262,57 @@ def test_persistent_schedule_simulated_with_few_and_many_workers(dyn):
                 heapq.heappush(free_at, (end, wid))
                 done += 1
             assert done == v.n_tickets
+
+
+def test_backward_tables_of_a_keep_plan(dyn):
+    """DYNB_PLAN_KEEP: gradient routes, per-function item lists and the work units of the parameter-gradient kernel."""
+    w = iep.config2()
+    v = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_PLAN_BALANCE | dyn.DYNB_PLAN_KEEP))
+    n_items, arity = v.n_compute_nodes, w.arity
+    item_of = np.full(v.n_nodes, -1)
+    item_of[v.item_node] = np.arange(n_items)
+    assert v.n_slots == n_items - (item_of[v.root] >= 0).sum()           # every result but the roots (they go to `out`) keeps a slot of its own
+    # routes: an argument that is a module goes to the item that evaluates it; SCENE leaves are numbered in node order
+    leaf_no = np.cumsum(arity[v.node_type] == 0) - 1
+    for dst, child in ((v.grad_dst0, v.child0), (v.grad_dst1, v.child1)):
+        c = child[v.item_node]
+        has = c >= 0
+        is_leaf = has & (arity[v.node_type[np.maximum(c, 0)]] == 0)
+        assert (dst[has & ~is_leaf] == item_of[c[has & ~is_leaf]]).all()
+        assert (dst[is_leaf] == -1 - leaf_no[c[is_leaf]]).all()
+    # every module result but the roots is routed to exactly once (a tree: one consumer per node)
+    routed = np.concatenate([v.grad_dst0[v.grad_dst0 >= 0], v.grad_dst1[(v.grad_dst1 >= 0) & (arity[v.node_type[v.item_node]] == 2)]])
+    assert len(np.unique(routed)) == len(routed) == n_items - (item_of[v.root] >= 0).sum()
+    # items of a function, ascending
+    types = v.node_type[v.item_node]
+    for t in range(v.n_types):
+        mine = v.fn_items[v.fn_first[t]:v.fn_first[t + 1]]
+        assert (mine == np.flatnonzero(types == t)).all()
+    # work units: per (mode, function, part) the chunks tile the function's item list, at most 16 items each
+    assert sorted(v.wg_order) == list(range(v.n_wg_units))
+    cover = {}
+    for mode, t, part, b, e in v.wg_units[:, :5]:
+        assert 0 < e - b <= 16 and v.fn_first[t] <= b and e <= v.fn_first[t + 1]
+        assert arity[t] == 2 if mode == 2 else arity[t] >= 1
+        assert 0 <= part < (2 if mode == 2 else 3)
+        cover.setdefault((mode, t, part), []).append((b, e))
+    for t in range(v.n_types):
+        for mode in range(3):
+            wanted = arity[t] >= 1 and (mode != 2 or arity[t] == 2) and v.fn_first[t + 1] > v.fn_first[t]
+            for part in range(2 if mode == 2 else 3):
+                chunks = cover.get((mode, t, part), [])
+                assert bool(chunks) == bool(wanted)
+                if chunks:
+                    assert chunks[0][0] == v.fn_first[t] and chunks[-1][1] == v.fn_first[t + 1]
+                    assert all(a[1] == b[0] for a, b in zip(chunks, chunks[1:]))
+    # the parts of one chunk are taken by workgroups 8 apart (they run on one die at the same time)
+    pos = np.empty(v.n_wg_units, np.int64)
+    pos[v.wg_order] = np.arange(v.n_wg_units)
+    key = {tuple(u[[0, 1, 3]]): {} for u in v.wg_units}
+    for i, u in enumerate(v.wg_units):
+        key[tuple(u[[0, 1, 3]])][u[2]] = pos[i]
+    apart = [p[1] - p[0] for p in key.values()]
+    assert np.mean(np.array(apart) == 8) > 0.95
+    # without the flag there are no such tables
+    v0 = dyn.dynbatch_plan_view(dyn.dynbatch_plan(w.prog, w.prog_off, w.arity, dyn.DYNB_PLAN_BALANCE))
+    assert v0.n_wg_units == 0 and len(v0.fn_items) == 0 and len(v0.grad_dst0) == 0
