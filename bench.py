@@ -115,12 +115,17 @@ def main():
             fl[0] = dyn.dynb_probe_mfma_bf16(4000, 256 * 2 * 4, sink)      # 8 waves per SIMD-set keep the pipes full
 
         mfma_ms = gpu_ms(mfma_probe, 5)
+        rsink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        read_ms = gpu_ms(lambda: dyn.dynb_probe_read(cal_src, rsink), 10, warm_ms=10.0)
         peak = {"mfma_bf16_tflops": round(fl[0] / mfma_ms / 1e9, 1),
                 "mfma_bf16_frac_of_published": round(fl[0] / mfma_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
                 "mfma_kind": "register-only loop of independent v_mfma_f32_32x32x16_bf16, 2048 workgroups x 4 waves (dynb_probe_mfma_bf16)",
                 "copy_gbs": round(2 * cal_src.numel() * 4 / copy_ms / 1e6, 1),
                 "copy_frac_of_published": round(2 * cal_src.numel() * 4 / copy_ms / 1e6 / PEAK_HBM_GBS, 4),
-                "copy_kind": "1 GiB read + 1 GiB written by a plain 16-byte copy kernel (dynb_probe_copy)"}
+                "copy_kind": "1 GiB read + 1 GiB written by a plain 16-byte copy kernel (dynb_probe_copy)",
+                "read_gbs": round(cal_src.numel() * 4 / read_ms / 1e6, 1),
+                "read_frac_of_published": round(cal_src.numel() * 4 / read_ms / 1e6 / PEAK_HBM_GBS, 4),
+                "read_kind": "1 GiB read, nothing written, 16-byte loads, 8 in flight per lane (dynb_probe_read)"}
     del cal_src, cal_dst
 
     # ------------------------------------------------------------------ program-tree engine

@@ -29,7 +29,7 @@ EXPORTS = ["dynb_last_error", "dynbatch_plan", "dynbatch_plan_dag", "dynbatch_pl
            "dynbatch_packed_weights_bytes", "dynbatch_pack_weights",
            "dynbatch_classify_workspace_bytes", "dynbatch_classify", "dynbatch_backward_workspace_bytes", "dynbatch_backward",
            "dynbatch_execute", "dynbatch_execute_check", "dynb_set_spin_limit", "moe_workspace_bytes", "moe_forward", "moe_forward_static", "moe_forward_naive",
-           "dynb_timing_enable", "dynb_probe_mfma_bf16", "dynb_probe_copy",
+           "dynb_timing_enable", "dynb_probe_mfma_bf16", "dynb_probe_copy", "dynb_probe_read",
            "dynb_timing_read"]
 
 
@@ -128,6 +128,7 @@ def _load():
     L.moe_forward_static.argtypes = L.moe_forward.argtypes[:9] + [ct.c_void_p]
     L.dynb_probe_mfma_bf16.argtypes = [ct.c_int32, ct.c_int32, ct.c_void_p, ct.c_void_p, ct.POINTER(ct.c_double)]
     L.dynb_probe_copy.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_size_t, ct.c_void_p]
+    L.dynb_probe_read.argtypes = [ct.c_void_p, ct.c_size_t, ct.c_void_p, ct.c_void_p]
     L.dynb_timing_enable.argtypes = [ct.c_int]
     L.dynb_timing_read.argtypes = [ct.POINTER(_StageTime), ct.c_int32, ct.POINTER(ct.c_int32)]
     return L
@@ -503,6 +504,13 @@ def dynb_probe_mfma_bf16(iters: int, workgroups: int, sink, stream=None) -> floa
     fl = ct.c_double(0.0)
     _check(lib.dynb_probe_mfma_bf16(iters, workgroups, _ptr(sink), _stream(stream), ct.byref(fl)))
     return fl.value
+
+
+def dynb_probe_read(src, sink, stream=None) -> int:
+    """Reads all of `src` (device tensor) and stores nothing; returns the number of bytes read."""
+    n = src.numel() * src.element_size()
+    _check(lib.dynb_probe_read(_ptr(src), n, _ptr(sink), _stream(stream)))
+    return n
 
 
 def dynb_probe_copy(dst, src, stream=None) -> int:

@@ -5,6 +5,8 @@
 //     traffic at all): the dense bf16 rate the matrix pipes sustain at the clock the card settles at.
 //   * dynb_probe_copy: plain device-to-device copy with 16-byte accesses: achievable HBM bandwidth,
 //     and the known-size reference that the profiler's FETCH_SIZE / WRITE_SIZE counters are scaled by.
+//   * dynb_probe_read: the same accesses without the stores: what a kernel that only streams operands in
+//     (the expert layers' weights) can expect.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -51,7 +53,38 @@ __global__ __launch_bounds__(256) void k_probe_copy(const u32x4* __restrict__ sr
         dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void k_probe_read(const u32x4* __restrict__ src, uint32_t* __restrict__ sink, size_t n16)
+{
+    const size_t stride = size_t(gridDim.x) * blockDim.x;
+    size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n16; i += 8 * stride) {                  // eight loads in flight per lane
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc |= v[j];
+    }
+    for (; i < n16; i += stride) acc |= src[i];
+    if ((acc.x & acc.y & acc.z & acc.w) == 0xdeadbeefu) sink[0] = acc.x;   // keeps the loads alive; practically never taken
+}
+
 }  // namespace
+
+extern "C" int dynb_probe_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink) return fail(DYNB_E_INVAL, "dynb_probe_read: NULL argument");
+    if (bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16)
+        return fail(DYNB_E_INVAL, "dynb_probe_read: size and pointer must be multiples of 16 bytes");
+    if (bytes == 0) return DYNB_OK;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = unsigned(std::min<size_t>((n16 + 255) / 256, size_t(256) * 8));
+    hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(src), static_cast<uint32_t*>(sink), n16);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(DYNB_E_HIP, std::string("dynb_probe_read: ") + hipGetErrorString(e));
+    return DYNB_OK;
+}
 
 extern "C" int dynb_probe_mfma_bf16(int32_t iters, int32_t workgroups, float* sink, void* stream, double* flops)
 {
