@@ -92,7 +92,11 @@ enum {
      * bit-identical either way.  See dynbatch_execute_check for the bounded waits.                 */
     DYNB_PLAN_PERSISTENT = 16,
     /* Optional, any scheduling mode: keep every node's result (a slot of its own in the workspace, no
-     * reuse) so that dynbatch_backward can run after dynbatch_execute.  Larger workspace.         */
+     * reuse) so that dynbatch_backward can run after dynbatch_execute.  On the fast path (bf16, C = 128,
+     * 14 x 14) dynbatch_execute also saves the two intermediate maps of every node (the output of the 1x1
+     * convolution of two-argument functions and of the first 3x3 convolution) in the workspace, and a plan
+     * that also carries DYNB_PLAN_PERSISTENT runs one launch per label.  Larger workspace (three maps per
+     * node).  The plan view then lists the tables the backward pass works from.                     */
     DYNB_PLAN_KEEP = 32
 };
 
