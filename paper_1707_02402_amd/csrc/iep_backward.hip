@@ -257,6 +257,8 @@ __global__ void k_bwd_leaves(const float* __restrict__ gleaf, const int32_t* __r
 //   conv(dmid; W_a flipped^T)  -> du = that + g (the residual path, in fp32 from the gradient map), written as fp32
 //                                 to the argument's gradient map; two-argument functions: dc = du * [u > 0] into the
 //                                 tile, then two 1x1 convolutions with the halves of W_1^T
+// Everything that enters or leaves in the accumulator layout (masks, the residual term, results) goes through LDS so
+// that all global accesses are coalesced 16-byte pieces.
 // Gradients travel between nodes as fp32 maps and enter the MFMAs as bf16 (like every other operand of this
 // path).  g, dmid and dc are saved as bf16 maps per item for the parameter gradients, which one kernel sums
 // function by function afterwards.
@@ -322,6 +324,20 @@ __global__ void k_bwd_pack(const bf16_t* __restrict__ src, u32x4* __restrict__ d
     }
 }
 
+// LDS of the backward node kernel: the halo tile, one mask byte per 16-byte piece of the y and the mid map, and an
+// fp32 staging area through which accumulators (lane = pixel) leave as coalesced 16-byte pieces.  A global access in
+// which every lane touches a line of its own costs about 125 clocks to issue, so nothing is loaded or stored in the
+// accumulator layout: masks come from the LDS bytes, the residual term and the result go through the staging area.
+namespace bn {
+constexpr int MASK_OFF = mf::TILE_BYTES;                 // y mask bytes [P][16], then mid mask bytes [P][16]
+constexpr int MASK_BYTES = 2 * mf::P * 16 + 128;         // (+ padding to a multiple of 256)
+constexpr int STAGE_OFF = MASK_OFF + MASK_BYTES;
+constexpr int STAGE_PITCH = mf::C * 4 + 16;              // bytes per pixel: 128 floats + a bank-shifting pad
+constexpr int STAGE_PIX = 128;                           // pixels per round: four pixel tiles
+constexpr int LDS_BYTES = STAGE_OFF + STAGE_PIX * STAGE_PITCH;
+static_assert(MASK_BYTES % 256 == 0 && LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+}  // namespace bn
+
 template <int RW>
 __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
 {
@@ -333,6 +349,12 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
     if (logical >= a.count) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r = lane & 31, h = lane >> 5, n0 = wave * 32;
+#ifdef DYNB_NODE_CLOCKS
+    long long tck[10], tck0 = clock64();
+#define NCLK(i) tck[i] = clock64() - tck0
+#else
+#define NCLK(i) do {} while (0)
+#endif
     const dynb_item it = a.items[logical];
     const bool binary = a.arity[it.type] == 2;                        // uniform over the workgroup
     const size_t item_off = size_t(a.first_item + logical) * (P * C);
@@ -346,10 +368,19 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
         const int p = c >> 4, part = c & 15;
         return uint32_t((p / S + 1) * ROW_BYTES + (p % S + 1) * PIX_BYTES + part * 16);
     };
+    // bit i of the result: element i of the piece is positive
+    auto piece_mask = [](const u32x4& v) -> uint32_t {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t bits = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bits |= (bf16_lo_positive(w[i]) ? 1u : 0u) << (2 * i) | (bf16_hi_positive(w[i]) ? 1u : 0u) << (2 * i + 1);
+        return bits;
+    };
     const float* gyp = a.gy + item_off;
     const bf16_t* yp = it.dst >= 0 ? a.slots + size_t(it.dst) * (P * C) : a.out + size_t(-1 - it.dst) * (P * C);
 
-    // ---- g = gy * [y > 0] as bf16 into the tile, saved for dW_b and db_b; all loads are issued before the first use
+    // ---- g = gy * [y > 0] as bf16 into the tile, saved for dW_b and db_b; mask bytes of y and mid; all loads are
+    // issued before the first use
     constexpr int NIT = (P * 16 + NTHR - 1) / NTHR;
     {
         const f32x4* gy4 = reinterpret_cast<const f32x4*>(gyp);
@@ -376,14 +407,15 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
         for (int i = 0; i < NIT; ++i) {
             const int c = tid + i * NTHR;
             if (c < P * 16) {
-                const u32x4 y = yv[i];
+                const uint32_t yb = piece_mask(yv[i]);
                 u32x4 pk;
-                pk.x = pack_bf16x2(bf16_lo_positive(y.x) ? glo[i].x : 0.f, bf16_hi_positive(y.x) ? glo[i].y : 0.f);
-                pk.y = pack_bf16x2(bf16_lo_positive(y.y) ? glo[i].z : 0.f, bf16_hi_positive(y.y) ? glo[i].w : 0.f);
-                pk.z = pack_bf16x2(bf16_lo_positive(y.z) ? ghi[i].x : 0.f, bf16_hi_positive(y.z) ? ghi[i].y : 0.f);
-                pk.w = pack_bf16x2(bf16_lo_positive(y.w) ? ghi[i].z : 0.f, bf16_hi_positive(y.w) ? ghi[i].w : 0.f);
+                pk.x = pack_bf16x2(yb & 1u ? glo[i].x : 0.f, yb & 2u ? glo[i].y : 0.f);
+                pk.y = pack_bf16x2(yb & 4u ? glo[i].z : 0.f, yb & 8u ? glo[i].w : 0.f);
+                pk.z = pack_bf16x2(yb & 16u ? ghi[i].x : 0.f, yb & 32u ? ghi[i].y : 0.f);
+                pk.w = pack_bf16x2(yb & 64u ? ghi[i].z : 0.f, yb & 128u ? ghi[i].w : 0.f);
                 *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = pk;
                 sg4[c] = pk;
+                lds_raw[bn::MASK_OFF + c] = static_cast<unsigned char>(yb);
             }
         }
     }
@@ -403,16 +435,6 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
             for (int i = 0; i < 16; ++i) acc[t][0][i] = 0.f;
     };
     auto centre = [&](int t) -> uint32_t { return xaddr[t] - uint32_t(h * 128) + CENTER; };
-    // the 16 mask bits [v > 0] of this lane's channels of pixel tile t of a saved bf16 map
-    auto mask_bits = [&](const bf16_t* map, int t) -> uint32_t {
-        const u32x4 lo = *reinterpret_cast<const u32x4*>(map + size_t(min(t * 32 + r, P - 1)) * C + chan);
-        const u32x4 hi = *reinterpret_cast<const u32x4*>(map + size_t(min(t * 32 + r, P - 1)) * C + chan + 8);
-        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        uint32_t bits = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) bits |= (bf16_lo_positive(w[i]) ? 1u : 0u) << (2 * i) | (bf16_hi_positive(w[i]) ? 1u : 0u) << (2 * i + 1);
-        return bits;
-    };
     // acc[t][0][8q .. 8q+7] where the mask bit is set, as 8 packed bf16
     auto packed_masked = [&](int t, int q, uint32_t bits) -> u32x4 {
         float v[8];
@@ -420,93 +442,132 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
         for (int i = 0; i < 8; ++i) v[i] = (bits >> (8 * q + i)) & 1u ? acc[t][0][8 * q + i] : 0.f;
         return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
     };
+    // Accumulators -> the fp32 staging area, four pixel tiles per round; then every thread takes 16-byte pieces
+    // (8 channels of a pixel) out of it: fn(c, lo, hi, pre(c)) with c the piece's index in the whole map.  pre(c)
+    // is evaluated for all of a thread's pieces before the round's barriers, so what it loads is there afterwards.
+    auto through_lds = [&](auto&& pre, auto&& fn) {
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            const int t0 = round * 4, t1 = round == 0 ? 4 : MTW, p0 = t0 * 32, p1 = round == 0 ? 128 : P;
+            constexpr int NI = 128 * 16 / NTHR;                       // pieces per thread of the larger round
+            decltype(pre(0)) ahead[NI];
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int c = p0 * 16 + tid + i * NTHR;
+                if (c < p1 * 16) ahead[i] = pre(c);
+            }
+            __syncthreads();                                          // the area (and, the first time, the tile) is free
+#pragma unroll
+            for (int t = 0; t < MTW; ++t)
+                if (t >= t0 && t < t1) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        *reinterpret_cast<f32x4*>(lds_raw + bn::STAGE_OFF + uint32_t(((t - t0) * 32 + r) * bn::STAGE_PITCH + (chan + 4 * b) * 4)) =
+                            f32x4{acc[t][0][4 * b], acc[t][0][4 * b + 1], acc[t][0][4 * b + 2], acc[t][0][4 * b + 3]};
+                }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int c = p0 * 16 + tid + i * NTHR;
+                if (c < p1 * 16) {
+                    const uint32_t at = bn::STAGE_OFF + uint32_t(((c >> 4) - p0) * bn::STAGE_PITCH + (c & 15) * 32);
+                    fn(c, *reinterpret_cast<const f32x4*>(lds_raw + at), *reinterpret_cast<const f32x4*>(lds_raw + at + 16), ahead[i]);
+                }
+            }
+        }
+    };
+    struct Nothing {};
+    struct Grad { f32x4 g0, g1; };
+    struct GradU { f32x4 g0, g1; u32x4 u; };
+    auto store_piece = [](float* dst, int c, const f32x4& lo, const f32x4& hi) {
+        *reinterpret_cast<f32x4*>(dst + size_t(c) * 8) = lo;
+        *reinterpret_cast<f32x4*>(dst + size_t(c) * 8 + 4) = hi;
+    };
+    NCLK(0);
     __syncthreads();
 
     // ---- dmid = conv(g; W_b flipped, transposed) * [mid > 0], written into the tile in place of g
-    uint32_t mmask[MTW], ymask[MTW];
+    // (mid is requested now and turned into mask bytes after the loop)
+    u32x4 mv[NIT];
 #pragma unroll
-    for (int t = 0; t < MTW; ++t) {                                   // (the loads return under the loop)
-        mmask[t] = mask_bits(a.sv_m + item_off, t);
-        ymask[t] = mask_bits(yp, t);
+    for (int i = 0; i < NIT; ++i) {
+        const int c = tid + i * NTHR;
+        if (c < P * 16) mv[i] = reinterpret_cast<const u32x4*>(a.sv_m + item_off)[c];
     }
     zero_acc();
+    NCLK(1);
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_bT, wrow_aT);
+    NCLK(2);
+#pragma unroll
+    for (int i = 0; i < NIT; ++i) {
+        const int c = tid + i * NTHR;
+        if (c < P * 16) lds_raw[bn::MASK_OFF + P * 16 + c] = static_cast<unsigned char>(piece_mask(mv[i]));
+    }
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < MTW; ++t)
         if (t * 32 + r < P) {
+            // this lane's 16 mask bits: the bytes of the two pieces that hold its channels
+            const uint32_t mm = *reinterpret_cast<const uint16_t*>(lds_raw + bn::MASK_OFF + P * 16 + (t * 32 + r) * 16 + (chan >> 3));
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const u32x4 pk = packed_masked(t, q, mmask[t]);
-                *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
-                *reinterpret_cast<u32x4*>(a.sv_dm + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
-            }
+            for (int q = 0; q < 2; ++q)
+                *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = packed_masked(t, q, mm);
         }
     __syncthreads();
+    {                                                                 // dmid saved for dW_a and db_a, out of the tile
+        u32x4* sdm4 = reinterpret_cast<u32x4*>(a.sv_dm + item_off);
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < P * 16) sdm4[c] = *reinterpret_cast<const u32x4*>(lds_raw + centre_addr(c));
+        }
+    }
 
-    // ---- du = g + conv(dmid; W_a flipped, transposed).  The residual term is added in fp32 from the gradient map
+    // ---- du = g + conv(dmid; W_a flipped, transposed).  The residual term g is added in fp32, from the gradient map
     // itself, not from its bf16 copy in the tile: down a chain of modules the convolution's share is small against
     // the residual's and would vanish below the bfloat16 quantum of the latter at every level.
-    uint32_t umask[MTW];
-#pragma unroll
-    for (int t = 0; t < MTW; ++t) umask[t] = binary ? mask_bits(a.sv_u + item_off, t) : 0u;
-    // (this lane's part of gy for the first pixel tiles is requested before the loop and arrives under it; the
-    // registers do not hold more)
-    constexpr int NPRE = 3;
-    f32x4 rg[NPRE][4];
-    auto gy_at = [&](int t, int b) -> f32x4 {
-        return *reinterpret_cast<const f32x4*>(gyp + size_t(min(t * 32 + r, P - 1)) * C + chan + 4 * b);
-    };
-#pragma unroll
-    for (int t = 0; t < NPRE; ++t)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) rg[t][b] = gy_at(t, b);
     zero_acc();
+    NCLK(3);
     kloop<MTW, NT, RW, XS, false>(acc, xaddr, ring, wrow_aT, wrow_aT);
-    f32x4 rl[MTW - NPRE][4];
-#pragma unroll
-    for (int t = NPRE; t < MTW; ++t)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) rl[t - NPRE][b] = gy_at(t, b);
-#pragma unroll
-    for (int t = 0; t < MTW; ++t)
-        if (t * 32 + r < P) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t bits = ymask[t] >> (4 * b);
-                const f32x4 v = t < NPRE ? rg[t < NPRE ? t : 0][b] : rl[t < NPRE ? 0 : t - NPRE][b];
-                acc[t][0][4 * b + 0] += bits & 1u ? v.x : 0.f;
-                acc[t][0][4 * b + 1] += bits & 2u ? v.y : 0.f;
-                acc[t][0][4 * b + 2] += bits & 4u ? v.z : 0.f;
-                acc[t][0][4 * b + 3] += bits & 8u ? v.w : 0.f;
-            }
-        }
-    auto store_grad = [&](float* dst) {                               // the accumulators as an fp32 map
-#pragma unroll
-        for (int t = 0; t < MTW; ++t)
-            if (t * 32 + r < P) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    *reinterpret_cast<f32x4*>(dst + size_t(t * 32 + r) * C + chan + 4 * b) =
-                        f32x4{acc[t][0][4 * b], acc[t][0][4 * b + 1], acc[t][0][4 * b + 2], acc[t][0][4 * b + 3]};
-            }
+    NCLK(4);
+    auto residual = [&](int c, f32x4& lo, f32x4& hi, const f32x4& g0, const f32x4& g1) {
+        const uint32_t yb = lds_raw[bn::MASK_OFF + c];
+        lo.x += yb & 1u ? g0.x : 0.f; lo.y += yb & 2u ? g0.y : 0.f; lo.z += yb & 4u ? g0.z : 0.f; lo.w += yb & 8u ? g0.w : 0.f;
+        hi.x += yb & 16u ? g1.x : 0.f; hi.y += yb & 32u ? g1.y : 0.f; hi.z += yb & 64u ? g1.z : 0.f; hi.w += yb & 128u ? g1.w : 0.f;
     };
+    const f32x4* gy4 = reinterpret_cast<const f32x4*>(gyp);
     if (!binary) {
-        store_grad(route_mf(a, a.gdst0[logical]));
+        float* dst = route_mf(a, a.gdst0[logical]);
+        through_lds([&](int c) { return Grad{gy4[2 * c], gy4[2 * c + 1]}; },
+                    [&](int c, f32x4 lo, f32x4 hi, const Grad& g) {
+                        residual(c, lo, hi, g.g0, g.g1);
+                        store_piece(dst, c, lo, hi);
+                    });
+        NCLK(5);
+#ifdef DYNB_NODE_CLOCKS
+        if (logical == 0 && (threadIdx.x & 63) == 0)
+            printf("node count %d wave %d: staged %lld | conv1 %lld..%lld | conv2 %lld..%lld | stored %lld\n", a.count, int(threadIdx.x >> 6), tck[0],
+                   tck[1], tck[2], tck[3], tck[4], tck[5]);
+#endif
         return;
     }
     // ---- two-argument functions: dc = du * [u > 0] into the tile, then da0 = dc W_1[:, :C], da1 = dc W_1[:, C:]
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < MTW; ++t)
-        if (t * 32 + r < P) {
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const u32x4 pk = packed_masked(t, q, umask[t]);
-                *reinterpret_cast<u32x4*>(lds_raw + centre(t) + uint32_t((chan + q * 8) * 2)) = pk;
-                *reinterpret_cast<u32x4*>(a.sv_dc + item_off + size_t(t * 32 + r) * C + chan + q * 8) = pk;
-            }
-        }
+    {
+        const u32x4* u4 = reinterpret_cast<const u32x4*>(a.sv_u + item_off);
+        u32x4* sdc4 = reinterpret_cast<u32x4*>(a.sv_dc + item_off);
+        through_lds([&](int c) { return GradU{gy4[2 * c], gy4[2 * c + 1], u4[c]}; },
+                    [&](int c, f32x4 lo, f32x4 hi, const GradU& g) {
+                        residual(c, lo, hi, g.g0, g.g1);
+                        const uint32_t ub = piece_mask(g.u);
+                        u32x4 pk;
+                        pk.x = pack_bf16x2(ub & 1u ? lo.x : 0.f, ub & 2u ? lo.y : 0.f);
+                        pk.y = pack_bf16x2(ub & 4u ? lo.z : 0.f, ub & 8u ? lo.w : 0.f);
+                        pk.z = pack_bf16x2(ub & 16u ? hi.x : 0.f, ub & 32u ? hi.y : 0.f);
+                        pk.w = pack_bf16x2(ub & 64u ? hi.z : 0.f, ub & 128u ? hi.w : 0.f);
+                        *reinterpret_cast<u32x4*>(lds_raw + centre_addr(c)) = pk;
+                        sdc4[c] = pk;
+                    });
+    }
     __syncthreads();
     {
         const bf16_t* t1row[NT] = {a.pk1T + frag1 * FRAG + lane * 8};
@@ -515,10 +576,12 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
         ring_fill<NT, 8>(ring1, t1row);
         zero_acc();
         kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row, t1row2);
-        store_grad(route_mf(a, a.gdst0[logical]));
+        float* d0 = route_mf(a, a.gdst0[logical]);
+        through_lds([](int) { return Nothing{}; }, [&](int c, f32x4 lo, f32x4 hi, const Nothing&) { store_piece(d0, c, lo, hi); });
         zero_acc();
         kloop<MTW, NT, 8, XS, true>(acc, xaddr, ring1, t1row2, t1row2);
-        store_grad(route_mf(a, a.gdst1[logical]));
+        float* d1 = route_mf(a, a.gdst1[logical]);
+        through_lds([](int) { return Nothing{}; }, [&](int c, f32x4 lo, f32x4 hi, const Nothing&) { store_piece(d1, c, lo, hi); });
     }
 }
 
@@ -942,7 +1005,7 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
     if (!(attr_set.load() >> (dev & 63) & 1)) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<8>), hipFuncAttributeMaxDynamicSharedMemorySize, mf::TILE_BYTES),
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_node_mfma<8>), hipFuncAttributeMaxDynamicSharedMemorySize, bn::LDS_BYTES),
                 "hipFuncSetAttribute(k_bwd_node_mfma)");
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwd_wgrad_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * mf::TILE_BYTES),
                 "hipFuncSetAttribute(k_bwd_wgrad_mfma)");
@@ -1012,7 +1075,7 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
         a.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + l.start;
         a.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + l.start;
         const unsigned grid = unsigned((l.count + 7) / 8 * 8);
-        hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), mf::TILE_BYTES, st, a);
+        hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), bn::LDS_BYTES, st, a);
     }
     if (!p->wg_units.empty()) {
         WgArgs q;
