@@ -592,8 +592,9 @@ __global__ __launch_bounds__(256, 1) void k_bwd_node_mfma(BmArgs a)
 // and with part 0 the bias gradient, the sum of g / dmid / dc over items and pixels.
 // The contraction runs over pixels, the dimension in which neither map is contiguous.  Both maps of an item are
 // copied into LDS halo tiles (pixel-major like the forward pass's tile) and the MFMA operands are read from
-// there two bytes at a time: lane (m, hk) of an operand fragment holds channel m of the 8 pixels x = 8 hk .. 8 hk + 7
-// of image row y, one K step per image row (x = 14, 15 are zeros).  For a kernel row the three taps' fragments of the
+// there four bytes (two channels of a pixel) at a time: lane (m, hk) holds, for the 8 pixels x = 8 hk .. 8 hk + 7 of image
+// row y, channels 2 m and 2 m + 1, which are row m of the wave's two interleaved channel tiles; a K step is an image
+// row (x = 14, 15 are zeros).  For a kernel row the three taps' fragments of the
 // input map are the same 10 pixels shifted by one, so they are read once.  The reads of row y + 1 are issued ahead of
 // the MFMAs of row y and packed into fragments behind them.  D[ci][co] accumulates in registers over the unit's items, in item order, and is written to the
 // unit's partial result; k_bwd_wgrad_sum adds the partial results of a (function, part) in chunk order.  Nothing is
@@ -672,9 +673,13 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
             }
         }
     };
-    auto rd16 = [&](uint32_t addr) -> uint32_t { return *reinterpret_cast<const uint16_t*>(lds_raw + addr); };
-    auto frag_of = [](const uint32_t* v) -> bf16x8 {                   // eight zero-extended 16-bit values -> 8 bf16, one v_perm per pair
-        auto pair = [](uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x05040100u); };
+    // A wave's two channel tiles interleave: tile c of its 64 channels holds channels 2 m + c (m = MFMA row / column),
+    // so that one 32-bit LDS read gives a lane its value of both tiles (a pixel's channels 2 m and 2 m + 1).
+    auto rd32 = [&](uint32_t addr) -> uint32_t { return *reinterpret_cast<const uint32_t*>(lds_raw + addr); };
+    // eight dwords (pixels), tile c in half c of every dword -> the 8 bf16 of tile c, one v_perm per pair of pixels
+    auto frag_of = [](const uint32_t* v, int c) -> bf16x8 {
+        const uint32_t sel = c ? 0x07060302u : 0x05040100u;
+        auto pair = [sel](uint32_t first, uint32_t second) { return __builtin_amdgcn_perm(second, first, sel); };
         const u32x4 w = {pair(v[0], v[1]), pair(v[2], v[3]), pair(v[4], v[5]), pair(v[6], v[7])};
         return __builtin_bit_cast(bf16x8, w);
     };
@@ -682,10 +687,10 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_w);
     // tile row / first tile column of this lane's 8 pixels of image row y:
     //   gradient map and conv1x1 input: row y + 1, column 1 + 8 hk;  conv3x3 input for kernel row kh: row y + kh, column 8 hk
-    const uint32_t g_lane = TILE_G + uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wj * 64 + m) * 2);
-    const uint32_t in_lane = MODE == 2 ? uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wi * 64 + m) * 2)
-                                       : uint32_t(part * ROW_BYTES + (8 * hk) * PIX_BYTES + (wi * 64 + m) * 2);
-    struct Raw { uint32_t g[2][8]; uint32_t in[2][NV]; };              // one row's 16-bit values as they come from LDS
+    const uint32_t g_lane = TILE_G + uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wj * 64 + 2 * m) * 2);
+    const uint32_t in_lane = MODE == 2 ? uint32_t(ROW_BYTES + (1 + 8 * hk) * PIX_BYTES + (wi * 64 + 2 * m) * 2)
+                                       : uint32_t(part * ROW_BYTES + (8 * hk) * PIX_BYTES + (wi * 64 + 2 * m) * 2);
+    struct Raw { uint32_t g[8]; uint32_t in[NV]; };                    // one row's values as they come from LDS
     struct Row { bf16x8 gf[2]; bf16x8 inf[2][NTAP]; };                 // ... and packed into operand fragments
     // The upper lane half's last pixels do not exist (x = 14, 15) or lie beyond the tile (conv3x3 input, tile columns
     // 16, 17).  Tile column 15 is the zero border: the gradient map's x = 14 is that column already, and the lanes
@@ -699,26 +704,20 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
         const uint32_t yo = uint32_t(y * ROW_BYTES);
         const uint32_t gb = g_lane + yo, g7 = g_lane7 + yo, ib = in_lane + yo, ia = in_lanea + yo, ibb = in_laneb + yo;
 #pragma unroll
-        for (int cj = 0; cj < 2; ++cj) {
+        for (int i = 0; i < 7; ++i) rw.g[i] = rd32(gb + uint32_t(i * PIX_BYTES));
+        rw.g[7] = rd32(g7);
 #pragma unroll
-            for (int i = 0; i < 7; ++i) rw.g[cj][i] = rd16(gb + uint32_t(cj * 64 + i * PIX_BYTES));
-            rw.g[cj][7] = rd16(g7 + uint32_t(cj * 64));
-        }
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-#pragma unroll
-            for (int i = 0; i < ILIM; ++i) rw.in[ct][i] = rd16(ib + uint32_t(ct * 64 + i * PIX_BYTES));
-            rw.in[ct][ILIM] = rd16(ia + uint32_t(ct * 64));
-            if (ILIM + 1 < NV) rw.in[ct][ILIM + 1 < NV ? ILIM + 1 : 0] = rd16(ibb + uint32_t(ct * 64));
-        }
+        for (int i = 0; i < ILIM; ++i) rw.in[i] = rd32(ib + uint32_t(i * PIX_BYTES));
+        rw.in[ILIM] = rd32(ia);
+        if (ILIM + 1 < NV) rw.in[ILIM + 1 < NV ? ILIM + 1 : 0] = rd32(ibb);
     };
     auto pack_row = [&](const Raw& rw, Row& row) {
 #pragma unroll
-        for (int cj = 0; cj < 2; ++cj) row.gf[cj] = frag_of(rw.g[cj]);
+        for (int c = 0; c < 2; ++c) {
+            row.gf[c] = frag_of(rw.g, c);
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-            for (int k = 0; k < NTAP; ++k) row.inf[ct][k] = frag_of(rw.in[ct] + k);
+            for (int k = 0; k < NTAP; ++k) row.inf[c][k] = frag_of(rw.in + k, c);
+        }
     };
     const bool with_bias = part == 0 && wi == 0;                      // uniform over the wave
     auto mfma_row = [&](const Row& rw, auto WB) {
@@ -742,7 +741,7 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
         mfma_row(cur, WB);
         pack_row(raw_pack, nxt);
         constexpr int NMF = NTAP * 4 + (decltype(WB)::value ? 2 : 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * 8 + 2 * NV, 0);          // all reads
+        __builtin_amdgcn_sched_group_barrier(0x100, 8 + NV, 0);                   // all reads
         __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                        // (their addresses)
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
@@ -774,20 +773,20 @@ __device__ __forceinline__ void wgrad_unit(const WgArgs& a, const dynb_wg_unit u
     };
     if (with_bias) items(std::true_type{});
     else items(std::false_type{});
-    // D[ci][co]: this lane holds co = wj*64 + cj*32 + m and ci = wi*64 + ct*32 + 8 b + 4 hk + (0..3) in elements 4 b .. 4 b + 3
+    // D[ci][co] of tiles (ct, cj): this lane holds co = wj*64 + 2 m + cj and, in elements 4 b .. 4 b + 3, the rows
+    // 8 b + 4 hk + (0..3), i.e. ci = wi*64 + 2 (8 b + 4 hk + e) + ct: the two ci tiles together give 8 consecutive ci
 #pragma unroll
     for (int cj = 0; cj < 2; ++cj) {
-        const int co = wj * 64 + cj * 32 + m;
+        const int co = wj * 64 + 2 * m + cj;
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int k = 0; k < NTAP; ++k)
 #pragma unroll
-            for (int k = 0; k < NTAP; ++k)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int ci = wi * 64 + ct * 32 + 8 * b + 4 * hk;
-                    *reinterpret_cast<f32x4*>(part_out + (size_t(k) * C + co) * C + ci) =
-                        f32x4{acc[k][ct][cj][4 * b], acc[k][ct][cj][4 * b + 1], acc[k][ct][cj][4 * b + 2], acc[k][ct][cj][4 * b + 3]};
-                }
+            for (int b = 0; b < 4; ++b) {
+                const int ci = wi * 64 + 16 * b + 8 * hk;
+                float* dst = part_out + (size_t(k) * C + co) * C + ci;
+                *reinterpret_cast<f32x4*>(dst) = f32x4{acc[k][0][cj][4 * b], acc[k][1][cj][4 * b], acc[k][0][cj][4 * b + 1], acc[k][1][cj][4 * b + 1]};
+                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[k][0][cj][4 * b + 2], acc[k][1][cj][4 * b + 2], acc[k][0][cj][4 * b + 3], acc[k][1][cj][4 * b + 3]};
+            }
         if (with_bias && hk == 0) part_out[size_t(3) * C * C + co] = accb[cj][0];
     }
 }
