@@ -836,8 +836,7 @@ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 size_t elt_bytes(int dtype) { return dtype == DYNB_BF16 ? 2 : 4; }
 
 struct BwdLayout {
-    size_t gy, gleaf, tmp_u, tmp_m, tmp_g, tmp_dm, tmp_du, tables, total;
-    size_t t_gdst0, t_gdst1, t_leaf_first, t_root_item;       // inside tables
+    size_t gy, gleaf, tmp_u, tmp_m, tmp_g, tmp_dm, tmp_du, total;
 };
 
 BwdLayout bwd_layout(const dynb_plan* p, const dynb_shape* s)
@@ -854,11 +853,6 @@ BwdLayout bwd_layout(const dynb_plan* p, const dynb_shape* s)
     L.tmp_g = take(size_t(p->max_launch) * chw * 4);
     L.tmp_dm = take(size_t(p->max_launch) * chw * 4);
     L.tmp_du = take(size_t(p->max_launch) * chw * 4);
-    L.tables = o;
-    L.t_gdst0 = take(n_items * 4);
-    L.t_gdst1 = take(n_items * 4);
-    L.t_leaf_first = take((size_t(p->B) + 1) * 4);
-    L.t_root_item = take(size_t(p->B) * 4);
     L.total = o;
     return L;
 }
@@ -870,16 +864,11 @@ int run_backward(const dynb_plan* p, const dynb_shape* s, const dynb_module_weig
     const BwdLayout L = bwd_layout(p, s);
     const size_t chw = size_t(s->C) * s->H * s->W;
     const int C = s->C, B = p->B;
-    // the routing tables travel with the call (a few bytes per node)
-    auto table = [&](size_t at, const std::vector<int32_t>& v) -> hipError_t {
-        return v.empty() ? hipSuccess : hipMemcpyAsync(ws + at, v.data(), v.size() * 4, hipMemcpyHostToDevice, st);
-    };
-    HIP_TRY(table(L.t_gdst0, p->grad_dst0), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_gdst1, p->grad_dst1), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_leaf_first, p->leaf_first), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_root_item, p->root_item), "dynbatch_backward(tables)");
-    const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(ws + L.t_leaf_first);
-    const int32_t* d_root_item = reinterpret_cast<const int32_t*>(ws + L.t_root_item);
+    // the routing tables were uploaded with the plan
+    const dynb_keep_tables KT = dynb_plan_keep_tables(p);
+    const char* pd = static_cast<const char*>(p->dev_buf);
+    const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(pd + KT.leaf_first);
+    const int32_t* d_root_item = reinterpret_cast<const int32_t*>(pd + KT.root_item);
 
     auto fill = [&](float* ptr, size_t n) {
         if (ptr && n) hipLaunchKernelGGL(k_bwd_fill, dim3(unsigned(std::min<size_t>((n + 255) / 256, 4096))), dim3(256), 0, st, ptr, n, 0.f);
@@ -920,8 +909,8 @@ int run_backward(const dynb_plan* p, const dynb_shape* s, const dynb_module_weig
             ga.items = d_items + first; ga.count = cnt;
             ga.tmp_u = ws + L.tmp_u; ga.tmp_m = ws + L.tmp_m;
             ba.items = d_items + first; ba.first_item = first; ba.count = cnt;
-            ba.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + first;
-            ba.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + first;
+            ba.gdst0 = reinterpret_cast<const int32_t*>(pd + KT.gdst0) + first;
+            ba.gdst1 = reinterpret_cast<const int32_t*>(pd + KT.gdst1) + first;
             ba.tmp_u = ws + L.tmp_u; ba.tmp_m = ws + L.tmp_m;
             ba.tmp_g = reinterpret_cast<float*>(ws + L.tmp_g); ba.tmp_dm = reinterpret_cast<float*>(ws + L.tmp_dm);
             ba.tmp_du = reinterpret_cast<float*>(ws + L.tmp_du);
@@ -966,7 +955,7 @@ bool fast_shape(const dynb_shape* s) { return s->dtype == DYNB_BF16 && s->C == 1
 // workspace of the MFMA path
 struct BmLayout {
     size_t gy, gleaf, sv_g, sv_dm, sv_dc, pk3bT, pk3aT, pk1T;
-    size_t partial, t_gdst0, t_gdst1, t_leaf_first, t_root_item, t_fn_items, t_units, t_groups, t_order, total;
+    size_t partial, total;
 };
 
 BmLayout bm_layout(const dynb_plan* p)
@@ -984,15 +973,7 @@ BmLayout bm_layout(const dynb_plan* p)
     L.pk3bT = take(nt * 9 * 128 * 128 * 2);
     L.pk3aT = take(nt * 9 * 128 * 128 * 2);
     L.pk1T = take(nt * 2 * 128 * 128 * 2);
-    L.t_gdst0 = take(n_items * 4);
-    L.t_gdst1 = take(n_items * 4);
-    L.t_leaf_first = take((size_t(p->B) + 1) * 4);
-    L.t_root_item = take(size_t(p->B) * 4);
-    L.t_fn_items = take(n_items * 4);
     L.partial = take(p->wg_units.size() * WG_PARTIAL * 4);
-    L.t_units = take(p->wg_units.size() * sizeof(dynb_wg_unit));
-    L.t_groups = take(p->wg_groups.size() * sizeof(dynb_wg_group));
-    L.t_order = take(p->wg_order.size() * 4);
     L.total = o;
     return L;
 }
@@ -1013,30 +994,21 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     const BmLayout L = bm_layout(p);
     const size_t chw = size_t(mf::P) * mf::C, n_items_all = p->items.size();
     const int C = mf::C, B = p->B, nt = p->n_types;
-    auto table = [&](size_t at, const std::vector<int32_t>& v) -> hipError_t {
-        return v.empty() ? hipSuccess : hipMemcpyAsync(ws + at, v.data(), v.size() * 4, hipMemcpyHostToDevice, st);
-    };
-    HIP_TRY(table(L.t_gdst0, p->grad_dst0), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_gdst1, p->grad_dst1), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_leaf_first, p->leaf_first), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_root_item, p->root_item), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_fn_items, p->fn_items), "dynbatch_backward(tables)");
-    HIP_TRY(table(L.t_order, p->wg_order), "dynbatch_backward(tables)");
-    if (!p->wg_units.empty())
-        HIP_TRY(hipMemcpyAsync(ws + L.t_units, p->wg_units.data(), p->wg_units.size() * sizeof(dynb_wg_unit), hipMemcpyHostToDevice, st),
-                "dynbatch_backward(tables)");
-    if (!p->wg_groups.empty())
-        HIP_TRY(hipMemcpyAsync(ws + L.t_groups, p->wg_groups.data(), p->wg_groups.size() * sizeof(dynb_wg_group), hipMemcpyHostToDevice, st),
-                "dynbatch_backward(tables)");
-    const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(ws + L.t_leaf_first);
-    const int32_t* d_root_item = reinterpret_cast<const int32_t*>(ws + L.t_root_item);
+    // the routing tables, item lists and work units were uploaded with the plan
+    const dynb_keep_tables KT = dynb_plan_keep_tables(p);
+    const char* pd = static_cast<const char*>(p->dev_buf);
+    const int32_t* d_leaf_first = reinterpret_cast<const int32_t*>(pd + KT.leaf_first);
+    const int32_t* d_root_item = reinterpret_cast<const int32_t*>(pd + KT.root_item);
 
-    // gradients of functions that no item uses stay zero
-    auto fill = [&](float* ptr, size_t n) {
-        if (ptr && n) hipLaunchKernelGGL(k_bwd_fill, dim3(unsigned(std::min<size_t>((n + 255) / 256, 4096))), dim3(256), 0, st, ptr, n, 0.f);
-    };
-    fill(g->dw3a, size_t(nt) * C * 9 * C); fill(g->dw3b, size_t(nt) * C * 9 * C); fill(g->db3a, size_t(nt) * C); fill(g->db3b, size_t(nt) * C);
-    fill(g->dw1, size_t(nt) * C * 2 * C); fill(g->db1, size_t(nt) * C);
+    // (the parameter gradients of every function are written by k_bwd_wgrad_sum, zeros included; without a
+    // two-argument function in the batch there is no conv1x1 gradient to sum)
+    if (!p->has_binary) {
+        auto fill = [&](float* ptr, size_t n) {
+            if (ptr && n) hipLaunchKernelGGL(k_bwd_fill, dim3(unsigned(std::min<size_t>((n + 255) / 256, 4096))), dim3(256), 0, st, ptr, n, 0.f);
+        };
+        fill(g->dw1, size_t(nt) * C * 2 * C);
+        fill(g->db1, size_t(nt) * C);
+    }
 
     // weights in fragment order, as given and transposed
     auto pack = [&](const void* src, size_t at, int ntap, int mode) {
@@ -1071,26 +1043,27 @@ int run_backward_mfma(const dynb_plan* p, const dynb_module_weights* w, const vo
     for (size_t li = p->launches.size(); li-- > 0;) {
         const dynb_launch& l = p->launches[li];
         a.items = d_items + l.start; a.first_item = l.start; a.count = l.count;
-        a.gdst0 = reinterpret_cast<const int32_t*>(ws + L.t_gdst0) + l.start;
-        a.gdst1 = reinterpret_cast<const int32_t*>(ws + L.t_gdst1) + l.start;
+        a.gdst0 = reinterpret_cast<const int32_t*>(pd + KT.gdst0) + l.start;
+        a.gdst1 = reinterpret_cast<const int32_t*>(pd + KT.gdst1) + l.start;
         const unsigned grid = unsigned((l.count + 7) / 8 * 8);
         hipLaunchKernelGGL((k_bwd_node_mfma<8>), dim3(grid), dim3(256), bn::LDS_BYTES, st, a);
     }
-    if (!p->wg_units.empty()) {
+    {
         WgArgs q;
         q.items = d_items; q.arity = d_arity;
-        q.units = reinterpret_cast<const dynb_wg_unit*>(ws + L.t_units);
-        q.order = reinterpret_cast<const int32_t*>(ws + L.t_order);
-        q.fn_items = reinterpret_cast<const int32_t*>(ws + L.t_fn_items);
+        q.units = reinterpret_cast<const dynb_wg_unit*>(pd + KT.units);
+        q.order = reinterpret_cast<const int32_t*>(pd + KT.order);
+        q.fn_items = reinterpret_cast<const int32_t*>(pd + KT.fn_items);
         q.feats = a.feats; q.slots = a.slots;
         q.sv_u = a.sv_u; q.sv_m = a.sv_m; q.sv_g = a.sv_g; q.sv_dm = a.sv_dm; q.sv_dc = a.sv_dc;
         q.partial = reinterpret_cast<float*>(ws + L.partial);
-        hipLaunchKernelGGL(k_bwd_wgrad_mfma, dim3(unsigned(p->wg_units.size())), dim3(256), 2 * mf::TILE_BYTES, st, q);
+        if (!p->wg_units.empty())
+            hipLaunchKernelGGL(k_bwd_wgrad_mfma, dim3(unsigned(p->wg_units.size())), dim3(256), 2 * mf::TILE_BYTES, st, q);
         WsArgs r;
-        r.groups = reinterpret_cast<const dynb_wg_group*>(ws + L.t_groups);
+        r.groups = reinterpret_cast<const dynb_wg_group*>(pd + KT.groups);
         r.partial = q.partial;
         r.dw3a = g->dw3a; r.db3a = g->db3a; r.dw3b = g->dw3b; r.db3b = g->db3b; r.dw1 = g->dw1; r.db1 = g->db1;
-        // functions without items have groups without units: the sum writes their zeros
+        // groups without units: the sum writes their zeros
         hipLaunchKernelGGL(k_bwd_wgrad_sum, dim3(3 * 128 * 128 / 4 / 256, unsigned(p->wg_groups.size())), dim3(256), 0, st, r);
     }
     for (int e0 = 0; e0 < B; e0 += 32768)

@@ -496,13 +496,13 @@ extern "C" int dynb_debug_phase_clocks(void* device_buf)
 // Device buffer layout of an uploaded plan: items | leaf-root example ids | arity table | tickets
 static size_t plan_items_bytes(const dynb_plan* p) { return dynb_plan_items_bytes(p); }
 static size_t plan_leaf_bytes(const dynb_plan* p) { return dynb_plan_leaf_bytes(p); }
-static size_t plan_arity_bytes(const dynb_plan* p) { return align256(p->arity.size()); }
-static size_t plan_ticket_bytes(const dynb_plan* p) { return align256(p->tickets.size() * sizeof(int32_t)); }
+static size_t plan_arity_bytes(const dynb_plan* p) { return dynb_plan_arity_bytes(p); }
+static size_t plan_ticket_bytes(const dynb_plan* p) { return dynb_plan_ticket_bytes(p); }
 
 extern "C" size_t dynbatch_plan_device_bytes(const dynb_plan* p)
 {
     if (!p) return 0;
-    return plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p) + plan_ticket_bytes(p) + 256;
+    return dynb_plan_keep_tables(p).end + 256;
 }
 
 // Workspace tail of the dependency-driven launch: ready[n_slots] | counter | status (after the slots and,
@@ -540,6 +540,20 @@ extern "C" int dynbatch_plan_upload(dynb_plan* p, void* dev_buf, size_t bytes, v
         HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p), p->tickets.data(),
                                p->tickets.size() * sizeof(int32_t), hipMemcpyHostToDevice, st),
                 "dynbatch_plan_upload(tickets)");
+    if (p->keep) {                                            // what the backward pass works from
+        const dynb_keep_tables t = dynb_plan_keep_tables(p);
+        auto put = [&](size_t at, const void* src, size_t n) -> hipError_t {
+            return n ? hipMemcpyAsync(d + at, src, n, hipMemcpyHostToDevice, st) : hipSuccess;
+        };
+        HIP_TRY(put(t.gdst0, p->grad_dst0.data(), p->grad_dst0.size() * 4), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.gdst1, p->grad_dst1.data(), p->grad_dst1.size() * 4), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.leaf_first, p->leaf_first.data(), p->leaf_first.size() * 4), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.root_item, p->root_item.data(), p->root_item.size() * 4), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.fn_items, p->fn_items.data(), p->fn_items.size() * 4), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.units, p->wg_units.data(), p->wg_units.size() * sizeof(dynb_wg_unit)), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.groups, p->wg_groups.data(), p->wg_groups.size() * sizeof(dynb_wg_group)), "dynbatch_plan_upload(backward tables)");
+        HIP_TRY(put(t.order, p->wg_order.data(), p->wg_order.size() * 4), "dynbatch_plan_upload(backward tables)");
+    }
     p->dev_buf = dev_buf;
     p->dev_bytes = bytes;
     return DYNB_OK;

@@ -65,12 +65,31 @@ struct dynb_plan {
     size_t dev_bytes = 0;
 };
 
-// Device buffer of an uploaded plan: items | ids of single-SCENE examples | arity table | tickets, each part
-// padded to 256 bytes.
+// Device buffer of an uploaded plan: items | ids of single-SCENE examples | arity table | tickets | the backward
+// pass's tables (DYNB_PLAN_KEEP), each part padded to 256 bytes.
 inline size_t dynb_align256(size_t v) { return (v + 255) & ~size_t(255); }
 inline size_t dynb_plan_items_bytes(const dynb_plan* p) { return dynb_align256(p->items.size() * sizeof(dynb_item)); }
 inline size_t dynb_plan_leaf_bytes(const dynb_plan* p) { return dynb_align256(p->leaf_roots.size() * sizeof(int32_t)); }
 inline size_t dynb_plan_arity_offset(const dynb_plan* p) { return dynb_plan_items_bytes(p) + dynb_plan_leaf_bytes(p); }
+inline size_t dynb_plan_arity_bytes(const dynb_plan* p) { return dynb_align256(p->arity.size()); }
+inline size_t dynb_plan_ticket_bytes(const dynb_plan* p) { return dynb_align256(p->tickets.size() * sizeof(int32_t)); }
+struct dynb_keep_tables { size_t gdst0, gdst1, leaf_first, root_item, fn_items, units, groups, order, end; };   // byte offsets
+inline dynb_keep_tables dynb_plan_keep_tables(const dynb_plan* p)
+{
+    dynb_keep_tables t;
+    size_t o = dynb_plan_arity_offset(p) + dynb_plan_arity_bytes(p) + dynb_plan_ticket_bytes(p);
+    auto take = [&](size_t bytes) { const size_t at = o; o += p->keep ? dynb_align256(bytes) : 0; return at; };
+    t.gdst0 = take(p->grad_dst0.size() * 4);
+    t.gdst1 = take(p->grad_dst1.size() * 4);
+    t.leaf_first = take(p->leaf_first.size() * 4);
+    t.root_item = take(p->root_item.size() * 4);
+    t.fn_items = take(p->fn_items.size() * 4);
+    t.units = take(p->wg_units.size() * sizeof(dynb_wg_unit));
+    t.groups = take(p->wg_groups.size() * sizeof(dynb_wg_group));
+    t.order = take(p->wg_order.size() * 4);
+    t.end = o;
+    return t;
+}
 
 // Workspace of dynbatch_execute on the fused kernels' shape (bf16, C = 128, 14 x 14), in this order:
 //   slots | module weights in fragment order (w3a, w3b: 9 taps, w1: 2 halves; 128 x 128 bf16 per tap and function)

@@ -342,10 +342,12 @@ void build_lists(dynb_plan* p, const uint8_t* arity, const int32_t* prog_off, co
         std::vector<int32_t> at(p->fn_first.begin(), p->fn_first.end() - 1);
         for (size_t i = 0; i < p->items.size(); ++i) p->fn_items[at[p->items[i].type]++] = int32_t(i);
         // units of the parameter-gradient kernel
-        for (int32_t mode = 0; mode < 3; ++mode)
+        // (every function has its groups, also those without a gradient of that kind: their sum is zero; the
+        // conv1x1 groups exist only if the batch uses a two-argument function at all)
+        for (int32_t mode = 0; mode < (p->has_binary ? 3 : 2); ++mode)
             for (int32_t t = 0; t < p->n_types; ++t) {
-                if (arity[t] == 0 || (mode == 2 && arity[t] != 2)) continue;
-                const int32_t lo = p->fn_first[t], hi = p->fn_first[t + 1];
+                const bool has_units = arity[t] != 0 && (mode != 2 || arity[t] == 2);
+                const int32_t lo = p->fn_first[t], hi = has_units ? p->fn_first[t + 1] : lo;
                 for (int32_t part = 0; part < (mode == 2 ? 2 : 3); ++part) {
                     dynb_wg_group g{mode, t, part, int32_t(p->wg_units.size()), 0, 0, 0, 0};
                     for (int32_t b = lo; b < hi; b += DYNB_WG_CHUNK) {
