@@ -202,10 +202,11 @@ void dynbatch_plan_free(dynb_plan* plan);
 /* Bytes of device memory the plan's index lists need. */
 size_t dynbatch_plan_device_bytes(const dynb_plan* plan);
 
-/* Copies the index lists to `dev_buf` (device, >= dynbatch_plan_device_bytes, 16-byte aligned)
- * on `stream`, once per plan.  The plan remembers dev_buf; it must stay valid and unmodified
- * while the plan is executed.  The copies read the plan's own host arrays: do not free the plan
- * before the work enqueued on `stream` up to this call has finished.
+/* Copies the index lists (and, for DYNB_PLAN_KEEP plans, the backward pass's tables) to `dev_buf` (device,
+ * >= dynbatch_plan_device_bytes, 16-byte aligned) on `stream` with one copy, once per plan.  The plan
+ * remembers dev_buf; it must stay valid and unmodified while the plan is executed.  The copy reads a host
+ * image that the plan owns: do not free the plan, or upload it again, before the work enqueued on
+ * `stream` up to this call has finished.
  * Errors: DYNB_E_INVAL, DYNB_E_WORKSPACE (too small), DYNB_E_HIP.                               */
 int dynbatch_plan_upload(dynb_plan* plan, void* dev_buf, size_t bytes, void* stream);
 

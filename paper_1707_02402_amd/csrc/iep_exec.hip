@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstdlib>
+#include <cstring>
 #include <string>
 
 #include "device_utils.h"
@@ -525,35 +526,28 @@ extern "C" int dynbatch_plan_upload(dynb_plan* p, void* dev_buf, size_t bytes, v
     if (bytes < dynbatch_plan_device_bytes(p)) return fail(DYNB_E_WORKSPACE, "dynbatch_plan_upload: buffer too small");
     if (reinterpret_cast<uintptr_t>(dev_buf) & 15) return fail(DYNB_E_INVAL, "dynbatch_plan_upload: buffer not 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    char* d = static_cast<char*>(dev_buf);
-    if (!p->items.empty())
-        HIP_TRY(hipMemcpyAsync(d, p->items.data(), p->items.size() * sizeof(dynb_item), hipMemcpyHostToDevice, st),
-                "dynbatch_plan_upload(items)");
-    if (!p->leaf_roots.empty())
-        HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p), p->leaf_roots.data(), p->leaf_roots.size() * sizeof(int32_t),
-                               hipMemcpyHostToDevice, st),
-                "dynbatch_plan_upload(leaf roots)");
-    HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p) + plan_leaf_bytes(p), p->arity.data(), p->arity.size(),
-                           hipMemcpyHostToDevice, st),
-            "dynbatch_plan_upload(arity)");
-    if (!p->tickets.empty())
-        HIP_TRY(hipMemcpyAsync(d + plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p), p->tickets.data(),
-                               p->tickets.size() * sizeof(int32_t), hipMemcpyHostToDevice, st),
-                "dynbatch_plan_upload(tickets)");
+    // One copy: the parts are laid out in a host image of the device buffer (a separate copy per part costs a few
+    // microseconds of stream time each, which shows in a step of less than a millisecond).  The image belongs to the
+    // plan, so it lives as long as the copy may need it.
+    const dynb_keep_tables t = dynb_plan_keep_tables(p);
+    p->image.assign(t.end, 0);
+    char* h = p->image.data();
+    auto put = [&](size_t at, const void* src, size_t n) { if (n) memcpy(h + at, src, n); };
+    put(0, p->items.data(), p->items.size() * sizeof(dynb_item));
+    put(plan_items_bytes(p), p->leaf_roots.data(), p->leaf_roots.size() * sizeof(int32_t));
+    put(plan_items_bytes(p) + plan_leaf_bytes(p), p->arity.data(), p->arity.size());
+    put(plan_items_bytes(p) + plan_leaf_bytes(p) + plan_arity_bytes(p), p->tickets.data(), p->tickets.size() * sizeof(int32_t));
     if (p->keep) {                                            // what the backward pass works from
-        const dynb_keep_tables t = dynb_plan_keep_tables(p);
-        auto put = [&](size_t at, const void* src, size_t n) -> hipError_t {
-            return n ? hipMemcpyAsync(d + at, src, n, hipMemcpyHostToDevice, st) : hipSuccess;
-        };
-        HIP_TRY(put(t.gdst0, p->grad_dst0.data(), p->grad_dst0.size() * 4), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.gdst1, p->grad_dst1.data(), p->grad_dst1.size() * 4), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.leaf_first, p->leaf_first.data(), p->leaf_first.size() * 4), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.root_item, p->root_item.data(), p->root_item.size() * 4), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.fn_items, p->fn_items.data(), p->fn_items.size() * 4), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.units, p->wg_units.data(), p->wg_units.size() * sizeof(dynb_wg_unit)), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.groups, p->wg_groups.data(), p->wg_groups.size() * sizeof(dynb_wg_group)), "dynbatch_plan_upload(backward tables)");
-        HIP_TRY(put(t.order, p->wg_order.data(), p->wg_order.size() * 4), "dynbatch_plan_upload(backward tables)");
+        put(t.gdst0, p->grad_dst0.data(), p->grad_dst0.size() * 4);
+        put(t.gdst1, p->grad_dst1.data(), p->grad_dst1.size() * 4);
+        put(t.leaf_first, p->leaf_first.data(), p->leaf_first.size() * 4);
+        put(t.root_item, p->root_item.data(), p->root_item.size() * 4);
+        put(t.fn_items, p->fn_items.data(), p->fn_items.size() * 4);
+        put(t.units, p->wg_units.data(), p->wg_units.size() * sizeof(dynb_wg_unit));
+        put(t.groups, p->wg_groups.data(), p->wg_groups.size() * sizeof(dynb_wg_group));
+        put(t.order, p->wg_order.data(), p->wg_order.size() * 4);
     }
+    if (t.end) HIP_TRY(hipMemcpyAsync(dev_buf, h, t.end, hipMemcpyHostToDevice, st), "dynbatch_plan_upload");
     p->dev_buf = dev_buf;
     p->dev_bytes = bytes;
     return DYNB_OK;

@@ -61,6 +61,7 @@ struct dynb_plan {
     std::vector<dynb_wg_unit> wg_units;  // grouped: the chunks of one (mode, function, part) are consecutive
     std::vector<dynb_wg_group> wg_groups;
     std::vector<int32_t> wg_order;       // unit indices, longest chunks first: the order in which workgroups take them
+    std::vector<char> image;             // host image of the device buffer, filled by dynbatch_plan_upload
     void* dev_buf = nullptr;             // set by dynbatch_plan_upload
     size_t dev_bytes = 0;
 };
