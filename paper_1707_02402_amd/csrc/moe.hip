@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <type_traits>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -50,6 +52,18 @@ __device__ __forceinline__ bf16x8 ldg_frag(const bf16_t* p) { return *reinterpre
 // for both matrices (clean and noise accumulators), multiplied with 32x32x16 MFMAs.
 constexpr int GKC = 64;                // K-chunk
 constexpr int GLDP = GKC + 8;          // LDS row pitch in elements (144 bytes, conflict free)
+
+// softplus(z) = max(z, 0) + log(1 + u), u = exp(-|z|) in (0, 1], from the hardware's exp2 and log2 (good to about
+// 1e-7).  w = 1 + u is rounded; c = u - (w - 1) is exactly what the rounding dropped (w - 1 and the difference are
+// exact for w in [1, 2]), and log(1 + u) = log(w) + c / w, where leaving out the division costs less than 2^-25: small
+// u keep their relative accuracy without a second code path (u < 2^-24 gives w = 1, log(w) = 0, c = u).
+__device__ __forceinline__ float softplus_f(float z)
+{
+    const float u = __builtin_amdgcn_exp2f(-1.4426950408889634f * fabsf(z));
+    const float w = 1.f + u;
+    const float c = u - (w - 1.f);
+    return fmaxf(z, 0.f) + fmaf(0.6931471805599453f, __builtin_amdgcn_logf(w), c);
+}
 
 __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
                                               const bf16_t* __restrict__ Wn, const float* __restrict__ noise,
@@ -115,10 +129,185 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
         float v = ag[i];
         if (noise) {
             const float z = an[i];
-            const float sp = fmaxf(z, 0.f) + log1pf(expf(-fabsf(z)));
+            const float sp = softplus_f(z);
             v += noise[size_t(t) * E + e] * sp;
         }
         logits[size_t(t) * E + e] = v;
+    }
+}
+
+// The same product for wide gates: a workgroup owns a CU and a tile of 256 tokens x 128 experts, both gate matrices
+// at once.  A 64 x 64 tile takes in 24 KB per K-chunk for 8 MFMAs per wave (96 B per
+// MFMA clock), three times what a CU receives from L2; this tile takes in 64 KB for 64 MFMAs per wave (32 B per MFMA
+// clock).  Operands go through LDS in K-chunks of 64, double buffered, one barrier per chunk.  A wave owns 128
+// tokens x 64 experts of both matrices: 16 accumulator tiles.  It is alone on its SIMD, so nothing but its own
+// instruction order hides latency: every request is issued between two MFMA groups - an LDS fragment of the next
+// K-step; a 16-byte piece of chunk c+1 going from its register to the other LDS buffer, and the piece of chunk c+2
+// that takes its place; during the last four chunks half of the epilogue's noise values.  Tiles that share token
+// rows are given to one die: its L2 keeps the rows, and the gate matrices too.  Whole tiles only: T a multiple of 256, E of
+// 128, d of 64 and at least 256 (k_gate takes every other shape).
+constexpr int GB_TOK = 256, GB_EXP = 128;
+constexpr int GB_BUF = (GB_TOK + 2 * GB_EXP) * GLDP;       // elements of one LDS buffer: x rows, Wg rows, Wn rows
+constexpr int GB_LDS_BYTES = 2 * GB_BUF * 2;
+
+template <bool NOISY>
+__global__ __launch_bounds__(256, 1) void k_gate_big(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
+                                                     const bf16_t* __restrict__ Wn, const float* __restrict__ noise,
+                                                     float* __restrict__ logits, int T, int d, int E, int n_tok_tiles, int n_exp_tiles,
+                                                     int tok_tiles_per_die)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char gb_lds[];
+    const int die = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int tok_tile = die * tok_tiles_per_die + j / n_exp_tiles, exp_tile = j % n_exp_tiles;
+    if (j / n_exp_tiles >= tok_tiles_per_die || tok_tile >= n_tok_tiles) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int t0 = tok_tile * GB_TOK, e0 = exp_tile * GB_EXP;
+    const int part = tid & 7, srow = tid >> 3;          // staging: 32 rows x 8 pieces of 16 bytes per pass
+    constexpr int NP = NOISY ? 16 : 12;                 // pieces of a chunk per thread: 8 of x, 4 of Wg, 4 of Wn
+    constexpr int NF = NOISY ? 8 : 6;                   // fragments of a K-step: 4 token tiles, 2 (+2) expert tiles
+    const int q = lane & 31, hk = lane >> 5, th = wave & 1, eh = wave >> 1;   // 2 token halves x 2 expert halves
+    bf16_t* const lds = reinterpret_cast<bf16_t*>(gb_lds);
+
+    // piece i of a chunk: 16 bytes of row srow + 32 i of the x tile (i < 8), of the Wg tile (i < 12), of the Wn tile;
+    // 32-bit offsets from the tiles' corners, one register for all of them (a tile spans 256 d < 2^31 elements)
+    const bf16_t* const x_tile = x + size_t(t0) * d;
+    const bf16_t* const wg_tile = Wg + size_t(e0) * d;
+    const bf16_t* const wn_tile = NOISY ? Wn + size_t(e0) * d : nullptr;
+    // (byte offsets: a uniform base plus a 32-bit lane offset is an addressing mode of the loads and stores)
+    const unsigned row_bytes = unsigned(d) * 2u, lane_off = unsigned(srow) * row_bytes + unsigned(part * 16);
+    u32x4 stage[NP];                                    // a chunk on its way to LDS
+    auto fetch_piece = [&](int i, int kc) {
+        const char* src = reinterpret_cast<const char*>(i < 8 ? x_tile : i < 12 ? wg_tile : wn_tile);
+        const unsigned row32 = unsigned(i < 8 ? i : (i - 8) & 3) * 32u;
+        stage[i] = *reinterpret_cast<const u32x4*>(src + (lane_off + row32 * row_bytes + unsigned(kc * GKC * 2)));
+    };
+    auto store_piece = [&](int i, bf16_t* buf) {        // piece i covers rows srow + 32 i of the buffer's 512
+        *reinterpret_cast<u32x4*>(buf + (srow + i * 32) * GLDP + part * 8) = stage[i];
+    };
+    // element i of accumulator tile n = 4 b + a (expert column b, token tile a) belongs to expert e0 + eh*64 + b*32
+    // + q and token t0 + th*128 + a*32 + 4*hk + 8*(i/4) + i%4; its place in the tile of logits (and of noise values)
+    // is a 32-bit byte offset from the tile's corner
+    const unsigned uE = unsigned(E) * 4u;                 // bytes of a row of logits
+    const unsigned lane_at = unsigned(th * 128 + 4 * hk) * uE + unsigned(eh * 64 + q) * 4u;
+    auto at = [&](int n, int i) { return lane_at + unsigned((n & 3) * 32 + 8 * (i / 4) + (i % 4)) * uE + unsigned((n >> 2) * 128); };
+    const char* const noise_tile = reinterpret_cast<const char*>(noise + size_t(t0) * E + e0);
+    float nz[NOISY ? 8 : 1][16];                          // noise values, 16 per accumulator tile
+
+    f32x16 ag[4][2], an[NOISY ? 4 : 1][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { ag[a][b][i] = 0.f; if (NOISY) an[NOISY ? a : 0][b][i] = 0.f; }
+
+    // one chunk: 4 K-steps of 8 MFMA groups (a token tile x an expert tile, both matrices); `side(g)` issues what
+    // else has to be requested before group g, g = 0..31
+    auto chunk = [&](const bf16_t* buf, auto&& side) {
+        const bf16_t* Xs = buf;
+        const bf16_t* Ws = buf + GB_TOK * GLDP;          // rows 0..127 Wg, 128..255 Wn
+        auto read_frag = [&](int r, int ks) -> bf16x8 {
+            const bf16_t* row = r < 4   ? Xs + (th * 128 + r * 32 + q) * GLDP
+                                : r < 6 ? Ws + (eh * 64 + (r - 4) * 32 + q) * GLDP
+                                        : Ws + (GB_EXP + eh * 64 + (r - 6) * 32 + q) * GLDP;
+            return *reinterpret_cast<const bf16x8*>(row + ks * 16 + hk * 8);
+        };
+        bf16x8 fr[2][NF];
+#pragma unroll
+        for (int r = 0; r < NF; ++r) fr[0][r] = read_frag(r, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < GKC / 16; ++ks) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const int a = g >> 1, b = g & 1;
+                if (ks + 1 < GKC / 16 && g < NF) fr[(ks + 1) & 1][g] = read_frag(g, ks + 1);
+                side(ks * 8 + g);
+                __builtin_amdgcn_sched_barrier(0);
+                ag[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks & 1][a], fr[ks & 1][4 + b], ag[a][b], 0, 0, 0);
+                if (NOISY)
+                    an[NOISY ? a : 0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks & 1][a], fr[ks & 1][NOISY ? 6 + b : 0],
+                                                                                  an[NOISY ? a : 0][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    const int nchunk = d / GKC;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) fetch_piece(i, 0);
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        store_piece(i, lds);
+        fetch_piece(i, min(1, nchunk - 1));
+    }
+    __syncthreads();
+    // chunk kc multiplies out of buffer kc & 1 while chunk kc+1 moves from the registers to the other buffer (all
+    // waves left that buffer before the last barrier) and chunk kc+2 is requested into the registers; past the end
+    // the requests repeat the last chunk, which nobody reads.  The last four chunks also request the noise values
+    // of accumulator tiles 0..3, one tile each: every workgroup of the launch reaches its epilogue at about the
+    // same time, and what they all ask of HBM then is what bounds the epilogue.
+    auto steady = [&](int kc, auto&& also) {
+        bf16_t* other = lds + ((kc + 1) & 1) * GB_BUF;
+        const int k2 = min(kc + 2, nchunk - 1);
+        chunk(lds + (kc & 1) * GB_BUF, [&](int g) {
+            if ((g >> 1) < NP) {
+                if ((g & 1) == 0) store_piece(g >> 1, other);
+                else fetch_piece(g >> 1, k2);
+            }
+            also(g);
+        });
+        __syncthreads();
+    };
+    auto noise_of = [&](auto n) {                     // tile n's 16 values, in the even groups
+        return [&, n](int g) {
+            if (NOISY && (g & 1) == 0) nz[NOISY ? decltype(n)::value : 0][g >> 1] = *reinterpret_cast<const float*>(noise_tile + at(decltype(n)::value, g >> 1));
+        };
+    };
+    for (int kc = 0; kc + 4 < nchunk; ++kc) steady(kc, [](int) {});
+    steady(nchunk - 4, noise_of(std::integral_constant<int, 0>{}));
+    steady(nchunk - 3, noise_of(std::integral_constant<int, 1>{}));
+    steady(nchunk - 2, noise_of(std::integral_constant<int, 2>{}));
+    chunk(lds + ((nchunk - 1) & 1) * GB_BUF, noise_of(std::integral_constant<int, 3>{}));
+
+    // the noise values of tile n+4 are requested before tile n is worked on
+    char* const tile = reinterpret_cast<char*>(logits + size_t(t0) * E + e0);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        const int a = n & 3, b = n >> 2;
+        if (NOISY && n + 4 < 8) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) nz[NOISY ? n + 4 : 0][i] = *reinterpret_cast<const float*>(noise_tile + at(n + 4, i));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // a wave alone on its SIMD waits out every dependent instruction, so the softplus of 8 elements advances
+        // stage by stage
+#pragma unroll
+        for (int i0 = 0; i0 < 16; i0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = ag[a][b][i0 + i];
+            if (NOISY) {
+                float z[8], u[8], w[8], c[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) z[i] = an[NOISY ? a : 0][b][i0 + i];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) u[i] = __builtin_amdgcn_exp2f(-1.4426950408889634f * fabsf(z[i]));
+#pragma unroll
+                for (int i = 0; i < 8; ++i) w[i] = 1.f + u[i];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) c[i] = u[i] - (w[i] - 1.f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) w[i] = __builtin_amdgcn_logf(w[i]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) c[i] = __builtin_amdgcn_fmed3f(z[i], 0.f, INFINITY) + fmaf(0.6931471805599453f, w[i], c[i]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = fmaf(nz[NOISY ? n : 0][i0 + i], c[i], v[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *reinterpret_cast<float*>(tile + at(n, i0 + i)) = v[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -181,27 +370,49 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
     for (int j = lane; j < k; j += 64) w_t[j] = expf(w_t[j] - v0) / den;       // each lane revisits its own stores
 }
 
-// The same selection for k <= MAX_K with the row in registers: a bit per register marks what was taken, the k
-// rounds are unrolled and the selected logits stay in registers until the softmax (about a quarter faster than the
-// general kernel at k = 4, E = 1024).
+// The same selection for k <= MAX_K with the row in registers, as integer keys whose order is the logits' order
+// (-0 is read as +0, NaN as -infinity, like above).  A round finds the largest key of the wave (per lane, then
+// across lanes with data-parallel-primitive moves: inside rows of 16, then two row broadcasts to lane 63), and then
+// its owner: the registers are asked in turn which lanes hold that key; the registers go up through the expert ids
+// in groups of 256, so the first group with an answer holds the lowest expert id, the tie rule.  The owner replaces
+// the key by one below every key a logit can have.  All of this is the same for the whole wave, so the search is
+// scalar branches around one compare per register.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int wave_max_step(int v)
+{
+    return max(v, __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xF, false));   // lanes without a source see v
+}
+
 template <int NV>
 __global__ __launch_bounds__(256) void k_topk_small(const float* __restrict__ logits, int32_t* __restrict__ topk_idx,
                                                     float* __restrict__ topk_w, int T, int E, int k)
 {
-    static_assert(NV > 0 && NV <= 32, "one taken-bit per register");
+    static_assert(NV % 4 == 0, "registers in groups of four consecutive experts");
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const float* row = logits + size_t(t) * E;
-    float reg[NV];
+    constexpr int TAKEN = int(0x80000000);           // below the key of -infinity (0x807fffff)
+    // register 4 i + c holds expert 256 i + 4 lane + c: one 16-byte load per i where the row allows it
+    int key[NV];
+    const bool wide = (E & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;   // rows start 16-byte aligned, end on a group
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int e = lane + 64 * i;
-        const float v = e < E ? row[e] : 0.f;
-        reg[i] = v != v ? -INFINITY : v;
+    for (int i = 0; i < NV / 4; ++i) {
+        const int e0 = 256 * i + 4 * lane;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (wide) {
+            if (e0 < E) { const f32x4 q = *reinterpret_cast<const f32x4*>(row + e0); v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3]; }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) if (e0 + c < E) v[c] = row[e0 + c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float u = v[c] != v[c] ? -INFINITY : v[c] + 0.f;
+            const int bits = __builtin_bit_cast(int, u);
+            key[4 * i + c] = e0 + c < E ? bits ^ ((bits >> 31) & 0x7fffffff) : TAKEN;
+        }
     }
-    constexpr int NONE = 0x7fffffff;
-    uint32_t taken = 0;                      // bit i: this lane's i-th value was already selected
     int chosen[MAX_K];
     float val[MAX_K];
 #pragma unroll
@@ -209,23 +420,37 @@ __global__ __launch_bounds__(256) void k_topk_small(const float* __restrict__ lo
 #pragma unroll
     for (int j = 0; j < MAX_K; ++j) {
         if (j < k) {
-            float bv = -INFINITY;
-            int bi = NONE;
+            int m = key[0];
 #pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int e = lane + 64 * i;
-                const float v = reg[i];
-                if (e < E && !((taken >> i) & 1u) && (v > bv || bi == NONE)) { bv = v; bi = e; }
-            }
+            for (int i = 1; i < NV; ++i) m = max(m, key[i]);
+            m = wave_max_step<0xB1, 0xF>(m);       // quad_perm [1,0,3,2]
+            m = wave_max_step<0x4E, 0xF>(m);       // quad_perm [2,3,0,1]
+            m = wave_max_step<0x141, 0xF>(m);      // row_half_mirror
+            m = wave_max_step<0x140, 0xF>(m);      // row_mirror
+            m = wave_max_step<0x142, 0xA>(m);      // row_bcast15 into rows 1 and 3
+            m = wave_max_step<0x143, 0xC>(m);      // row_bcast31 into rows 2 and 3
+            m = __builtin_amdgcn_readlane(m, 63);
+            bool found = false;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oi = __shfl_xor(bi, off);
-                if (oi != NONE && (bi == NONE || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+            for (int i = 0; i < NV / 4; ++i) {
+                if (!found) {
+                    int best = 0x7fffffff;           // lowest expert id of this group of 256 that holds m
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const unsigned long long owners = __ballot(key[4 * i + c] == m);
+                        if (owners) best = min(best, 256 * i + 4 * (__ffsll(owners) - 1) + c);
+                    }
+                    if (best != 0x7fffffff) {
+                        chosen[j] = best;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (256 * i + 4 * lane + c == best) key[4 * i + c] = TAKEN;
+                        found = true;
+                    }
+                }
             }
-            chosen[j] = bi;
-            val[j] = bv;
-            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            const int bits = m ^ ((m >> 31) & 0x7fffffff);
+            val[j] = __builtin_bit_cast(float, bits);
         }
     }
     float den = 0.f;
@@ -693,8 +918,28 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     const bool timed = dynb::timing_on();
     if (timed) dynb::timing_begin(st);
     // m1 gate
-    hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 63) / 64), dim3(256), 0, st, xb,
-                       static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
+    if (T % GB_TOK == 0 && E % GB_EXP == 0 && d % GKC == 0 && d >= 4 * GKC && T > 0 && size_t(GB_TOK) * size_t(std::max(E, d)) < (size_t(1) << 30)) {
+        static std::atomic<uint64_t> attr_set{0};             // one bit per device: LDS beyond 64 KB
+        int dev = 0;
+        HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+        if (!(attr_set.load() >> (dev & 63) & 1)) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gate_big<true>), hipFuncAttributeMaxDynamicSharedMemorySize, GB_LDS_BYTES),
+                    "hipFuncSetAttribute(k_gate_big)");
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gate_big<false>), hipFuncAttributeMaxDynamicSharedMemorySize, GB_LDS_BYTES),
+                    "hipFuncSetAttribute(k_gate_big)");
+            attr_set.fetch_or(uint64_t(1) << (dev & 63));
+        }
+        const int ntt = (T + GB_TOK - 1) / GB_TOK, net = (E + GB_EXP - 1) / GB_EXP, per_die = (ntt + 7) / 8;
+        const dim3 grid(unsigned(8 * per_die * net));
+        if (noise)
+            hipLaunchKernelGGL((k_gate_big<true>), grid, dim3(256), GB_LDS_BYTES, st, xb, static_cast<const bf16_t*>(Wg),
+                               static_cast<const bf16_t*>(Wn), noise, logits, T, d, E, ntt, net, per_die);
+        else
+            hipLaunchKernelGGL((k_gate_big<false>), grid, dim3(256), GB_LDS_BYTES, st, xb, static_cast<const bf16_t*>(Wg),
+                               static_cast<const bf16_t*>(Wn), noise, logits, T, d, E, ntt, net, per_die);
+    } else
+        hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 63) / 64), dim3(256), 0, st, xb,
+                           static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
     if (timed) dynb::timing_mark(st, dynb::ST_GATE, 0);
     // m2 top-k + softmax
     const dim3 tk_grid((T + 3) / 4), tk_block(256);

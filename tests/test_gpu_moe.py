@@ -116,6 +116,29 @@ def test_noiseless_gate_and_ties(dyn, util, oracle):
     assert util.normwise(out, oracle.moe_experts(m.x, r.topk_idx, r.topk_w, W1, W2)) < OUT_TOL
 
 
+@pytest.mark.parametrize("T,d,h,E,k", [(256, 256, 32, 128, 2),      # one tile, the shortest K loop the wide kernel takes
+                                        (512, 320, 32, 256, 4),      # 2 x 2 tiles, an odd number of K-chunks
+                                        (768, 1024, 32, 384, 8),     # 3 x 3 tiles: dies without a token tile
+                                        (2304, 256, 32, 128, 1)])    # 9 token tiles: two for the first die
+@pytest.mark.parametrize("noisy", [True, False])
+def test_wide_gate_tiles(dyn, util, oracle, T, d, h, E, k, noisy):
+    """Whole 256-token x 128-expert tiles go to the wide gate kernel (every other shape in this file to the
+    64 x 64 one): every logit against the oracle, with and without the noise term, routing on the GPU's logits;
+    duplicated gate columns tie exactly and the lower id wins."""
+    m = moe.small(seed=T + E + d, T=T, d=d, h=h, E=E, k=k)
+    if not noisy:
+        m.Wg[:, 64:128] = m.Wg[:, :64]           # expert e and e+64: same tile, the other expert half of a workgroup
+    W1, W2 = stack(m)
+    out, aux = util.moe_run(dyn, m, W1, W2, noise=noisy)
+    ref_logits = oracle.moe_logits(m.x, m.Wg, m.Wn if noisy else None, m.noise if noisy else None)
+    assert util.normwise(aux["logits"], ref_logits) < LOGIT_TOL
+    assert np.abs(aux["logits"] - ref_logits).max() < 4 * LOGIT_TOL * np.abs(ref_logits).max()
+    if not noisy:
+        assert (aux["logits"][:, 64:128] == aux["logits"][:, :64]).all()
+    r = check_routing(oracle, m, aux)
+    assert util.normwise(out, oracle_experts(oracle, m, r, W1, W2)) < OUT_TOL
+
+
 def full_layer(dyn, util, m):
     """Runs a benchmark-size layer with per-expert generated weights; returns (out, aux, device inputs)."""
     import torch
