@@ -125,7 +125,7 @@ def main():
                 "copy_kind": "1 GiB read + 1 GiB written by a plain 16-byte copy kernel (dynb_probe_copy)",
                 "read_gbs": round(cal_src.numel() * 4 / read_ms / 1e6, 1),
                 "read_frac_of_published": round(cal_src.numel() * 4 / read_ms / 1e6 / PEAK_HBM_GBS, 4),
-                "read_kind": "1 GiB read, nothing written, 16-byte loads, 8 in flight per lane (dynb_probe_read)"}
+                "read_kind": "1 GiB read, nothing written, 16-byte loads, 8 in flight per lane, a contiguous share per workgroup (dynb_probe_read)"}
     del cal_src, cal_dst
 
     # ------------------------------------------------------------------ program-tree engine

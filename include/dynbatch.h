@@ -495,8 +495,9 @@ int dynb_probe_mfma_bf16(int32_t iters, int32_t workgroups, float* sink, void* s
  * Errors: DYNB_E_INVAL, DYNB_E_HIP.                                                             */
 int dynb_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
-/* Reads `bytes` of device memory with the same 16-byte accesses and stores nothing (`sink`: device, at least 4
- * bytes, practically never written): the bandwidth a kernel that only streams operands in can expect.
+/* Reads `bytes` of device memory with 16-byte loads, every workgroup a contiguous share of the buffer, and stores
+ * nothing (`sink`: device, at least 4 bytes, practically never written): the bandwidth a kernel that only streams
+ * operands in can expect at best.
  * Errors: DYNB_E_INVAL (NULL, size or pointer not a multiple of 16), DYNB_E_HIP.                          */
 int dynb_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 

@@ -53,19 +53,25 @@ __global__ __launch_bounds__(256) void k_probe_copy(const u32x4* __restrict__ sr
         dst[i] = src[i];
 }
 
+// Every workgroup reads a contiguous share of the buffer, 4 KB per step of its 256 lanes, eight steps in flight: of
+// the patterns tried (this one, lanes striding over the whole buffer with 4 to 16 loads in flight, grids of 512 to
+// 8192 workgroups, non-temporal loads, shares dealt so that a die reads one eighth) the fastest on this card, about
+// a fifth above the striding one.
 __global__ __launch_bounds__(256) void k_probe_read(const u32x4* __restrict__ src, uint32_t* __restrict__ sink, size_t n16)
 {
-    const size_t stride = size_t(gridDim.x) * blockDim.x;
-    size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t per = (n16 / gridDim.x) & ~size_t(2047);          // pieces per workgroup: whole steps of 8 x 256
+    const u32x4* p = src + size_t(blockIdx.x) * per + threadIdx.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
-    for (; i + 7 * stride < n16; i += 8 * stride) {                  // eight loads in flight per lane
+    for (size_t i = 0; i < per; i += 8 * 256) {
         u32x4 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+        for (int j = 0; j < 8; ++j) v[j] = p[i + j * 256];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc |= v[j];
     }
-    for (; i < n16; i += stride) acc |= src[i];
+    // what the shares left over, lanes striding
+    for (size_t i = per * gridDim.x + size_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += size_t(gridDim.x) * blockDim.x)
+        acc |= src[i];
     if ((acc.x & acc.y & acc.z & acc.w) == 0xdeadbeefu) sink[0] = acc.x;   // keeps the loads alive; practically never taken
 }
 
@@ -78,7 +84,7 @@ extern "C" int dynb_probe_read(const void* src, size_t bytes, void* sink, void* 
         return fail(DYNB_E_INVAL, "dynb_probe_read: size and pointer must be multiples of 16 bytes");
     if (bytes == 0) return DYNB_OK;
     const size_t n16 = bytes / 16;
-    const unsigned grid = unsigned(std::min<size_t>((n16 + 255) / 256, size_t(256) * 8));
+    const unsigned grid = unsigned(std::min<size_t>((n16 + 2047) / 2048, size_t(256) * 8));
     hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4*>(src), static_cast<uint32_t*>(sink), n16);
     const hipError_t e = hipGetLastError();

@@ -139,6 +139,20 @@ def test_wide_gate_tiles(dyn, util, oracle, T, d, h, E, k, noisy):
     assert util.normwise(out, oracle_experts(oracle, m, r, W1, W2)) < OUT_TOL
 
 
+@pytest.mark.parametrize("T,d,h,E,k,zipf", [(1536, 256, 512, 6, 2, 1.5),      # most groups beyond 256 rows, ragged rests
+                                             (2048, 128, 256, 3, 1, 0.0),      # near-equal groups, short K loops
+                                             (700, 256, 256, 2, 2, 0.0)])      # every token to both experts: 700 rows each
+def test_crowded_experts(dyn, util, oracle, T, d, h, E, k, zipf):
+    """Few experts with hundreds of rows each (groups of several full 64-row tiles that share weight tiles, and a
+    ragged last tile): every output row against the oracle."""
+    m = moe.small(seed=T + E + d, T=T, d=d, h=h, E=E, k=k, zipf_s=zipf)
+    W1, W2 = stack(m)
+    out, aux = util.moe_run(dyn, m, W1, W2)
+    r = check_routing(oracle, m, aux)
+    assert (r.counts >= 256).any() and (r.counts % 64 != 0).any()
+    assert util.normwise(out, oracle_experts(oracle, m, r, W1, W2)) < OUT_TOL
+
+
 def full_layer(dyn, util, m):
     """Runs a benchmark-size layer with per-expert generated weights; returns (out, aux, device inputs)."""
     import torch
