@@ -58,6 +58,8 @@ def check_routing(oracle, m, aux):
 @pytest.mark.parametrize("T,d,h,E,k,empty", [(300, 64, 96, 20, 3, 0.2), (257, 32, 32, 5, 5, 0.0), (1000, 128, 160, 70, 1, 0.1),
                                               (64, 96, 64, 300, 8, 0.5), (1, 32, 32, 2, 2, 0.0),
                                               (24, 32, 32, 2100, 3, 0.0),
+                                              (40, 32, 32, 1500, 6, 0.0),      # 32 register-held logits per lane, 16-byte loads
+                                              (33, 32, 32, 1027, 4, 0.0),      # the same with rows that are not 16-byte aligned
                                               (200, 64, 96, 64, 16, 0.0),      # k beyond the register-held uses
                                               (50, 32, 32, 12, 12, 0.0),       # k = E > 8: full softmax
                                               (90, 40, 72, 12, 3, 0.0),        # d, h multiples of 8 only
