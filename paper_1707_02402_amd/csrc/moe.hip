@@ -515,14 +515,17 @@ __global__ __launch_bounds__(256) void k_scan_blocks(int32_t* __restrict__ block
     if (lane == 0) counts[e] = carry;
 }
 
-// One wave: offsets = exclusive scan of counts; tile_start = exclusive scan of ceil(counts / TM).
-__global__ __launch_bounds__(64) void k_offsets(const int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                int32_t* __restrict__ tile_start, int E)
+// One workgroup of 16 waves: offsets = exclusive scan of counts; tile_start = exclusive scan of ceil(counts / TM).
+// 1024 experts per pass: a scan inside every wave, the waves' totals through LDS.
+constexpr int OFFS_THREADS = 1024;
+__global__ __launch_bounds__(OFFS_THREADS) void k_offsets(const int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                          int32_t* __restrict__ tile_start, int E)
 {
-    const int lane = threadIdx.x;
+    __shared__ int32_t wsum[OFFS_THREADS / 64], wtsum[OFFS_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int carry = 0, tcarry = 0;
-    for (int e0 = 0; e0 < E; e0 += 64) {
-        const int e = e0 + lane;
+    for (int e0 = 0; e0 < E; e0 += OFFS_THREADS) {
+        const int e = e0 + tid;
         const int c = e < E ? counts[e] : 0;
         const int tl = (c + TM - 1) / TM;
         int inc = c, tinc = tl;
@@ -532,11 +535,22 @@ __global__ __launch_bounds__(64) void k_offsets(const int32_t* __restrict__ coun
             const int to = __shfl_up(tinc, off);
             if (lane >= off) { inc += o; tinc += to; }
         }
-        if (e < E) { offsets[e] = carry + inc - c; tile_start[e] = tcarry + tinc - tl; }
-        carry += __shfl(inc, 63);
-        tcarry += __shfl(tinc, 63);
+        if (lane == 63) { wsum[wave] = inc; wtsum[wave] = tinc; }
+        __syncthreads();
+        int before = 0, tbefore = 0, all = 0, tall = 0;      // totals of the waves before this one, and of all
+#pragma unroll
+        for (int w = 0; w < OFFS_THREADS / 64; ++w) {
+            const int a = wsum[w], t = wtsum[w];
+            if (w < wave) { before += a; tbefore += t; }
+            all += a;
+            tall += t;
+        }
+        if (e < E) { offsets[e] = carry + before + inc - c; tile_start[e] = tcarry + tbefore + tinc - tl; }
+        carry += all;
+        tcarry += tall;
+        __syncthreads();                                     // the totals are overwritten by the next pass
     }
-    if (lane == 0) { offsets[E] = carry; tile_start[E] = tcarry; }
+    if (tid == 0) { offsets[E] = carry; tile_start[E] = tcarry; }
 }
 
 __global__ __launch_bounds__(SORT_BLOCK) void k_place(const int32_t* __restrict__ idx, const int32_t* __restrict__ lrank,
@@ -963,7 +977,7 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     hipLaunchKernelGGL(k_zero_i32, dim3(unsigned(std::min<size_t>((nbc + 255) / 256, 2048))), dim3(256), 0, st, blockcnt, nbc);
     hipLaunchKernelGGL(k_rank_blocks, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, A, L.nblk);
     hipLaunchKernelGGL(k_scan_blocks, dim3((E + 3) / 4), dim3(256), 0, st, blockcnt, counts, E, L.nblk);
-    hipLaunchKernelGGL(k_offsets, dim3(1), dim3(64), 0, st, counts, offsets, tile_start, E);
+    hipLaunchKernelGGL(k_offsets, dim3(1), dim3(OFFS_THREADS), 0, st, counts, offsets, tile_start, E);
     hipLaunchKernelGGL(k_place, dim3(L.nblk), dim3(SORT_BLOCK), 0, st, topk_idx, lrank, blockcnt, offsets, perm, inv, A, L.nblk);
     if (timed) dynb::timing_mark(st, dynb::ST_SORT, 0);
     // m4 permute: as a kernel of its own (MOE_SEPARATE_PERMUTE, and for the per-use loop), else inside the
