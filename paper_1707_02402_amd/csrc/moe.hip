@@ -396,21 +396,23 @@ __global__ __launch_bounds__(256) void k_topk_small(const float* __restrict__ lo
     // register 4 i + c holds expert 256 i + 4 lane + c: one 16-byte load per i where the row allows it
     int key[NV];
     const bool wide = (E & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;   // rows start 16-byte aligned, end on a group
+    const bool full = E == 64 * NV;                   // no register lies beyond the row
 #pragma unroll
     for (int i = 0; i < NV / 4; ++i) {
         const int e0 = 256 * i + 4 * lane;
         float v[4] = {0.f, 0.f, 0.f, 0.f};
         if (wide) {
-            if (e0 < E) { const f32x4 q = *reinterpret_cast<const f32x4*>(row + e0); v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3]; }
+            if (full || e0 < E) { const f32x4 q = *reinterpret_cast<const f32x4*>(row + e0); v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3]; }
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c) if (e0 + c < E) v[c] = row[e0 + c];
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const float u = v[c] != v[c] ? -INFINITY : v[c] + 0.f;
+            const float u = fmaxf(v[c], -INFINITY) + 0.f;            // the maximum drops a NaN, the sum turns -0 into +0
             const int bits = __builtin_bit_cast(int, u);
-            key[4 * i + c] = e0 + c < E ? bits ^ ((bits >> 31) & 0x7fffffff) : TAKEN;
+            const int ordered = bits ^ ((bits >> 31) & 0x7fffffff);
+            key[4 * i + c] = (full || e0 + c < E) ? ordered : TAKEN;
         }
     }
     int chosen[MAX_K];
@@ -453,14 +455,18 @@ __global__ __launch_bounds__(256) void k_topk_small(const float* __restrict__ lo
             val[j] = __builtin_bit_cast(float, bits);
         }
     }
-    float den = 0.f;
+    // softmax over the k kept logits with the hardware's exp2 (arguments <= 0, results in (0, 1], good to ~2e-6)
+    float den = 0.f, ex[MAX_K];
 #pragma unroll
-    for (int j = 0; j < MAX_K; ++j) if (j < k) den += expf(val[j] - val[0]);
+    for (int j = 0; j < MAX_K; ++j) {
+        ex[j] = j < k ? __expf(val[j] - val[0]) : 0.f;
+        den += ex[j];
+    }
 #pragma unroll
     for (int j = 0; j < MAX_K; ++j)
         if (j < k && lane == j) {
             topk_idx[size_t(t) * k + j] = chosen[j];
-            topk_w[size_t(t) * k + j] = expf(val[j] - val[0]) / den;
+            topk_w[size_t(t) * k + j] = ex[j] / den;
         }
 }
 
