@@ -130,6 +130,7 @@ def test_wide_gate_tiles(dyn, util, oracle, T, d, h, E, k, noisy):
     m = moe.small(seed=T + E + d, T=T, d=d, h=h, E=E, k=k)
     if not noisy:
         m.Wg[:, 64:128] = m.Wg[:, :64]           # expert e and e+64: same tile, the other expert half of a workgroup
+        m.x[3, :] = 0                            # a token whose logits all tie: experts 0 .. k-1, in that order
     W1, W2 = stack(m)
     out, aux = util.moe_run(dyn, m, W1, W2, noise=noisy)
     ref_logits = oracle.moe_logits(m.x, m.Wg, m.Wn if noisy else None, m.noise if noisy else None)
@@ -137,6 +138,7 @@ def test_wide_gate_tiles(dyn, util, oracle, T, d, h, E, k, noisy):
     assert np.abs(aux["logits"] - ref_logits).max() < 4 * LOGIT_TOL * np.abs(ref_logits).max()
     if not noisy:
         assert (aux["logits"][:, 64:128] == aux["logits"][:, :64]).all()
+        assert (aux["logits"][3] == 0).all() and (aux["topk_idx"][3] == np.arange(k)).all()
     r = check_routing(oracle, m, aux)
     assert util.normwise(out, oracle_experts(oracle, m, r, W1, W2)) < OUT_TOL
 
