@@ -137,15 +137,14 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
 }
 
 // The same product for wide gates: a workgroup owns a CU and a tile of 256 tokens x 128 experts, both gate matrices
-// at once.  A 64 x 64 tile takes in 24 KB per K-chunk for 8 MFMAs per wave (96 B per
-// MFMA clock), three times what a CU receives from L2; this tile takes in 64 KB for 64 MFMAs per wave (32 B per MFMA
-// clock).  Operands go through LDS in K-chunks of 64, double buffered, one barrier per chunk.  A wave owns 128
+// at once.  A 64 x 64 tile takes in 24 KB per K-chunk for 8 MFMAs per wave (96 B per MFMA clock), three times what
+// a CU receives from L2; this tile takes in 64 KB for 64 MFMAs per wave (32 B per MFMA clock).  Operands go through LDS in K-chunks of 64, double buffered, one barrier per chunk.  A wave owns 128
 // tokens x 64 experts of both matrices: 16 accumulator tiles.  It is alone on its SIMD, so nothing but its own
 // instruction order hides latency: every request is issued between two MFMA groups - an LDS fragment of the next
 // K-step; a 16-byte piece of chunk c+1 going from its register to the other LDS buffer, and the piece of chunk c+2
 // that takes its place; during the last four chunks half of the epilogue's noise values.  Tiles that share token
-// rows are given to one die: its L2 keeps the rows, and the gate matrices too.  Whole tiles only: T a multiple of 256, E of
-// 128, d of 64 and at least 256 (k_gate takes every other shape).
+// rows are given to one die: its L2 keeps the rows, and the gate matrices too.  Whole tiles only: T a multiple of
+// 256, E of 128, d of 64 and at least 256 (k_gate takes every other shape).
 constexpr int GB_TOK = 256, GB_EXP = 128;
 constexpr int GB_BUF = (GB_TOK + 2 * GB_EXP) * GLDP;       // elements of one LDS buffer: x rows, Wg rows, Wn rows
 constexpr int GB_LDS_BYTES = 2 * GB_BUF * 2;
@@ -190,7 +189,7 @@ __global__ __launch_bounds__(256, 1) void k_gate_big(const bf16_t* __restrict__ 
     const unsigned uE = unsigned(E) * 4u;                 // bytes of a row of logits
     const unsigned lane_at = unsigned(th * 128 + 4 * hk) * uE + unsigned(eh * 64 + q) * 4u;
     auto at = [&](int n, int i) { return lane_at + unsigned((n & 3) * 32 + 8 * (i / 4) + (i % 4)) * uE + unsigned((n >> 2) * 128); };
-    const char* const noise_tile = reinterpret_cast<const char*>(noise + size_t(t0) * E + e0);
+    const char* const noise_tile = NOISY ? reinterpret_cast<const char*>(noise + size_t(t0) * E + e0) : nullptr;
     float nz[NOISY ? 8 : 1][16];                          // noise values, 16 per accumulator tile
 
     f32x16 ag[4][2], an[NOISY ? 4 : 1][2];
