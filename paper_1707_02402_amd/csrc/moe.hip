@@ -379,7 +379,8 @@ __global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int wave_max_step(int v)
 {
-    return max(v, __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xF, false));   // lanes without a source see v
+    // lanes without a source see the smallest integer, the identity of the maximum (which lets the move fold into it)
+    return max(v, __builtin_amdgcn_update_dpp(int(0x80000000), v, CTRL, ROW_MASK, 0xF, false));
 }
 
 template <int NV>
