@@ -143,8 +143,8 @@ __global__ __launch_bounds__(256) void k_gate(const bf16_t* __restrict__ x, cons
 // instruction order hides latency: every request is issued between two MFMA groups - an LDS fragment of the next
 // K-step; a 16-byte piece of chunk c+1 going from its register to the other LDS buffer, and the piece of chunk c+2
 // that takes its place; during the last four chunks half of the epilogue's noise values.  Tiles that share token
-// rows are given to one die: its L2 keeps the rows, and the gate matrices too.  Whole tiles only: T a multiple of
-// 256, E of 128, d of 64 and at least 256 (k_gate takes every other shape).
+// rows are given to one die: its L2 keeps the rows, and the gate matrices too.  Whole tiles only: E a multiple of
+// 128, d of 64 and at least 256; the tokens behind the last whole tile of 256, and every other shape, go to k_gate.
 constexpr int GB_TOK = 256, GB_EXP = 128;
 constexpr int GB_BUF = (GB_TOK + 2 * GB_EXP) * GLDP;       // elements of one LDS buffer: x rows, Wg rows, Wn rows
 constexpr int GB_LDS_BYTES = 2 * GB_BUF * 2;
@@ -938,7 +938,11 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
     const bool timed = dynb::timing_on();
     if (timed) dynb::timing_begin(st);
     // m1 gate
-    if (T % GB_TOK == 0 && E % GB_EXP == 0 && d % GKC == 0 && d >= 4 * GKC && T > 0 && size_t(GB_TOK) * size_t(std::max(E, d)) < (size_t(1) << 30)) {
+    // whole tiles of 256 tokens go to k_gate_big where the expert and model widths allow it, the tokens behind the
+    // last whole tile (and every other shape) to k_gate
+    const int T_big = (E % GB_EXP == 0 && d % GKC == 0 && d >= 4 * GKC && size_t(GB_TOK) * size_t(std::max(E, d)) < (size_t(1) << 30))
+                          ? T / GB_TOK * GB_TOK : 0;
+    if (T_big > 0) {
         static std::atomic<uint64_t> attr_set{0};             // one bit per device: LDS beyond 64 KB
         int dev = 0;
         HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
@@ -949,17 +953,19 @@ static int moe_run(const moe_shape* s, const void* x, const void* Wg, const void
                     "hipFuncSetAttribute(k_gate_big)");
             attr_set.fetch_or(uint64_t(1) << (dev & 63));
         }
-        const int ntt = (T + GB_TOK - 1) / GB_TOK, net = (E + GB_EXP - 1) / GB_EXP, per_die = (ntt + 7) / 8;
+        const int ntt = T_big / GB_TOK, net = E / GB_EXP, per_die = (ntt + 7) / 8;
         const dim3 grid(unsigned(8 * per_die * net));
         if (noise)
             hipLaunchKernelGGL((k_gate_big<true>), grid, dim3(256), GB_LDS_BYTES, st, xb, static_cast<const bf16_t*>(Wg),
-                               static_cast<const bf16_t*>(Wn), noise, logits, T, d, E, ntt, net, per_die);
+                               static_cast<const bf16_t*>(Wn), noise, logits, T_big, d, E, ntt, net, per_die);
         else
             hipLaunchKernelGGL((k_gate_big<false>), grid, dim3(256), GB_LDS_BYTES, st, xb, static_cast<const bf16_t*>(Wg),
-                               static_cast<const bf16_t*>(Wn), noise, logits, T, d, E, ntt, net, per_die);
-    } else
-        hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T + 63) / 64), dim3(256), 0, st, xb,
-                           static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise, logits, T, d, E);
+                               static_cast<const bf16_t*>(Wn), noise, logits, T_big, d, E, ntt, net, per_die);
+    }
+    if (T > T_big)
+        hipLaunchKernelGGL(k_gate, dim3((E + 63) / 64, (T - T_big + 63) / 64), dim3(256), 0, st, xb + size_t(T_big) * d,
+                           static_cast<const bf16_t*>(Wg), static_cast<const bf16_t*>(Wn), noise ? noise + size_t(T_big) * E : nullptr,
+                           logits + size_t(T_big) * E, T - T_big, d, E);
     if (timed) dynb::timing_mark(st, dynb::ST_GATE, 0);
     // m2 top-k + softmax
     const dim3 tk_grid((T + 3) / 4), tk_block(256);

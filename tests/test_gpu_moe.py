@@ -121,11 +121,12 @@ def test_noiseless_gate_and_ties(dyn, util, oracle):
 @pytest.mark.parametrize("T,d,h,E,k", [(256, 256, 32, 128, 2),      # one tile, the shortest K loop the wide kernel takes
                                         (512, 320, 32, 256, 4),      # 2 x 2 tiles, an odd number of K-chunks
                                         (768, 1024, 32, 384, 8),     # 3 x 3 tiles: dies without a token tile
-                                        (2304, 256, 32, 128, 1)])    # 9 token tiles: two for the first die
+                                        (2304, 256, 32, 128, 1),     # 9 token tiles: two for the first die
+                                        (700, 256, 32, 128, 2)])     # two whole token tiles, 188 tokens for the 64 x 64 tiles
 @pytest.mark.parametrize("noisy", [True, False])
 def test_wide_gate_tiles(dyn, util, oracle, T, d, h, E, k, noisy):
-    """Whole 256-token x 128-expert tiles go to the wide gate kernel (every other shape in this file to the
-    64 x 64 one): every logit against the oracle, with and without the noise term, routing on the GPU's logits;
+    """Whole 256-token x 128-expert tiles go to the wide gate kernel (tokens behind the last whole tile, and every
+    other shape in this file, to the 64 x 64 one): every logit against the oracle, with and without the noise term, routing on the GPU's logits;
     duplicated gate columns tie exactly and the lower id wins."""
     m = moe.small(seed=T + E + d, T=T, d=d, h=h, E=E, k=k)
     if not noisy:
