@@ -475,6 +475,15 @@ def main():
                              "first expert layer gathers the token rows itself and this kernel does not run"))
         moe_roof.append(roof("k_combine", by_comb, stage_ms["combine"]))
         moe_roof.append(roof("k_grouped_gemm (both expert layers)", by_ffn, ffn_ms, mfma_tflops=round(fl_ffn / ffn_ms / 1e9, 1)))
+        if "gate" in stage_ms and "topk" in stage_ms:
+            fl_gate = 4.0 * m.T * m.d * m.E                       # both gate matrices
+            moe_roof.append(dict(kernel="k_gate_big / k_gate (gate stage)", bound="mfma",
+                                 achieved=round(fl_gate / stage_ms["gate"] / 1e9, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                                 frac=round(fl_gate / stage_ms["gate"] / 1e9 / PEAK_BF16_TFLOPS, 4), traffic=None,
+                                 note="also reads x and the noise values and writes the logits: %.0f MB" %
+                                      ((m.T * m.d * 2 + 2 * m.E * m.d * 2 + 2 * m.T * m.E * 4) / 1e6)))
+            moe_roof.append(roof("k_topk_small / k_topk (top-k stage)", m.T * m.E * 4 + m.T * m.k * 8, stage_ms["topk"]))
+            moe_res["gate_plus_topk_ms"] = round(stage_ms["gate"] + stage_ms["topk"], 4)
 
     # ------------------------------------------------------------------ CPU oracle baseline (bounded samples)
     cpu = None
@@ -539,6 +548,7 @@ def main():
             moe_traffic = {k_: round(v["fetch_bytes"] + v["write_bytes"]) for k_, v in tj.get("moe", {}).items()}
     for r_ in moe_roof:
         key = r_["kernel"].split(" ")[0]
+        key = "k_gate" if key.startswith("k_gate") else "k_topk" if key.startswith("k_topk") else key
         if key == "k_grouped_gemm":
             parts = [v for k_, v in moe_traffic.items() if k_.startswith("k_grouped_gemm")]
             if parts:
